@@ -1,0 +1,18 @@
+"""Seeded synthetic inputs for the Talon hot path.
+
+This package only makes inputs (random logits rows, Q/K/V tensors) and names the
+workload shapes.  It holds none of the method's arithmetic: no softmax, no
+ranking, no gating, no attention.  Both the CPU oracle's tests and the GPU
+path's tests draw their inputs from here so that the two sides see identical
+bytes.
+"""
+from .configs import CONFIGS, WorkloadConfig, get_config  # noqa: F401
+from .generators import (  # noqa: F401
+    attention_inputs,
+    bf16_bits_to_f64,
+    f32_to_bf16_bits,
+    logits_pool,
+    logits_row,
+    storage_to_f64,
+    zipf_row,
+)
