@@ -1,0 +1,197 @@
+/*
+ * talon.h - C ABI of the MI355X (gfx950) hot path of one Talon speculative-decoding step:
+ * budget-driven adaptive draft-tree expansion and tree-attention verification
+ * (arXiv 2601.07353, Sec. 5 and App. A/B).
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless it is marked "host".  The caller owns every
+ *     buffer; the library allocates nothing and keeps no state between calls.
+ *   - Calls only enqueue work on `stream` (a hipStream_t passed as void*; NULL = the null
+ *     stream) and return at once.  Nothing synchronises with the host.
+ *   - Every call returns TALON_OK or a negative TALON_ERR_* code; all argument checks run on
+ *     the host before anything is launched, so a failed call has enqueued nothing.
+ *     talon_last_error_string() gives the reason (thread-local, host pointer).
+ *   - Problems only the device can see (a NaN logit, a row with no finite maximum) set
+ *     TALON_STATUS_BAD_ROW in status[b] and stop that sequence; they are not host errors.
+ *   - Device pointers must be 16-byte aligned.
+ *
+ * Notation (paper): B sequences, V vocabulary, K top-K width, N node budget (root counted,
+ * Alg. 2 starts from T = {x_t}), mu gate threshold, P_d frontier of layer d, S_d candidate
+ * pool, p(u) path confidence (Eq. 2).
+ */
+#ifndef TALON_H_
+#define TALON_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TALON_OK 0
+#define TALON_ERR_INVALID_ARG (-1)
+#define TALON_ERR_UNSUPPORTED (-2)
+#define TALON_ERR_WORKSPACE (-3)
+#define TALON_ERR_RUNTIME (-4)
+
+#define TALON_DTYPE_F32 0
+#define TALON_DTYPE_BF16 1
+
+/* limits */
+#define TALON_K_MAX 16     /* per-row candidate cap k                           */
+#define TALON_N_MAX 256    /* node budget N (root included)                     */
+#define TALON_B_MAX 1024   /* sequences per call                                */
+
+/* status[b] bits */
+#define TALON_STATUS_DONE_BUDGET 1u /* |T| reached N (Alg. 2 loop condition false)    */
+#define TALON_STATUS_DONE_DEPTH 2u  /* max_depth layers built before the budget ran out */
+#define TALON_STATUS_BAD_ROW 4u     /* NaN / +inf logit or a row with no finite maximum */
+
+/* logits row addressing for talon_expand_layer */
+#define TALON_ROWS_BY_NODE 0     /* row of node i of sequence b = i                        */
+#define TALON_ROWS_BY_FRONTIER 1 /* row = i - frontier_begin[b] (dense draft-forward batch) */
+
+/*
+ * Token tree T of Alg. 2 in structure-of-arrays form, one slab of N_pad entries per
+ * sequence (N_pad = N rounded up to a multiple of 64).  Node 0 is the root x_t.  Node ids
+ * are layer-major; inside a layer they are ordered (parent id ascending, in-row rank
+ * ascending), so the frontier P_d is always the contiguous id range
+ * [frontier_begin, frontier_begin + frontier_count).
+ */
+typedef struct talon_tree_state {
+  int32_t B, N, N_pad;
+  int32_t* token;          /* [B][N_pad] token id of the node                            */
+  int32_t* parent;         /* [B][N_pad] parent node id; root: -1                         */
+  int32_t* depth;          /* [B][N_pad] root: 0; child = parent + 1                      */
+  float* prob;             /* [B][N_pad] edge probability P(token | path); root: 1        */
+  double* logp;            /* [B][N_pad] log path confidence log p(v) (Eq. 2); root: 0    */
+  int32_t* n_nodes;        /* [B] |T|                                                     */
+  int32_t* frontier_begin; /* [B] first node id of the last layer built                   */
+  int32_t* frontier_count; /* [B] size of that layer                                      */
+  int32_t* depth_cur;      /* [B] number of layers built (d of Alg. 2)                    */
+  uint32_t* status;        /* [B] TALON_STATUS_* bits                                     */
+} talon_tree_state;
+
+/* Reason for the last non-OK return on this thread (host string, never NULL). */
+const char* talon_last_error_string(void);
+
+/*
+ * Alg. 2 line 1: T = {x_t}, P_0 = {x_t}, p(x_t) = 1, d = 0 for every sequence.
+ * root_token [B] (device).  Entries of the per-node arrays beyond node 0 are not touched.
+ */
+int talon_tree_init(const talon_tree_state* st, const int32_t* root_token, void* stream);
+
+/*
+ * Scratch for talon_expand_layer.  Size it once for the largest call; before the first
+ * use (and never again) clear it with talon_expand_workspace_init.
+ */
+size_t talon_expand_workspace_bytes(int32_t B, int32_t N_pad, int32_t vocab, int32_t k, int dtype);
+int talon_expand_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Candidate pool S_d of one layer (Eq. 3; Alg. 2 "gather" loop), restricted to the k best
+ * tokens of every parent.  For every frontier node v of every unfinished sequence: one
+ * pass over its logits row gives the softmax statistics (P(.|x<=v) is the softmax of the
+ * row) and the k largest logits ordered (logit descending, token id ascending).
+ *
+ *   logits      row-major rows of `vocab` elements (f32 or bf16), row_stride elements
+ *               between rows of a sequence, seq_stride elements between sequences.
+ *               Each row is read exactly once.  -inf entries are allowed (probability 0).
+ *   row_mode    which row node i reads (TALON_ROWS_BY_NODE / _BY_FRONTIER).
+ *   outputs, all indexed by [b][node id][rank], only rows of frontier nodes are written:
+ *     cand_token     [B][N_pad][k] int32   token ids; -1 where vocab < k
+ *     cand_logit     [B][N_pad][k] float   their logits (exact input values)
+ *     cand_prob      [B][N_pad][k] float   P(w | x<=v) = exp(logit - lse)
+ *     cand_edge_logp [B][N_pad][k] double  logit - lse (log of the above, unrounded)
+ *     row_max        [B][N_pad]    float   max logit of the row
+ *     row_lse        [B][N_pad]    double  log-sum-exp of the row
+ *   A row whose lse is not finite sets TALON_STATUS_BAD_ROW for its sequence.
+ *   Errors: INVALID_ARG (null/unaligned pointer, k not in [1, TALON_K_MAX], vocab < 1,
+ *   strides too small or not a multiple of 16 bytes), UNSUPPORTED (dtype, vocab beyond
+ *   what one merge supports), WORKSPACE (too small).
+ */
+int talon_expand_layer(const void* logits, int dtype, int64_t row_stride, int64_t seq_stride,
+                       int row_mode, const talon_tree_state* st, int32_t vocab, int32_t k,
+                       int32_t* cand_token, float* cand_logit, float* cand_prob,
+                       double* cand_edge_logp, float* row_max, double* row_lse,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Hybrid allocation of the remaining budget (Sec. 5.2; Alg. 2 "Hybrid Expansion Strategy"
+ * and "Budget Check"), one layer, every unfinished sequence:
+ *   score(u) = logp[v] + cand_edge_logp[v][rank]                 (log of Eq. 2 / Sec. 5.2.1)
+ *   layer < init_layers : P_{d+1} = Top-K_init of the pool        (Eq. 5)
+ *   otherwise           : m_d = max score;  keep score >= log(mu) + m_d   (Eq. 4)
+ *   if more than R = N - |T| remain, keep the R best               (budget check)
+ * Ties: (score descending, parent id ascending, rank ascending).  The kept candidates are
+ * appended to the tree in (parent, rank) order; n_nodes, frontier_*, depth_cur and status
+ * are advanced.  A sequence stops with DONE_BUDGET when |T| = N, or with DONE_DEPTH when
+ * depth_cur reaches max_depth first.
+ *   Errors: INVALID_ARG (mu outside (0,1], K_init < 1, init_layers < 0, max_depth < 1,
+ *   k outside [1, TALON_K_MAX], N > TALON_N_MAX, null pointers).
+ */
+int talon_select_budget(const talon_tree_state* st, int32_t k, const int32_t* cand_token,
+                        const float* cand_prob, const double* cand_edge_logp, float mu,
+                        int32_t K_init, int32_t init_layers, int32_t max_depth, void* stream);
+
+/*
+ * The whole while-loop of Alg. 2 enqueued in one call: max_depth times
+ * { talon_expand_layer ; talon_select_budget }.  Finished sequences cost nothing in the
+ * later iterations.  Arguments as in the two calls above.
+ */
+int talon_expand_tree(const void* logits, int dtype, int64_t row_stride, int64_t seq_stride,
+                      int row_mode, const talon_tree_state* st, int32_t vocab, int32_t k,
+                      float mu, int32_t K_init, int32_t init_layers, int32_t max_depth,
+                      int32_t* cand_token, float* cand_logit, float* cand_prob,
+                      double* cand_edge_logp, float* row_max, double* row_lse,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Tree attention mask (Fig. 5(b); App. B): bit j of row i is set iff node j is node i or
+ * one of its ancestors, the root included.
+ *   mask [B][N_pad][N_pad/64] uint64, bit j of row i = word j/64, bit j%64.
+ *   Rows of node ids >= n_nodes[b] and all padding bits are written as zero.
+ */
+int talon_build_tree_mask(const talon_tree_state* st, uint64_t* mask, void* stream);
+
+/*
+ * Scratch for talon_tree_attention (split-KV partial results).  max_prefix_len is the
+ * largest prefix length any call will pass.
+ */
+size_t talon_tree_attention_workspace_bytes(int32_t B, int32_t N_pad, int32_t Hq, int32_t Hkv,
+                                            int32_t Dh, int32_t max_prefix_len);
+
+/*
+ * One attention layer of the verification forward (App. B): tree node i of sequence b,
+ * query head h, attends to the prefix keys 0..prefix_len[b]-1 and to the tree keys j whose
+ * mask bit (i, j) is set; KV head = h / (Hq/Hkv).
+ *   out[b][i][h][:] = sum_j softmax_j(scale * q[b][i][h] . k_j) v_j
+ *
+ *   q, k_tree, v_tree  bf16 [B][N_pad][Hq|Hkv][Dh], dense
+ *   k_prefix, v_prefix bf16, element (b, t, g, :) at b*kv_stride_b + t*kv_stride_t +
+ *                      g*kv_stride_h (strides in elements; the Dh run is contiguous)
+ *   mask               as written by talon_build_tree_mask
+ *   n_nodes [B], prefix_len [B] int32 (device); prefix_len[b] <= max_prefix_len (host bound
+ *                      used to size the launch)
+ *   scale              0 means 1/sqrt(Dh)
+ *   out                bf16 [B][N_pad][Hq][Dh]; rows of node ids >= n_nodes[b] are untouched
+ *   out_lse            optional (NULL to skip) float [B][N_pad][Hq]: natural-log softmax
+ *                      denominator of the scaled scores
+ *   Arithmetic: bf16 MFMA with fp32 accumulation, fp32 online softmax, probabilities
+ *   rounded to bf16 before the P.V product, output rounded to bf16.
+ *   Errors: INVALID_ARG, UNSUPPORTED (Dh != 64 and != 128, Hq % Hkv != 0, Hq/Hkv > 16),
+ *   WORKSPACE.
+ */
+int talon_tree_attention(const void* q, const void* k_prefix, const void* v_prefix,
+                         const void* k_tree, const void* v_tree, const uint64_t* mask,
+                         const int32_t* n_nodes, const int32_t* prefix_len, int32_t B,
+                         int32_t N_pad, int32_t Hq, int32_t Hkv, int32_t Dh,
+                         int32_t max_prefix_len, int64_t kv_stride_b, int64_t kv_stride_t,
+                         int64_t kv_stride_h, float scale, void* out, float* out_lse,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TALON_H_ */

@@ -1,0 +1,228 @@
+"""ctypes binding of libtalon.so: same names as the C ABI, argument marshalling only.
+
+Tensors are torch CUDA tensors used purely as device buffers; every step of the path runs
+in the library's HIP kernels.  There is no CPU fallback: if the library is missing, or a
+call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, Structure, c_char_p, c_double, c_float, c_int, c_int32, c_int64, c_size_t, c_void_p
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "lib", "libtalon.so")
+
+TALON_OK = 0
+TALON_ERR_INVALID_ARG = -1
+TALON_ERR_UNSUPPORTED = -2
+TALON_ERR_WORKSPACE = -3
+TALON_ERR_RUNTIME = -4
+TALON_DTYPE_F32 = 0
+TALON_DTYPE_BF16 = 1
+TALON_K_MAX = 16
+TALON_N_MAX = 256
+TALON_B_MAX = 1024
+TALON_STATUS_DONE_BUDGET = 1
+TALON_STATUS_DONE_DEPTH = 2
+TALON_STATUS_BAD_ROW = 4
+TALON_ROWS_BY_NODE = 0
+TALON_ROWS_BY_FRONTIER = 1
+
+EXPORTS = [
+    "talon_last_error_string", "talon_tree_init", "talon_expand_workspace_bytes",
+    "talon_expand_workspace_init", "talon_expand_layer", "talon_select_budget", "talon_expand_tree",
+    "talon_build_tree_mask", "talon_tree_attention_workspace_bytes", "talon_tree_attention",
+]
+
+
+class TalonError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__("talon error %d: %s" % (code, message))
+        self.code = code
+
+
+class _CTreeState(Structure):
+    _fields_ = [("B", c_int32), ("N", c_int32), ("N_pad", c_int32),
+                ("token", c_void_p), ("parent", c_void_p), ("depth", c_void_p),
+                ("prob", c_void_p), ("logp", c_void_p), ("n_nodes", c_void_p),
+                ("frontier_begin", c_void_p), ("frontier_count", c_void_p),
+                ("depth_cur", c_void_p), ("status", c_void_p)]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libtalon.so (built in-tree by paper_2601_07353_amd.build); never falls back."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libtalon.so is not built (%s): run `python -m paper_2601_07353_amd.build` "
+                           "or __graft_entry__.build()" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    P = c_void_p
+    lib.talon_last_error_string.restype = c_char_p
+    lib.talon_last_error_string.argtypes = []
+    lib.talon_tree_init.argtypes = [POINTER(_CTreeState), P, P]
+    lib.talon_expand_workspace_bytes.restype = c_size_t
+    lib.talon_expand_workspace_bytes.argtypes = [c_int32, c_int32, c_int32, c_int32, c_int]
+    lib.talon_expand_workspace_init.argtypes = [P, c_size_t, P]
+    lib.talon_expand_layer.argtypes = [P, c_int, c_int64, c_int64, c_int, POINTER(_CTreeState), c_int32, c_int32,
+                                       P, P, P, P, P, P, P, c_size_t, P]
+    lib.talon_select_budget.argtypes = [POINTER(_CTreeState), c_int32, P, P, P, c_float, c_int32, c_int32, c_int32, P]
+    lib.talon_expand_tree.argtypes = [P, c_int, c_int64, c_int64, c_int, POINTER(_CTreeState), c_int32, c_int32,
+                                      c_float, c_int32, c_int32, c_int32, P, P, P, P, P, P, P, c_size_t, P]
+    lib.talon_build_tree_mask.argtypes = [POINTER(_CTreeState), P, P]
+    lib.talon_tree_attention_workspace_bytes.restype = c_size_t
+    lib.talon_tree_attention_workspace_bytes.argtypes = [c_int32] * 6
+    lib.talon_tree_attention.argtypes = [P, P, P, P, P, P, P, P, c_int32, c_int32, c_int32, c_int32, c_int32, c_int32,
+                                         c_int64, c_int64, c_int64, c_float, P, P, P, c_size_t, P]
+    for name in EXPORTS:
+        fn = getattr(lib, name)
+        if fn.restype is c_int:
+            fn.restype = c_int
+    _lib = lib
+    return lib
+
+
+def _check(rc: int):
+    if rc != TALON_OK:
+        raise TalonError(rc, load_library().talon_last_error_string().decode())
+
+
+def _ptr(t):
+    return None if t is None else c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+class TreeState:
+    """Device buffers of the token tree T (structure of arrays) plus the C struct that names them."""
+
+    def __init__(self, B: int, N: int, device="cuda"):
+        self.B, self.N = B, N
+        self.N_pad = (N + 63) // 64 * 64
+        i32 = dict(dtype=torch.int32, device=device)
+        self.token = torch.zeros(B, self.N_pad, **i32)
+        self.parent = torch.full((B, self.N_pad), -1, **i32)
+        self.depth = torch.zeros(B, self.N_pad, **i32)
+        self.prob = torch.zeros(B, self.N_pad, dtype=torch.float32, device=device)
+        self.logp = torch.zeros(B, self.N_pad, dtype=torch.float64, device=device)
+        self.n_nodes = torch.zeros(B, **i32)
+        self.frontier_begin = torch.zeros(B, **i32)
+        self.frontier_count = torch.zeros(B, **i32)
+        self.depth_cur = torch.zeros(B, **i32)
+        self.status = torch.zeros(B, **i32)
+        self.c = _CTreeState(B, N, self.N_pad, *[t.data_ptr() for t in (
+            self.token, self.parent, self.depth, self.prob, self.logp, self.n_nodes,
+            self.frontier_begin, self.frontier_count, self.depth_cur, self.status)])
+
+
+class Candidates:
+    """Device buffers for the per-row outputs of talon_expand_layer."""
+
+    def __init__(self, B: int, N_pad: int, k: int, device="cuda"):
+        self.k = k
+        self.token = torch.full((B, N_pad, k), -1, dtype=torch.int32, device=device)
+        self.logit = torch.zeros(B, N_pad, k, dtype=torch.float32, device=device)
+        self.prob = torch.zeros(B, N_pad, k, dtype=torch.float32, device=device)
+        self.edge_logp = torch.zeros(B, N_pad, k, dtype=torch.float64, device=device)
+        self.row_max = torch.zeros(B, N_pad, dtype=torch.float32, device=device)
+        self.row_lse = torch.zeros(B, N_pad, dtype=torch.float64, device=device)
+
+
+def _logits_meta(logits: torch.Tensor):
+    if logits.dtype == torch.float32:
+        dt = TALON_DTYPE_F32
+    elif logits.dtype == torch.bfloat16:
+        dt = TALON_DTYPE_BF16
+    else:
+        raise TalonError(TALON_ERR_UNSUPPORTED, "logits dtype %s" % logits.dtype)
+    if logits.dim() != 3 or logits.stride(2) != 1:
+        raise TalonError(TALON_ERR_INVALID_ARG, "logits must be [B][rows][V] with contiguous rows")
+    return dt, logits.stride(1), logits.stride(0), logits.shape[2]
+
+
+def talon_tree_init(st: TreeState, root_token: torch.Tensor, stream=None):
+    _check(load_library().talon_tree_init(ctypes.byref(st.c), _ptr(root_token), _stream(stream)))
+
+
+def talon_expand_workspace_bytes(B, N_pad, vocab, k, dtype) -> int:
+    return load_library().talon_expand_workspace_bytes(B, N_pad, vocab, k, dtype)
+
+
+def talon_expand_workspace_init(workspace: torch.Tensor, stream=None):
+    _check(load_library().talon_expand_workspace_init(_ptr(workspace), workspace.numel() * workspace.element_size(),
+                                                      _stream(stream)))
+
+
+def make_expand_workspace(B, N_pad, vocab, k, dtype, device="cuda") -> torch.Tensor:
+    nbytes = talon_expand_workspace_bytes(B, N_pad, vocab, k, dtype)
+    if nbytes == 0:
+        raise TalonError(TALON_ERR_UNSUPPORTED, load_library().talon_last_error_string().decode())
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    talon_expand_workspace_init(ws)
+    return ws
+
+
+def talon_expand_layer(logits, st: TreeState, k, cand: Candidates, workspace, row_mode=TALON_ROWS_BY_NODE,
+                       vocab=None, stream=None):
+    dt, row_stride, seq_stride, V = _logits_meta(logits)
+    _check(load_library().talon_expand_layer(
+        _ptr(logits), dt, row_stride, seq_stride, row_mode, ctypes.byref(st.c), V if vocab is None else vocab, k,
+        _ptr(cand.token), _ptr(cand.logit), _ptr(cand.prob), _ptr(cand.edge_logp), _ptr(cand.row_max),
+        _ptr(cand.row_lse), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def talon_select_budget(st: TreeState, k, cand: Candidates, mu, K_init, init_layers, max_depth, stream=None):
+    _check(load_library().talon_select_budget(
+        ctypes.byref(st.c), k, _ptr(cand.token), _ptr(cand.prob), _ptr(cand.edge_logp), c_float(mu), K_init,
+        init_layers, max_depth, _stream(stream)))
+
+
+def talon_expand_tree(logits, st: TreeState, k, mu, K_init, init_layers, max_depth, cand: Candidates, workspace,
+                      row_mode=TALON_ROWS_BY_NODE, vocab=None, stream=None):
+    dt, row_stride, seq_stride, V = _logits_meta(logits)
+    _check(load_library().talon_expand_tree(
+        _ptr(logits), dt, row_stride, seq_stride, row_mode, ctypes.byref(st.c), V if vocab is None else vocab, k,
+        c_float(mu), K_init, init_layers, max_depth, _ptr(cand.token), _ptr(cand.logit), _ptr(cand.prob),
+        _ptr(cand.edge_logp), _ptr(cand.row_max), _ptr(cand.row_lse), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def talon_build_tree_mask(st: TreeState, mask: torch.Tensor, stream=None):
+    _check(load_library().talon_build_tree_mask(ctypes.byref(st.c), _ptr(mask), _stream(stream)))
+
+
+def talon_tree_attention_workspace_bytes(B, N_pad, Hq, Hkv, Dh, max_prefix_len) -> int:
+    return load_library().talon_tree_attention_workspace_bytes(B, N_pad, Hq, Hkv, Dh, max_prefix_len)
+
+
+def talon_tree_attention(q, k_prefix, v_prefix, k_tree, v_tree, mask, n_nodes, prefix_len, max_prefix_len, out,
+                         out_lse=None, workspace=None, scale=0.0, stream=None):
+    """q/k_tree/v_tree [B][N_pad][H][Dh] bf16 dense; k_prefix/v_prefix [B][L][Hkv][Dh] views (any strides
+    with a contiguous Dh run); mask [B][N_pad][N_pad/64] int64."""
+    B, N_pad, Hq, Dh = q.shape
+    Hkv = k_tree.shape[2]
+    for t in (q, k_tree, v_tree, out, mask):
+        if not t.is_contiguous():
+            raise TalonError(TALON_ERR_INVALID_ARG, "q, k_tree, v_tree, mask and out must be contiguous")
+    if k_prefix is not None:
+        if k_prefix.stride() != v_prefix.stride() or k_prefix.stride(3) != 1:
+            raise TalonError(TALON_ERR_INVALID_ARG, "k_prefix and v_prefix must share strides, Dh contiguous")
+        sb, st_, sh = k_prefix.stride(0), k_prefix.stride(1), k_prefix.stride(2)
+    else:
+        sb = st_ = sh = Dh
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load_library().talon_tree_attention(
+        _ptr(q), _ptr(k_prefix), _ptr(v_prefix), _ptr(k_tree), _ptr(v_tree), _ptr(mask), _ptr(n_nodes),
+        _ptr(prefix_len), B, N_pad, Hq, Hkv, Dh, max_prefix_len, sb, st_, sh, c_float(scale), _ptr(out),
+        _ptr(out_lse), _ptr(workspace), ws_bytes, _stream(stream)))

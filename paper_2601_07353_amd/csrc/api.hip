@@ -1,0 +1,300 @@
+// C ABI of libtalon: argument validation and kernel launches.  Everything that can be
+// checked on the host is checked before the first launch, so a failed call enqueues nothing.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "talon_internal.h"
+
+namespace talon {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+int check_hip(hipError_t e, const char* what) {
+  if (e == hipSuccess) return TALON_OK;
+  set_error("%s: %s", what, hipGetErrorString(e));
+  return TALON_ERR_RUNTIME;
+}
+
+namespace {
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int check_state(const talon_tree_state* st) {
+  if (!st) { set_error("tree state is NULL"); return TALON_ERR_INVALID_ARG; }
+  if (st->B < 1 || st->B > TALON_B_MAX) { set_error("B=%d outside [1, %d]", st->B, TALON_B_MAX); return TALON_ERR_INVALID_ARG; }
+  if (st->N < 1 || st->N > TALON_N_MAX) { set_error("N=%d outside [1, %d]", st->N, TALON_N_MAX); return TALON_ERR_INVALID_ARG; }
+  if (st->N_pad < st->N || st->N_pad % 64 != 0 || st->N_pad > TALON_N_MAX) {
+    set_error("N_pad=%d must be a multiple of 64 with N <= N_pad <= %d", st->N_pad, TALON_N_MAX);
+    return TALON_ERR_INVALID_ARG;
+  }
+  const void* ptrs[] = {st->token, st->parent, st->depth, st->prob, st->logp, st->n_nodes,
+                        st->frontier_begin, st->frontier_count, st->depth_cur, st->status};
+  for (const void* p : ptrs) {
+    if (!p) { set_error("tree state holds a NULL pointer"); return TALON_ERR_INVALID_ARG; }
+    if (reinterpret_cast<uintptr_t>(p) & 7u) { set_error("tree state pointer is not 8-byte aligned"); return TALON_ERR_INVALID_ARG; }
+  }
+  return TALON_OK;
+}
+
+struct ExpandLayout {
+  size_t off_max, off_sum, off_keys, off_ticket, total;
+  int chunks;
+};
+
+int expand_layout(int B, int N_pad, int vocab, int k, int dtype, ExpandLayout* L) {
+  if (dtype != TALON_DTYPE_F32 && dtype != TALON_DTYPE_BF16) { set_error("dtype %d not supported", dtype); return TALON_ERR_UNSUPPORTED; }
+  if (B < 1 || B > TALON_B_MAX || N_pad < 64 || N_pad > TALON_N_MAX || N_pad % 64) { set_error("bad B=%d or N_pad=%d", B, N_pad); return TALON_ERR_INVALID_ARG; }
+  if (vocab < 1) { set_error("vocab=%d must be >= 1", vocab); return TALON_ERR_INVALID_ARG; }
+  if (k < 1 || k > TALON_K_MAX) { set_error("k=%d outside [1, %d]", k, TALON_K_MAX); return TALON_ERR_INVALID_ARG; }
+  const int ce = expand_chunk_elems(dtype);
+  const long long chunks = (static_cast<long long>(vocab) + ce - 1) / ce;
+  if (chunks * k > kMergeCap) {
+    set_error("vocab=%d with k=%d needs %lld chunk partials per row; at most %d are supported", vocab, k, chunks * k, kMergeCap);
+    return TALON_ERR_UNSUPPORTED;
+  }
+  const size_t rows = static_cast<size_t>(B) * N_pad;
+  L->chunks = static_cast<int>(chunks);
+  L->off_ticket = 0;
+  L->off_max = align_up(rows * sizeof(int32_t), 256);
+  L->off_sum = L->off_max + align_up(rows * chunks * sizeof(float), 256);
+  L->off_keys = L->off_sum + align_up(rows * chunks * sizeof(double), 256);
+  L->total = L->off_keys + align_up(rows * chunks * k * sizeof(uint64_t), 256);
+  return TALON_OK;
+}
+
+int check_expand_args(const void* logits, int dtype, int64_t row_stride, int64_t seq_stride, int row_mode,
+                      const talon_tree_state* st, int32_t vocab, int32_t k, const void* cand_token,
+                      const void* cand_logit, const void* cand_prob, const void* cand_edge_logp,
+                      const void* row_max, const void* row_lse, void* workspace, size_t workspace_bytes,
+                      ExpandLayout* L) {
+  int rc = check_state(st);
+  if (rc) return rc;
+  rc = expand_layout(st->B, st->N_pad, vocab, k, dtype, L);
+  if (rc) return rc;
+  const void* ptrs[] = {logits, cand_token, cand_logit, cand_prob, cand_edge_logp, row_max, row_lse, workspace};
+  for (const void* p : ptrs) {
+    if (!p) { set_error("NULL pointer argument"); return TALON_ERR_INVALID_ARG; }
+    if (!aligned16(p)) { set_error("pointer argument is not 16-byte aligned"); return TALON_ERR_INVALID_ARG; }
+  }
+  const int epv = dtype == TALON_DTYPE_F32 ? 4 : 8;
+  if (row_stride < vocab || row_stride % epv) { set_error("row_stride=%lld must be >= vocab and a multiple of %d elements", (long long)row_stride, epv); return TALON_ERR_INVALID_ARG; }
+  if (seq_stride < 0 || seq_stride % epv || (st->B > 1 && seq_stride < row_stride)) { set_error("seq_stride=%lld invalid", (long long)seq_stride); return TALON_ERR_INVALID_ARG; }
+  if (row_mode != TALON_ROWS_BY_NODE && row_mode != TALON_ROWS_BY_FRONTIER) { set_error("row_mode=%d unknown", row_mode); return TALON_ERR_INVALID_ARG; }
+  if (workspace_bytes < L->total) { set_error("workspace of %zu bytes is smaller than the %zu needed", workspace_bytes, L->total); return TALON_ERR_WORKSPACE; }
+  return TALON_OK;
+}
+
+int check_select_args(const talon_tree_state* st, int32_t k, const void* cand_token, const void* cand_prob,
+                      const void* cand_edge_logp, float mu, int32_t K_init, int32_t init_layers, int32_t max_depth) {
+  int rc = check_state(st);
+  if (rc) return rc;
+  if (k < 1 || k > TALON_K_MAX) { set_error("k=%d outside [1, %d]", k, TALON_K_MAX); return TALON_ERR_INVALID_ARG; }
+  if (!(mu > 0.f && mu <= 1.f)) { set_error("mu=%g outside (0, 1]", (double)mu); return TALON_ERR_INVALID_ARG; }
+  if (K_init < 1) { set_error("K_init=%d must be >= 1", K_init); return TALON_ERR_INVALID_ARG; }
+  if (init_layers < 0) { set_error("init_layers=%d must be >= 0", init_layers); return TALON_ERR_INVALID_ARG; }
+  if (max_depth < 1) { set_error("max_depth=%d must be >= 1", max_depth); return TALON_ERR_INVALID_ARG; }
+  if (!cand_token || !cand_prob || !cand_edge_logp) { set_error("NULL candidate pointer"); return TALON_ERR_INVALID_ARG; }
+  return TALON_OK;
+}
+
+ExpandArgs make_expand_args(const void* logits, int64_t row_stride, int64_t seq_stride, int row_mode,
+                            const talon_tree_state* st, int32_t vocab, int32_t k, int32_t* cand_token,
+                            float* cand_logit, float* cand_prob, double* cand_edge_logp, float* row_max,
+                            double* row_lse, void* workspace, const ExpandLayout& L) {
+  ExpandArgs a;
+  a.logits = logits; a.row_stride = row_stride; a.seq_stride = seq_stride; a.row_mode = row_mode;
+  a.B = st->B; a.N_pad = st->N_pad; a.vocab = vocab; a.k = k; a.chunks = L.chunks;
+  a.frontier_begin = st->frontier_begin; a.frontier_count = st->frontier_count; a.status = st->status;
+  a.cand_token = cand_token; a.cand_logit = cand_logit; a.cand_prob = cand_prob;
+  a.cand_edge_logp = cand_edge_logp; a.row_max = row_max; a.row_lse = row_lse;
+  char* w = static_cast<char*>(workspace);
+  a.ticket = reinterpret_cast<int32_t*>(w + L.off_ticket);
+  a.part_max = reinterpret_cast<float*>(w + L.off_max);
+  a.part_sum = reinterpret_cast<double*>(w + L.off_sum);
+  a.part_keys = reinterpret_cast<unsigned long long*>(w + L.off_keys);
+  return a;
+}
+
+// Workgroups for the scan: enough to hold every (row, chunk) item of the largest possible
+// layer, capped at 8 resident workgroups on each of the 256 compute units.
+int expand_grid(const talon_tree_state* st, int chunks) {
+  const long long rows = static_cast<long long>(st->B) * (st->N > 1 ? st->N - 1 : 1);
+  long long items = rows * chunks;
+  if (items > 2048) items = 2048;
+  if (items < 1) items = 1;
+  return static_cast<int>(items);
+}
+
+}  // namespace
+}  // namespace talon
+
+using namespace talon;
+
+extern "C" {
+
+const char* talon_last_error_string(void) { return g_err; }
+
+int talon_tree_init(const talon_tree_state* st, const int32_t* root_token, void* stream) {
+  int rc = check_state(st);
+  if (rc) return rc;
+  if (!root_token) { set_error("root_token is NULL"); return TALON_ERR_INVALID_ARG; }
+  return check_hip(launch_tree_init(*st, root_token, static_cast<hipStream_t>(stream)), "tree_init launch");
+}
+
+size_t talon_expand_workspace_bytes(int32_t B, int32_t N_pad, int32_t vocab, int32_t k, int dtype) {
+  ExpandLayout L;
+  if (expand_layout(B, N_pad, vocab, k, dtype, &L)) return 0;
+  return L.total;
+}
+
+int talon_expand_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
+  if (!workspace || !aligned16(workspace)) { set_error("workspace is NULL or not 16-byte aligned"); return TALON_ERR_INVALID_ARG; }
+  if (workspace_bytes % 4) { set_error("workspace_bytes must be a multiple of 4"); return TALON_ERR_INVALID_ARG; }
+  return check_hip(launch_fill_zero(workspace, workspace_bytes, static_cast<hipStream_t>(stream)), "workspace fill launch");
+}
+
+int talon_expand_layer(const void* logits, int dtype, int64_t row_stride, int64_t seq_stride, int row_mode,
+                       const talon_tree_state* st, int32_t vocab, int32_t k, int32_t* cand_token,
+                       float* cand_logit, float* cand_prob, double* cand_edge_logp, float* row_max,
+                       double* row_lse, void* workspace, size_t workspace_bytes, void* stream) {
+  ExpandLayout L;
+  int rc = check_expand_args(logits, dtype, row_stride, seq_stride, row_mode, st, vocab, k, cand_token, cand_logit,
+                             cand_prob, cand_edge_logp, row_max, row_lse, workspace, workspace_bytes, &L);
+  if (rc) return rc;
+  const ExpandArgs a = make_expand_args(logits, row_stride, seq_stride, row_mode, st, vocab, k, cand_token,
+                                        cand_logit, cand_prob, cand_edge_logp, row_max, row_lse, workspace, L);
+  return check_hip(launch_expand(a, dtype, expand_grid(st, L.chunks), static_cast<hipStream_t>(stream)), "expand launch");
+}
+
+int talon_select_budget(const talon_tree_state* st, int32_t k, const int32_t* cand_token, const float* cand_prob,
+                        const double* cand_edge_logp, float mu, int32_t K_init, int32_t init_layers,
+                        int32_t max_depth, void* stream) {
+  int rc = check_select_args(st, k, cand_token, cand_prob, cand_edge_logp, mu, K_init, init_layers, max_depth);
+  if (rc) return rc;
+  SelectArgs a;
+  a.st = *st; a.k = k; a.cand_token = cand_token; a.cand_prob = cand_prob; a.cand_edge_logp = cand_edge_logp;
+  a.log_mu = log(static_cast<double>(mu)); a.K_init = K_init; a.init_layers = init_layers; a.max_depth = max_depth;
+  return check_hip(launch_select(a, static_cast<hipStream_t>(stream)), "select launch");
+}
+
+int talon_expand_tree(const void* logits, int dtype, int64_t row_stride, int64_t seq_stride, int row_mode,
+                      const talon_tree_state* st, int32_t vocab, int32_t k, float mu, int32_t K_init,
+                      int32_t init_layers, int32_t max_depth, int32_t* cand_token, float* cand_logit,
+                      float* cand_prob, double* cand_edge_logp, float* row_max, double* row_lse,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+  ExpandLayout L;
+  int rc = check_expand_args(logits, dtype, row_stride, seq_stride, row_mode, st, vocab, k, cand_token, cand_logit,
+                             cand_prob, cand_edge_logp, row_max, row_lse, workspace, workspace_bytes, &L);
+  if (rc) return rc;
+  rc = check_select_args(st, k, cand_token, cand_prob, cand_edge_logp, mu, K_init, init_layers, max_depth);
+  if (rc) return rc;
+  const ExpandArgs ea = make_expand_args(logits, row_stride, seq_stride, row_mode, st, vocab, k, cand_token,
+                                         cand_logit, cand_prob, cand_edge_logp, row_max, row_lse, workspace, L);
+  SelectArgs sa;
+  sa.st = *st; sa.k = k; sa.cand_token = cand_token; sa.cand_prob = cand_prob; sa.cand_edge_logp = cand_edge_logp;
+  sa.log_mu = log(static_cast<double>(mu)); sa.K_init = K_init; sa.init_layers = init_layers; sa.max_depth = max_depth;
+  const int grid = expand_grid(st, L.chunks);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // a tree of N nodes has at most N-1 layers: later iterations could not add anything
+  const int layers = max_depth < st->N - 1 ? max_depth : (st->N > 1 ? st->N - 1 : 0);
+  for (int d = 0; d < layers; ++d) {
+    rc = check_hip(launch_expand(ea, dtype, grid, s), "expand launch");
+    if (rc) return rc;
+    rc = check_hip(launch_select(sa, s), "select launch");
+    if (rc) return rc;
+  }
+  return TALON_OK;
+}
+
+int talon_build_tree_mask(const talon_tree_state* st, uint64_t* mask, void* stream) {
+  int rc = check_state(st);
+  if (rc) return rc;
+  if (!mask || (reinterpret_cast<uintptr_t>(mask) & 7u)) { set_error("mask is NULL or misaligned"); return TALON_ERR_INVALID_ARG; }
+  return check_hip(launch_mask(*st, mask, static_cast<hipStream_t>(stream)), "mask launch");
+}
+
+static int attention_layout(int32_t B, int32_t N_pad, int32_t Hq, int32_t Hkv, int32_t Dh, int32_t max_prefix_len,
+                            int* splits, int* tps, int* rows_pad, size_t* off_m, size_t* off_l, size_t* total) {
+  if (B < 1 || B > TALON_B_MAX) { set_error("B=%d outside [1, %d]", B, TALON_B_MAX); return TALON_ERR_INVALID_ARG; }
+  if (N_pad < 64 || N_pad > TALON_N_MAX || N_pad % 64) { set_error("N_pad=%d must be a multiple of 64 in [64, %d]", N_pad, TALON_N_MAX); return TALON_ERR_INVALID_ARG; }
+  if (Hq < 1 || Hkv < 1 || max_prefix_len < 0) { set_error("Hq, Hkv must be >= 1 and max_prefix_len >= 0"); return TALON_ERR_INVALID_ARG; }
+  if (Dh != 64 && Dh != 128) { set_error("Dh=%d not supported (64 or 128)", Dh); return TALON_ERR_UNSUPPORTED; }
+  if (Hq % Hkv) { set_error("Hq=%d is not a multiple of Hkv=%d", Hq, Hkv); return TALON_ERR_UNSUPPORTED; }
+  if (Hq / Hkv > 16) { set_error("Hq/Hkv=%d above 16 is not supported", Hq / Hkv); return TALON_ERR_UNSUPPORTED; }
+  attention_plan(B, N_pad, Hq, Hkv, Dh, max_prefix_len, splits, tps, rows_pad);
+  const size_t prow = static_cast<size_t>(B) * Hkv * (*splits) * (*rows_pad);
+  *off_m = prow * Dh * sizeof(float);
+  *off_l = *off_m + prow * sizeof(float);
+  *total = *off_l + prow * sizeof(float);
+  if (*splits == 1) *total = 256;  // nothing is staged, keep a token size
+  return TALON_OK;
+}
+
+size_t talon_tree_attention_workspace_bytes(int32_t B, int32_t N_pad, int32_t Hq, int32_t Hkv, int32_t Dh,
+                                            int32_t max_prefix_len) {
+  int splits, tps, rows_pad;
+  size_t off_m, off_l, total;
+  if (attention_layout(B, N_pad, Hq, Hkv, Dh, max_prefix_len, &splits, &tps, &rows_pad, &off_m, &off_l, &total)) return 0;
+  return total;
+}
+
+int talon_tree_attention(const void* q, const void* k_prefix, const void* v_prefix, const void* k_tree,
+                         const void* v_tree, const uint64_t* mask, const int32_t* n_nodes,
+                         const int32_t* prefix_len, int32_t B, int32_t N_pad, int32_t Hq, int32_t Hkv, int32_t Dh,
+                         int32_t max_prefix_len, int64_t kv_stride_b, int64_t kv_stride_t, int64_t kv_stride_h,
+                         float scale, void* out, float* out_lse, void* workspace, size_t workspace_bytes,
+                         void* stream) {
+  AttnArgs a;
+  size_t off_m, off_l, total;
+  int rc = attention_layout(B, N_pad, Hq, Hkv, Dh, max_prefix_len, &a.splits, &a.tiles_per_split, &a.rows_pad, &off_m,
+                            &off_l, &total);
+  if (rc) return rc;
+  const void* ptrs[] = {q, k_tree, v_tree, mask, out};
+  for (const void* p : ptrs) {
+    if (!p) { set_error("NULL pointer argument"); return TALON_ERR_INVALID_ARG; }
+    if (!aligned16(p)) { set_error("pointer argument is not 16-byte aligned"); return TALON_ERR_INVALID_ARG; }
+  }
+  if (!n_nodes || !prefix_len) { set_error("n_nodes / prefix_len is NULL"); return TALON_ERR_INVALID_ARG; }
+  if (max_prefix_len > 0) {
+    if (!k_prefix || !v_prefix) { set_error("prefix K/V is NULL"); return TALON_ERR_INVALID_ARG; }
+    if (!aligned16(k_prefix) || !aligned16(v_prefix)) { set_error("prefix K/V is not 16-byte aligned"); return TALON_ERR_INVALID_ARG; }
+    if (kv_stride_t < Dh || kv_stride_h < Dh || kv_stride_b < 0 || kv_stride_t % 8 || kv_stride_h % 8 || kv_stride_b % 8) {
+      set_error("prefix K/V strides must be >= Dh and multiples of 8 elements");
+      return TALON_ERR_INVALID_ARG;
+    }
+  }
+  if (out_lse && (reinterpret_cast<uintptr_t>(out_lse) & 3u)) { set_error("out_lse is misaligned"); return TALON_ERR_INVALID_ARG; }
+  if (!(scale >= 0.f) || isinf(scale)) { set_error("scale=%g must be finite and >= 0 (0 selects 1/sqrt(Dh))", (double)scale); return TALON_ERR_INVALID_ARG; }
+  if (a.splits > 1) {
+    if (!workspace || !aligned16(workspace)) { set_error("workspace is NULL or not 16-byte aligned"); return TALON_ERR_INVALID_ARG; }
+    if (workspace_bytes < total) { set_error("workspace of %zu bytes is smaller than the %zu needed", workspace_bytes, total); return TALON_ERR_WORKSPACE; }
+  }
+  a.q = static_cast<const uint16_t*>(q);
+  a.k_prefix = static_cast<const uint16_t*>(k_prefix);
+  a.v_prefix = static_cast<const uint16_t*>(v_prefix);
+  a.k_tree = static_cast<const uint16_t*>(k_tree);
+  a.v_tree = static_cast<const uint16_t*>(v_tree);
+  a.mask = mask; a.n_nodes = n_nodes; a.prefix_len = prefix_len;
+  a.B = B; a.N_pad = N_pad; a.Hq = Hq; a.Hkv = Hkv; a.G = Hq / Hkv; a.Dh = Dh; a.max_prefix_len = max_prefix_len;
+  a.kv_stride_b = kv_stride_b; a.kv_stride_t = kv_stride_t; a.kv_stride_h = kv_stride_h;
+  const float sc = scale == 0.f ? 1.f / sqrtf(static_cast<float>(Dh)) : scale;
+  a.scale_log2e = sc * 1.4426950408889634f;
+  a.out = static_cast<uint16_t*>(out);
+  a.out_lse = out_lse;
+  char* w = static_cast<char*>(workspace);
+  a.part_o = reinterpret_cast<float*>(w);
+  a.part_m = reinterpret_cast<float*>(w + off_m);
+  a.part_l = reinterpret_cast<float*>(w + off_l);
+  return check_hip(launch_attention(a, static_cast<hipStream_t>(stream)), "tree attention launch");
+}
+
+}  // extern "C"

@@ -1,0 +1,88 @@
+// Internal declarations shared by the translation units of libtalon (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "talon.h"
+
+namespace talon {
+
+constexpr int kThreads = 256;       // every kernel here runs 4 wavefronts per workgroup
+constexpr int kScanTiles = 4;       // 16-byte vectors per thread per vocab chunk
+constexpr int kChunkBytes = kThreads * kScanTiles * 16;  // 16 KiB of a logits row per workgroup pass
+constexpr int kCandCap = 512;       // LDS candidate slots per chunk before the exact fallback
+constexpr int kMergeCap = 1024;     // chunks * k keys one row merge stages in LDS
+constexpr uint32_t kDoneMask = TALON_STATUS_DONE_BUDGET | TALON_STATUS_DONE_DEPTH;
+
+void set_error(const char* fmt, ...);
+int check_hip(hipError_t e, const char* what);
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+struct ExpandArgs {
+  const void* logits;
+  int64_t row_stride, seq_stride;
+  int row_mode;
+  int B, N_pad, vocab, k, chunks;
+  const int32_t* frontier_begin;
+  const int32_t* frontier_count;
+  uint32_t* status;
+  int32_t* cand_token;
+  float* cand_logit;
+  float* cand_prob;
+  double* cand_edge_logp;
+  float* row_max;
+  double* row_lse;
+  float* part_max;       // [rows][chunks]
+  double* part_sum;      // [rows][chunks]
+  unsigned long long* part_keys;  // [rows][chunks][k]
+  int32_t* ticket;       // [rows]
+};
+
+struct SelectArgs {
+  talon_tree_state st;
+  int k;
+  const int32_t* cand_token;
+  const float* cand_prob;
+  const double* cand_edge_logp;
+  double log_mu;
+  int K_init, init_layers, max_depth;
+};
+
+struct AttnArgs {
+  const uint16_t* q;
+  const uint16_t* k_prefix;
+  const uint16_t* v_prefix;
+  const uint16_t* k_tree;
+  const uint16_t* v_tree;
+  const uint64_t* mask;
+  const int32_t* n_nodes;
+  const int32_t* prefix_len;
+  int B, N_pad, Hq, Hkv, G, Dh;
+  int max_prefix_len;
+  int64_t kv_stride_b, kv_stride_t, kv_stride_h;
+  float scale_log2e;     // scale * log2(e): scores are kept in base-2 units
+  uint16_t* out;
+  float* out_lse;
+  int splits;            // KV splits per (sequence, kv head, row tile)
+  int tiles_per_split;   // key tiles of kAttnKeyTile per split
+  float* part_o;         // [B][Hkv][splits][rows_pad][Dh]  unnormalised partial outputs
+  float* part_m;         // [B][Hkv][splits][rows_pad]      running max (base-2 units)
+  float* part_l;         // [B][Hkv][splits][rows_pad]      running denominator
+  int rows_pad;          // N_pad * G rounded up to the row tile
+};
+
+// launchers (each checks nothing: arguments were validated by the ABI layer)
+hipError_t launch_tree_init(const talon_tree_state& st, const int32_t* root_token, hipStream_t s);
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+hipError_t launch_expand(const ExpandArgs& a, int dtype, int grid, hipStream_t s);
+hipError_t launch_select(const SelectArgs& a, hipStream_t s);
+hipError_t launch_mask(const talon_tree_state& st, uint64_t* mask, hipStream_t s);
+hipError_t launch_attention(const AttnArgs& a, hipStream_t s);
+
+int expand_chunk_elems(int dtype);
+void attention_plan(int B, int N_pad, int Hq, int Hkv, int Dh, int max_prefix_len, int* splits,
+                    int* tiles_per_split, int* rows_pad);
+
+}  // namespace talon

@@ -1,0 +1,240 @@
+"""Test harness: runs one expand+verify step through the HIP library and through the CPU
+oracle on the same seeded inputs, and compares them.  Test infrastructure only."""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+from workloads import WorkloadConfig, attention_inputs, bf16_bits_to_f64, logits_row, storage_to_f64
+
+MARGIN_TOL = 1e-4   # smallest cross-parent score gap a seed must leave (log units)
+PROB_RTOL = 1e-5    # probabilities and path confidences, relative
+ATTN_ATOL = 2e-2    # tree-attention outputs, absolute (bf16 inputs, fp64 oracle)
+LSE_ATOL = 2e-6     # row log-sum-exp, absolute
+
+
+def seeds_for(cfg: WorkloadConfig, seeds=None):
+    if seeds is None:
+        return [cfg.seed] * cfg.B
+    if isinstance(seeds, int):
+        return [seeds] * cfg.B
+    return list(seeds)
+
+
+def build_pool(cfg: WorkloadConfig, seeds) -> np.ndarray:
+    dt = np.float32 if cfg.logits_dtype == "f32" else np.uint16
+    pool = np.zeros((cfg.B, cfg.N_pad, cfg.V), dtype=dt)
+    for b in range(cfg.B):
+        for i in range(cfg.N):
+            pool[b, i] = logits_row(cfg, seeds[b], b, i)
+    return pool
+
+
+def root_tokens(cfg: WorkloadConfig) -> np.ndarray:
+    return (np.arange(cfg.B, dtype=np.int32) * 7 + 11) % cfg.V
+
+
+# --------------------------------------------------------------------------- oracle side
+def oracle_tree(cfg: WorkloadConfig, pool_b: np.ndarray, root: int, init_layers: int = 1, mu=None, K_init=None):
+    from oracle import talon_oracle as O
+    cache = {}
+
+    def row_of(i):
+        if i not in cache:
+            cache[i] = storage_to_f64(pool_b[i])
+        return cache[i]
+
+    mu = float(np.float32(cfg.mu if mu is None else mu))  # the ABI takes mu as a float
+    K_init = cfg.K if K_init is None else K_init
+    return O.build_tree(row_of, int(root), N=cfg.N, K=K_init, mu=mu, cap=cfg.K, Dmax=cfg.Dmax,
+                        init_layers=init_layers)
+
+
+def find_admissible_seed(cfg: WorkloadConfig, b: int, base_seed: int, tol: float = MARGIN_TOL, max_tries: int = 64):
+    """First seed >= base_seed whose oracle tree for sequence b leaves every cross-parent
+    decision a margin > tol, so that an fp32 log-sum-exp cannot change the topology."""
+    roots = root_tokens(cfg)
+    for s in range(base_seed, base_seed + max_tries):
+        rows = {}
+
+        class Lazy:
+            def __getitem__(self, i):
+                if i not in rows:
+                    rows[i] = logits_row(cfg, s, b, i)
+                return rows[i]
+
+        t = oracle_tree(cfg, Lazy(), roots[b])
+        if t.margin > tol:
+            return s, t
+    raise RuntimeError("no admissible seed found for %s sequence %d" % (cfg.name, b))
+
+
+def run_oracle_step(cfg: WorkloadConfig, seeds=None, pool=None, attn=None, attn_nodes=None, attn_heads=None,
+                    with_attention=True, init_layers=1, mu=None, K_init=None):
+    from oracle import talon_oracle as O
+    seeds = seeds_for(cfg, seeds)
+    pool = build_pool(cfg, seeds) if pool is None else pool
+    roots = root_tokens(cfg)
+    res = {"trees": [], "mask": [], "attn_out": [], "attn_lse": []}
+    for b in range(cfg.B):
+        t = oracle_tree(cfg, pool[b], roots[b], init_layers, mu, K_init)
+        m = O.build_tree_mask(t.parent)
+        res["trees"].append(t)
+        res["mask"].append(m)
+        if with_attention:
+            x = attention_inputs(cfg, seeds[b], b) if attn is None else attn[b]
+            n = t.n
+            out, lse = O.tree_attention(bf16_bits_to_f64(x["q"][:n]), bf16_bits_to_f64(x["k_prefix"]),
+                                        bf16_bits_to_f64(x["v_prefix"]), bf16_bits_to_f64(x["k_tree"][:n]),
+                                        bf16_bits_to_f64(x["v_tree"][:n]), m, nodes=attn_nodes, heads=attn_heads)
+            res["attn_out"].append(out)
+            res["attn_lse"].append(lse)
+    return res
+
+
+# --------------------------------------------------------------------------- GPU side
+def to_device_logits(pool: np.ndarray):
+    """Pool on the device, rows padded to a multiple of 8 elements (the ABI wants 16-byte row strides);
+    the returned view keeps the true vocabulary width."""
+    import torch
+    V = pool.shape[2]
+    V_pad = (V + 7) // 8 * 8
+    if V_pad != V:
+        padded = np.zeros(pool.shape[:2] + (V_pad,), dtype=pool.dtype)
+        padded[:, :, :V] = pool
+        pool = padded
+    if pool.dtype == np.uint16:
+        dev = torch.from_numpy(pool.view(np.int16)).cuda().view(torch.bfloat16)
+    else:
+        dev = torch.from_numpy(pool).cuda()
+    return dev[:, :, :V]
+
+
+def bf16_to_device(bits: np.ndarray):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def run_gpu_expand(cfg: WorkloadConfig, pool_dev, init_layers=1, mu=None, K_init=None, layerwise=False):
+    """Whole expansion loop on the GPU.  layerwise=True drives the two per-layer entry points
+    from the host instead of the single talon_expand_tree call."""
+    import torch
+    import paper_2601_07353_amd as T
+    st = T.TreeState(cfg.B, cfg.N)
+    cand = T.Candidates(cfg.B, st.N_pad, cfg.K)
+    dt = T.TALON_DTYPE_F32 if cfg.logits_dtype == "f32" else T.TALON_DTYPE_BF16
+    ws = T.make_expand_workspace(cfg.B, st.N_pad, cfg.V, cfg.K, dt)
+    roots = torch.from_numpy(root_tokens(cfg)).cuda()
+    mu = cfg.mu if mu is None else mu
+    K_init = cfg.K if K_init is None else K_init
+    T.talon_tree_init(st, roots)
+    if layerwise:
+        for _ in range(cfg.Dmax):
+            T.talon_expand_layer(pool_dev, st, cfg.K, cand, ws)
+            T.talon_select_budget(st, cfg.K, cand, mu, K_init, init_layers, cfg.Dmax)
+    else:
+        T.talon_expand_tree(pool_dev, st, cfg.K, mu, K_init, init_layers, cfg.Dmax, cand, ws)
+    torch.cuda.synchronize()
+    return st, cand, ws
+
+
+def run_gpu_step(cfg: WorkloadConfig, seeds=None, pool=None, attn=None, with_attention=True, init_layers=1,
+                 mu=None, K_init=None, layerwise=False):
+    import torch
+    import paper_2601_07353_amd as T
+    seeds = seeds_for(cfg, seeds)
+    pool = build_pool(cfg, seeds) if pool is None else pool
+    pool_dev = to_device_logits(pool)
+    st, cand, _ = run_gpu_expand(cfg, pool_dev, init_layers, mu, K_init, layerwise)
+    mask = torch.zeros(cfg.B, st.N_pad, st.N_pad // 64, dtype=torch.int64, device="cuda")
+    T.talon_build_tree_mask(st, mask)
+    res = {
+        "token": st.token.cpu().numpy(), "parent": st.parent.cpu().numpy(), "depth": st.depth.cpu().numpy(),
+        "prob": st.prob.cpu().numpy(), "logp": st.logp.cpu().numpy(), "n_nodes": st.n_nodes.cpu().numpy(),
+        "status": st.status.cpu().numpy(), "depth_cur": st.depth_cur.cpu().numpy(),
+        "frontier_begin": st.frontier_begin.cpu().numpy(), "frontier_count": st.frontier_count.cpu().numpy(),
+        "mask": mask.cpu().numpy().view(np.uint64),
+        "cand_token": cand.token.cpu().numpy(), "cand_logit": cand.logit.cpu().numpy(),
+        "cand_prob": cand.prob.cpu().numpy(), "cand_edge_logp": cand.edge_logp.cpu().numpy(),
+        "row_max": cand.row_max.cpu().numpy(), "row_lse": cand.row_lse.cpu().numpy(),
+    }
+    if with_attention:
+        xs = [attention_inputs(cfg, seeds[b], b) for b in range(cfg.B)] if attn is None else attn
+        q = bf16_to_device(np.stack([x["q"] for x in xs]))
+        kp = bf16_to_device(np.stack([x["k_prefix"] for x in xs]))
+        vp = bf16_to_device(np.stack([x["v_prefix"] for x in xs]))
+        kt = bf16_to_device(np.stack([x["k_tree"] for x in xs]))
+        vt = bf16_to_device(np.stack([x["v_tree"] for x in xs]))
+        L = kp.shape[1]
+        plen = torch.full((cfg.B,), L, dtype=torch.int32, device="cuda")
+        out = torch.zeros(cfg.B, st.N_pad, cfg.Hq, cfg.Dh, dtype=torch.bfloat16, device="cuda")
+        lse = torch.zeros(cfg.B, st.N_pad, cfg.Hq, dtype=torch.float32, device="cuda")
+        nb = T.talon_tree_attention_workspace_bytes(cfg.B, st.N_pad, cfg.Hq, cfg.Hkv, cfg.Dh, L)
+        ws = torch.empty(max(nb, 256), dtype=torch.uint8, device="cuda")
+        T.talon_tree_attention(q, kp, vp, kt, vt, mask, st.n_nodes, plen, L, out, lse, ws)
+        torch.cuda.synchronize()
+        res["attn_out"] = out.float().cpu().numpy()
+        res["attn_lse"] = lse.cpu().numpy()
+    return res
+
+
+# --------------------------------------------------------------------------- comparison
+def compare_tree(cfg: WorkloadConfig, gpu: dict, trees, check_rows=True):
+    """Topology, tokens and counters bit-exact; probabilities and confidences to PROB_RTOL."""
+    for b, t in enumerate(trees):
+        n = t.n
+        assert int(gpu["n_nodes"][b]) == n, (b, int(gpu["n_nodes"][b]), n)
+        np.testing.assert_array_equal(gpu["token"][b, :n], np.asarray(t.token, dtype=np.int32))
+        np.testing.assert_array_equal(gpu["parent"][b, :n], np.asarray(t.parent, dtype=np.int32))
+        np.testing.assert_array_equal(gpu["depth"][b, :n], np.asarray(t.depth, dtype=np.int32))
+        np.testing.assert_allclose(gpu["prob"][b, :n], np.asarray(t.prob), rtol=PROB_RTOL, atol=0)
+        np.testing.assert_allclose(np.exp(gpu["logp"][b, :n]), t.confidence(), rtol=PROB_RTOL, atol=0)
+        want_status = 1 if t.exit_reason == "budget" else 2
+        assert int(gpu["status"][b]) == want_status, (b, int(gpu["status"][b]), want_status)
+        assert int(gpu["depth_cur"][b]) == len(t.layers) - 1
+        last = t.layers[-1]
+        assert int(gpu["frontier_begin"][b]) == last.start and int(gpu["frontier_count"][b]) == len(last)
+        if check_rows:
+            for pool in t.pools:
+                for r in pool:
+                    c = len(r.token)
+                    np.testing.assert_array_equal(gpu["cand_token"][b, r.node, :c], r.token.astype(np.int32))
+                    np.testing.assert_array_equal(gpu["cand_logit"][b, r.node, :c], r.logit.astype(np.float32))
+                    assert float(gpu["row_max"][b, r.node]) == r.row_max
+                    assert abs(float(gpu["row_lse"][b, r.node]) - r.row_lse) <= LSE_ATOL
+                    np.testing.assert_allclose(gpu["cand_prob"][b, r.node, :c], r.prob, rtol=PROB_RTOL, atol=1e-37)
+                    np.testing.assert_allclose(gpu["cand_edge_logp"][b, r.node, :c], r.edge_logp, rtol=0, atol=LSE_ATOL)
+
+
+def compare_mask(cfg: WorkloadConfig, gpu: dict, masks):
+    from oracle import talon_oracle as O
+    for b, m in enumerate(masks):
+        np.testing.assert_array_equal(gpu["mask"][b], O.mask_to_words(m, cfg.N_pad))
+
+
+def compare_attention(cfg: WorkloadConfig, gpu: dict, ref: dict):
+    worst = 0.0
+    for b in range(cfg.B):
+        want = ref["attn_out"][b]
+        n = want.shape[0]
+        got = gpu["attn_out"][b, :n]
+        sel = ~np.isnan(want)
+        assert sel.any()
+        err = np.abs(got[sel] - want[sel]).max()
+        worst = max(worst, float(err))
+        assert err <= ATTN_ATOL, (b, err)
+        wl = ref["attn_lse"][b]
+        sl = ~np.isnan(wl)
+        assert np.abs(gpu["attn_lse"][b, :n][sl] - wl[sl]).max() <= 2e-3
+        # rows beyond n_nodes must be untouched (the harness pre-fills the output with zeros)
+        assert not gpu["attn_out"][b, n:].any()
+    return worst
+
+
+def compare_step(cfg: WorkloadConfig, gpu: dict, ref: dict, check_rows=True):
+    compare_tree(cfg, gpu, ref["trees"], check_rows)
+    compare_mask(cfg, gpu, ref["mask"])
+    if "attn_out" in gpu and ref["attn_out"]:
+        return compare_attention(cfg, gpu, ref)
+    return None

@@ -1,0 +1,134 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the header
+declares, and rejects bad arguments before anything is launched (no GPU needed: the
+pointers below are fake, validation never dereferences them)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2601_07353_amd as T
+from paper_2601_07353_amd.binding import _CTreeState
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(T.binding.LIB_PATH):
+        from paper_2601_07353_amd import build
+        build.build()
+    return T.load_library()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "talon.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(talon_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(lib):
+    names = declared_functions()
+    assert len(names) >= 10
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(names) == set(T.binding.EXPORTS)
+
+
+def fake_state(B=1, N=16, N_pad=64, ptr=0x10000):
+    return _CTreeState(B, N, N_pad, *[ptr + 0x1000 * i for i in range(10)])
+
+
+def err(lib):
+    return lib.talon_last_error_string().decode()
+
+
+P = 0x7000000  # aligned fake device address
+
+
+def expand_call(lib, st, logits=P, dtype=1, row_stride=1024, seq_stride=1024 * 64, row_mode=0, vocab=1024, k=4,
+                ws=P, ws_bytes=1 << 30, out=P):
+    return lib.talon_expand_layer(logits, dtype, row_stride, seq_stride, row_mode, ctypes.byref(st), vocab, k,
+                                  out, out, out, out, out, out, ws, ws_bytes, None)
+
+
+def test_expand_rejects_bad_arguments(lib):
+    st = fake_state()
+    assert expand_call(lib, st, k=0) == T.TALON_ERR_INVALID_ARG and "k=0" in err(lib)
+    assert expand_call(lib, st, k=17) == T.TALON_ERR_INVALID_ARG
+    assert expand_call(lib, st, vocab=0) == T.TALON_ERR_INVALID_ARG
+    assert expand_call(lib, st, dtype=7) == T.TALON_ERR_UNSUPPORTED
+    assert expand_call(lib, st, logits=0) == T.TALON_ERR_INVALID_ARG
+    assert expand_call(lib, st, logits=P + 2) == T.TALON_ERR_INVALID_ARG and "aligned" in err(lib)
+    assert expand_call(lib, st, row_stride=1000) == T.TALON_ERR_INVALID_ARG   # < vocab
+    assert expand_call(lib, st, row_stride=1028) == T.TALON_ERR_INVALID_ARG   # not a multiple of 8 bf16
+    assert expand_call(lib, st, row_mode=5) == T.TALON_ERR_INVALID_ARG
+    assert expand_call(lib, st, ws_bytes=16) == T.TALON_ERR_WORKSPACE and "smaller" in err(lib)
+    assert expand_call(lib, st, vocab=16 * 8192 * 5, row_stride=16 * 8192 * 5, k=16) == T.TALON_ERR_UNSUPPORTED
+    assert expand_call(lib, fake_state(N=300, N_pad=320)) == T.TALON_ERR_INVALID_ARG
+    assert expand_call(lib, fake_state(N_pad=48)) == T.TALON_ERR_INVALID_ARG
+    assert expand_call(lib, fake_state(B=0)) == T.TALON_ERR_INVALID_ARG
+    bad = fake_state(); bad.logp = 0
+    assert expand_call(lib, bad) == T.TALON_ERR_INVALID_ARG
+
+
+def test_workspace_size_queries(lib):
+    a = lib.talon_expand_workspace_bytes(1, 64, 128256, 10, 1)
+    b = lib.talon_expand_workspace_bytes(4, 128, 151936, 8, 1)
+    assert 0 < a < b
+    assert lib.talon_expand_workspace_bytes(1, 64, 128256, 0, 1) == 0
+    assert lib.talon_tree_attention_workspace_bytes(1, 64, 32, 8, 128, 2048) > 0
+    assert lib.talon_tree_attention_workspace_bytes(1, 64, 32, 8, 96, 2048) == 0
+    assert lib.talon_expand_workspace_init(None, 1024, None) == T.TALON_ERR_INVALID_ARG
+
+
+def select_call(lib, st, k=4, mu=0.03, K_init=4, init_layers=1, max_depth=8, cand=P):
+    return lib.talon_select_budget(ctypes.byref(st), k, cand, cand, cand, ctypes.c_float(mu), K_init, init_layers,
+                                   max_depth, None)
+
+
+def test_select_rejects_bad_arguments(lib):
+    st = fake_state()
+    for mu in (0.0, -0.1, 1.5, float("nan")):
+        assert select_call(lib, st, mu=mu) == T.TALON_ERR_INVALID_ARG and "mu" in err(lib)
+    assert select_call(lib, st, K_init=0) == T.TALON_ERR_INVALID_ARG
+    assert select_call(lib, st, init_layers=-1) == T.TALON_ERR_INVALID_ARG
+    assert select_call(lib, st, max_depth=0) == T.TALON_ERR_INVALID_ARG
+    assert select_call(lib, st, k=0) == T.TALON_ERR_INVALID_ARG
+    assert select_call(lib, st, cand=0) == T.TALON_ERR_INVALID_ARG
+    assert lib.talon_select_budget(None, 4, P, P, P, ctypes.c_float(0.03), 4, 1, 8, None) == T.TALON_ERR_INVALID_ARG
+
+
+def test_mask_and_init_reject_bad_arguments(lib):
+    st = fake_state()
+    assert lib.talon_build_tree_mask(ctypes.byref(st), None, None) == T.TALON_ERR_INVALID_ARG
+    assert lib.talon_build_tree_mask(None, P, None) == T.TALON_ERR_INVALID_ARG
+    assert lib.talon_tree_init(ctypes.byref(st), None, None) == T.TALON_ERR_INVALID_ARG
+
+
+def attn_call(lib, q=P, kp=P, vp=P, kt=P, vt=P, mask=P, n=P, pl=P, B=1, N_pad=64, Hq=32, Hkv=8, Dh=128, Lmax=2048,
+              sb=2048 * 8 * 128, st_=8 * 128, sh=128, scale=0.0, out=P, ws=P, ws_bytes=1 << 40):
+    return lib.talon_tree_attention(q, kp, vp, kt, vt, mask, n, pl, B, N_pad, Hq, Hkv, Dh, Lmax, sb, st_, sh,
+                                    ctypes.c_float(scale), out, None, ws, ws_bytes, None)
+
+
+def test_attention_rejects_bad_arguments(lib):
+    assert attn_call(lib, Dh=96) == T.TALON_ERR_UNSUPPORTED
+    assert attn_call(lib, Hq=30) == T.TALON_ERR_UNSUPPORTED
+    assert attn_call(lib, Hq=34, Hkv=2) == T.TALON_ERR_UNSUPPORTED     # group of 17
+    assert attn_call(lib, N_pad=60) == T.TALON_ERR_INVALID_ARG
+    assert attn_call(lib, q=0) == T.TALON_ERR_INVALID_ARG
+    assert attn_call(lib, q=P + 8) == T.TALON_ERR_INVALID_ARG
+    assert attn_call(lib, kp=0) == T.TALON_ERR_INVALID_ARG
+    assert attn_call(lib, st_=100) == T.TALON_ERR_INVALID_ARG
+    assert attn_call(lib, n=0) == T.TALON_ERR_INVALID_ARG
+    assert attn_call(lib, scale=-1.0) == T.TALON_ERR_INVALID_ARG
+    assert attn_call(lib, ws_bytes=64) == T.TALON_ERR_WORKSPACE
+    assert attn_call(lib, B=0) == T.TALON_ERR_INVALID_ARG
+
+
+def test_binding_refuses_missing_library(monkeypatch):
+    monkeypatch.setattr(T.binding, "_lib", None)
+    monkeypatch.setattr(T.binding, "LIB_PATH", "/nonexistent/libtalon.so")
+    with pytest.raises(RuntimeError, match="not built"):
+        T.binding.load_library()

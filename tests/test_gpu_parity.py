@@ -1,0 +1,296 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded synthetic inputs.  Topology, token ids, masks: bit-exact.  Probabilities and path
+confidences: 1e-5 relative.  Tree attention: 2e-2 absolute (bf16 inputs, fp64 oracle)."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+from tests import harness as H
+from workloads import CONFIGS, WorkloadConfig, f32_to_bf16_bits
+
+pytestmark = pytest.mark.gpu
+
+
+def admissible_seeds(cfg):
+    return [H.find_admissible_seed(cfg, b, cfg.seed)[0] for b in range(cfg.B)]
+
+
+def small(name="t", **kw):
+    base = dict(name=name, B=1, V=1024, logits_dtype="f32", K=2, N=16, Dmax=6, mu=0.03, Hq=4, Hkv=4, Dh=64,
+                L=128, recipe=("gauss", 0.5, 4.0))
+    base.update(kw)
+    return WorkloadConfig(**base)
+
+
+def step_and_compare(cfg, seeds=None, **kw):
+    seeds = admissible_seeds(cfg) if seeds is None else seeds
+    print("case", cfg.name, "seeds", seeds, flush=True)
+    pool = H.build_pool(cfg, seeds)
+    gpu = H.run_gpu_step(cfg, seeds, pool=pool, **kw)
+    okw = {k: v for k, v in kw.items() if k in ("init_layers", "mu", "K_init", "with_attention")}
+    ref = H.run_oracle_step(cfg, seeds, pool=pool, **okw)
+    return H.compare_step(cfg, gpu, ref), gpu, ref
+
+
+# ----------------------------------------------------------------------------- whole steps
+def test_c1_tiny_step():
+    worst, gpu, ref = step_and_compare(CONFIGS["c1"])
+    assert ref["trees"][0].n == 16
+
+
+def test_c1_layerwise_entry_points_match_single_call():
+    cfg = CONFIGS["c1"]
+    seeds = admissible_seeds(cfg)
+    a = H.run_gpu_step(cfg, seeds, with_attention=False, layerwise=True)
+    b = H.run_gpu_step(cfg, seeds, with_attention=False, layerwise=False)
+    for key in ("token", "parent", "depth", "n_nodes", "status", "mask", "prob", "logp"):
+        np.testing.assert_array_equal(a[key], b[key])
+
+
+def test_c2_llama3_8b_step_full_size():
+    worst, gpu, ref = step_and_compare(CONFIGS["c2"])
+    print("c2 attention worst abs err", worst)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(V=1000, logits_dtype="bf16", K=5, N=40, Dmax=10),        # bf16 row with a ragged 8-vector tail? (1000 % 8 == 0)
+    dict(V=1003, logits_dtype="f32", K=4, N=33, Dmax=9),           # ragged f32 tail, N not a multiple of 64
+    dict(V=20011, logits_dtype="bf16", K=16, N=100, Dmax=12, recipe=("gauss", 0.5, 8.0)),   # 3 chunks, ragged
+    dict(V=9001, logits_dtype="f32", K=7, N=64, Dmax=16, recipe=("gauss", 2.0, 8.0)),       # 3 f32 chunks
+    dict(V=40000, logits_dtype="bf16", K=8, N=130, Dmax=20, B=3, Hq=8, Hkv=2, Dh=128, L=200,
+         recipe=(("gauss", 6.0, 8.0), ("gauss", 0.5, 1.0), ("zipf_mix", 1.2, 0.05))),
+    dict(V=32000, logits_dtype="bf16", K=10, N=256, Dmax=24, B=2, Hq=8, Hkv=8, Dh=64, L=70,
+         recipe=("zipf_mix", 1.2, 0.05)),
+])
+def test_small_variants(kw):
+    cfg = small(name="variant", **kw)
+    step_and_compare(cfg)
+
+
+@pytest.mark.parametrize("mu", [0.01, 0.04, 1.0, 1e-30])
+def test_mu_sweep(mu):
+    cfg = small(name="mu", V=4096, logits_dtype="bf16", K=6, N=48, Dmax=48, mu=mu)
+    step_and_compare(cfg, with_attention=False)
+
+
+@pytest.mark.parametrize("init_layers,K_init", [(0, 4), (2, 4), (3, 2), (1, 9)])
+def test_init_layer_variants(init_layers, K_init):
+    cfg = small(name="init", V=4096, logits_dtype="bf16", K=6, N=40, Dmax=12)
+    seeds = [cfg.seed + 3]
+    pool = H.build_pool(cfg, seeds)
+    gpu = H.run_gpu_step(cfg, seeds, pool=pool, with_attention=False, init_layers=init_layers, K_init=K_init)
+    ref = H.run_oracle_step(cfg, seeds, pool=pool, with_attention=False, init_layers=init_layers, K_init=K_init)
+    if ref["trees"][0].margin <= H.MARGIN_TOL:
+        pytest.skip("seed not admissible for this variant")
+    H.compare_step(cfg, gpu, ref)
+
+
+# ----------------------------------------------------------------------------- degenerate rows
+def custom_pool(cfg, fill):
+    dt = np.float32 if cfg.logits_dtype == "f32" else np.uint16
+    pool = np.zeros((cfg.B, cfg.N_pad, cfg.V), dtype=dt)
+    for b in range(cfg.B):
+        for i in range(cfg.N):
+            x = fill(b, i).astype(np.float32)
+            pool[b, i] = x if cfg.logits_dtype == "f32" else f32_to_bf16_bits(x)
+    return pool
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_constant_rows_all_ties(dtype):
+    """Every logit equal: every candidate ties, lowest token ids win, budget spent at layer 2."""
+    cfg = small(name="const", V=20000, logits_dtype=dtype, K=5, N=20, Dmax=6)
+    pool = custom_pool(cfg, lambda b, i: np.full(cfg.V, 1.5))
+    gpu = H.run_gpu_step(cfg, pool=pool, with_attention=False)
+    ref = H.run_oracle_step(cfg, pool=pool, with_attention=False)
+    H.compare_step(cfg, gpu, ref)
+    assert list(gpu["token"][0, 1:6]) == [0, 1, 2, 3, 4]
+
+
+def test_one_hot_rows_deep_chain():
+    cfg = small(name="onehot", V=30000, logits_dtype="bf16", K=4, N=24, Dmax=64)
+
+    def fill(b, i):
+        x = np.zeros(cfg.V); x[(977 * (i + 1)) % cfg.V] = 40.0
+        return x
+
+    pool = custom_pool(cfg, fill)
+    gpu = H.run_gpu_step(cfg, pool=pool, with_attention=False)
+    ref = H.run_oracle_step(cfg, pool=pool, with_attention=False)
+    H.compare_step(cfg, gpu, ref)
+    assert gpu["depth"][0, :24].max() == 24 - 4
+
+
+def test_sorted_rows_and_neg_inf_entries():
+    """Monotone rows (all of a chunk's best logits sit in one lane) and rows that are mostly -inf."""
+    cfg = small(name="sorted", V=17000, logits_dtype="f32", K=8, N=30, Dmax=8)
+    rng = np.random.default_rng(5)
+
+    def fill(b, i):
+        if i % 3 == 0:
+            return np.linspace(-3, 3, cfg.V) * (1 + 0.1 * i)
+        if i % 3 == 1:
+            return np.linspace(4, -4, cfg.V) * (1 + 0.05 * i)
+        x = np.full(cfg.V, -np.inf)
+        idx = rng.choice(cfg.V, size=5, replace=False)
+        x[idx] = rng.normal(size=5)
+        return x
+
+    pool = custom_pool(cfg, fill)
+    gpu = H.run_gpu_step(cfg, pool=pool, with_attention=False)
+    ref = H.run_oracle_step(cfg, pool=pool, with_attention=False)
+    if min(t.margin for t in ref["trees"]) <= H.MARGIN_TOL:
+        pytest.skip("not admissible")
+    H.compare_step(cfg, gpu, ref)
+
+
+def test_vocab_smaller_than_k():
+    cfg = small(name="tinyv", V=8, logits_dtype="f32", K=12, N=14, Dmax=4, mu=1e-30)
+    seeds = [cfg.seed]
+    pool = H.build_pool(cfg, seeds)
+    gpu = H.run_gpu_step(cfg, seeds, pool=pool, with_attention=False)
+    ref = H.run_oracle_step(cfg, seeds, pool=pool, with_attention=False)
+    if min(t.margin for t in ref["trees"]) <= H.MARGIN_TOL:
+        pytest.skip("not admissible")
+    H.compare_step(cfg, gpu, ref)
+    assert (gpu["cand_token"][0, 0, 8:] == -1).all()
+
+
+def test_nan_row_sets_status_and_stops_sequence():
+    cfg = small(name="nan", V=5000, logits_dtype="f32", K=3, N=20, Dmax=6, B=2)
+    seeds = [cfg.seed, cfg.seed]
+    pool = H.build_pool(cfg, seeds)
+    pool[1, 2, 1234] = np.nan
+    gpu = H.run_gpu_step(cfg, seeds, pool=pool, with_attention=False)
+    ref = H.run_oracle_step(dataclasses.replace(cfg, B=1), seeds[:1], pool=pool[:1], with_attention=False)
+    assert int(gpu["status"][1]) & 4
+    assert int(gpu["n_nodes"][1]) == 1 + cfg.K          # stopped after the layer that read the bad row
+    assert int(gpu["frontier_count"][1]) == 0
+    if ref["trees"][0].margin > H.MARGIN_TOL:
+        H.compare_tree(cfg, {k: v[:1] for k, v in gpu.items()}, ref["trees"])
+
+
+def test_budget_of_one_and_two():
+    for N in (1, 2):
+        cfg = small(name="n%d" % N, V=2048, logits_dtype="bf16", K=4, N=N, Dmax=4)
+        gpu = H.run_gpu_step(cfg, [cfg.seed], with_attention=False)
+        ref = H.run_oracle_step(cfg, [cfg.seed], with_attention=False)
+        H.compare_step(cfg, gpu, ref)
+
+
+def test_integer_outputs_are_reproducible_run_to_run():
+    cfg = small(name="repro", V=50000, logits_dtype="bf16", K=10, N=60, Dmax=12, B=2, recipe=("gauss", 0.5, 8.0))
+    seeds = [cfg.seed, cfg.seed]
+    pool = H.build_pool(cfg, seeds)
+    a = H.run_gpu_step(cfg, seeds, pool=pool, with_attention=False)
+    for _ in range(3):
+        b = H.run_gpu_step(cfg, seeds, pool=pool, with_attention=False)
+        for key in ("token", "parent", "depth", "n_nodes", "mask", "cand_token", "row_lse", "logp"):
+            np.testing.assert_array_equal(a[key], b[key])
+
+
+# ----------------------------------------------------------------------------- attention only
+def attention_case(B, n_list, Hq, Hkv, Dh, L_list, seed, parents=None):
+    """Random trees (random parent pointers) straight into mask + attention, ragged prefix lengths."""
+    import torch
+    import paper_2601_07353_amd as T
+    from oracle import talon_oracle as O
+    rng = np.random.default_rng(seed)
+    N = max(n_list)
+    N_pad = (N + 63) // 64 * 64
+    Lmax = max(L_list)
+    st = T.TreeState(B, N)
+    parent = np.full((B, N_pad), -1, dtype=np.int32)
+    for b in range(B):
+        for i in range(1, n_list[b]):
+            parent[b, i] = rng.integers(0, i) if parents is None else parents[b][i]
+    st.parent.copy_(torch.from_numpy(parent))
+    st.n_nodes.copy_(torch.tensor(n_list, dtype=torch.int32))
+    mask = torch.zeros(B, N_pad, N_pad // 64, dtype=torch.int64, device="cuda")
+    T.talon_build_tree_mask(st, mask)
+
+    def bits(shape):
+        return f32_to_bf16_bits(rng.standard_normal(shape, dtype=np.float32))
+
+    q, kt, vt = bits((B, N_pad, Hq, Dh)), bits((B, N_pad, Hkv, Dh)), bits((B, N_pad, Hkv, Dh))
+    kp, vp = bits((B, max(Lmax, 1), Hkv, Dh)), bits((B, max(Lmax, 1), Hkv, Dh))
+    out = torch.zeros(B, N_pad, Hq, Dh, dtype=torch.bfloat16, device="cuda")
+    lse = torch.zeros(B, N_pad, Hq, dtype=torch.float32, device="cuda")
+    nb = T.talon_tree_attention_workspace_bytes(B, N_pad, Hq, Hkv, Dh, Lmax)
+    ws = torch.empty(max(nb, 256), dtype=torch.uint8, device="cuda")
+    plen = torch.tensor(L_list, dtype=torch.int32, device="cuda")
+    T.talon_tree_attention(H.bf16_to_device(q), H.bf16_to_device(kp), H.bf16_to_device(vp), H.bf16_to_device(kt),
+                           H.bf16_to_device(vt), mask, st.n_nodes, plen, Lmax, out, lse, ws)
+    torch.cuda.synchronize()
+    got, got_lse = out.float().cpu().numpy(), lse.cpu().numpy()
+    gmask = mask.cpu().numpy().view(np.uint64)
+    worst = 0.0
+    for b in range(B):
+        n, L = n_list[b], L_list[b]
+        m = O.build_tree_mask(list(parent[b, :n]))
+        np.testing.assert_array_equal(gmask[b], O.mask_to_words(m, N_pad))
+        f = H.bf16_bits_to_f64
+        want, wlse = O.tree_attention(f(q[b, :n]), f(kp[b, :L]), f(vp[b, :L]), f(kt[b, :n]), f(vt[b, :n]), m)
+        err = np.abs(got[b, :n] - want).max()
+        worst = max(worst, err)
+        assert err <= H.ATTN_ATOL, (b, err)
+        assert np.abs(got_lse[b, :n] - wlse).max() <= 2e-3
+        assert not got[b, n:].any()
+    return worst
+
+
+@pytest.mark.parametrize("B,n_list,Hq,Hkv,Dh,L_list", [
+    (1, [16], 4, 4, 64, [128]),
+    (2, [60, 37], 8, 2, 128, [300, 77]),        # GQA 4, ragged prefix lengths, ragged tiles
+    (1, [1], 4, 2, 64, [0]),                    # root only, empty prefix: output = own value
+    (3, [200, 130, 256], 4, 1, 128, [64, 1, 1000]),   # several tree tiles, G = 4
+    (1, [100], 16, 1, 64, [513]),               # G = 16
+    (2, [64, 65], 6, 2, 128, [4096, 63]),       # G = 3 (rows of a node straddle row blocks)
+])
+def test_tree_attention_random_trees(B, n_list, Hq, Hkv, Dh, L_list):
+    worst = attention_case(B, n_list, Hq, Hkv, Dh, L_list, seed=123)
+    print("worst abs err", worst)
+
+
+def test_tree_attention_chain_and_star():
+    n = 50
+    attention_case(1, [n], 8, 4, 128, [100], seed=5, parents=[[-1] + list(range(n - 1))])
+    attention_case(1, [n], 8, 4, 128, [100], seed=6, parents=[[-1] + [0] * (n - 1)])
+
+
+def test_tree_attention_strided_prefix_view():
+    """Prefix K/V given as a strided view of a larger cache (extra heads and tokens)."""
+    import torch
+    import paper_2601_07353_amd as T
+    from oracle import talon_oracle as O
+    rng = np.random.default_rng(9)
+    B, n, Hq, Hkv, Dh, L = 2, 20, 4, 2, 64, 150
+    N_pad = 64
+    st = T.TreeState(B, n)
+    parent = np.full((B, N_pad), -1, dtype=np.int32)
+    for b in range(B):
+        for i in range(1, n):
+            parent[b, i] = rng.integers(0, i)
+    st.parent.copy_(torch.from_numpy(parent)); st.n_nodes.fill_(n)
+    mask = torch.zeros(B, N_pad, 1, dtype=torch.int64, device="cuda")
+    T.talon_build_tree_mask(st, mask)
+    bits = lambda shape: f32_to_bf16_bits(rng.standard_normal(shape, dtype=np.float32))
+    q, kt, vt = bits((B, N_pad, Hq, Dh)), bits((B, N_pad, Hkv, Dh)), bits((B, N_pad, Hkv, Dh))
+    cache_k, cache_v = bits((B, 2 * L, Hkv + 3, Dh)), bits((B, 2 * L, Hkv + 3, Dh))
+    dk, dv = H.bf16_to_device(cache_k), H.bf16_to_device(cache_v)
+    kp, vp = dk[:, 10:10 + L, 1:1 + Hkv, :], dv[:, 10:10 + L, 1:1 + Hkv, :]
+    out = torch.zeros(B, N_pad, Hq, Dh, dtype=torch.bfloat16, device="cuda")
+    nb = T.talon_tree_attention_workspace_bytes(B, N_pad, Hq, Hkv, Dh, L)
+    ws = torch.empty(max(nb, 256), dtype=torch.uint8, device="cuda")
+    plen = torch.full((B,), L, dtype=torch.int32, device="cuda")
+    T.talon_tree_attention(H.bf16_to_device(q), kp, vp, H.bf16_to_device(kt), H.bf16_to_device(vt), mask,
+                           st.n_nodes, plen, L, out, None, ws)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy()
+    f = H.bf16_bits_to_f64
+    for b in range(B):
+        m = O.build_tree_mask(list(parent[b, :n]))
+        want, _ = O.tree_attention(f(q[b, :n]), f(cache_k[b, 10:10 + L, 1:1 + Hkv]), f(cache_v[b, 10:10 + L, 1:1 + Hkv]),
+                                   f(kt[b, :n]), f(vt[b, :n]), m)
+        assert np.abs(got[b, :n] - want).max() <= H.ATTN_ATOL

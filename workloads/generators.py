@@ -77,6 +77,22 @@ def zipf_row(V: int, alpha: float, a: int, c: int) -> np.ndarray:
     return (-alpha * np.log(rank.astype(np.float64))).astype(np.float32)
 
 
+def _zipf_keyed(g: np.random.Generator, V: int, alpha: float) -> np.ndarray:
+    """Zipf row with a per-row permutation and a per-row exponent within 2% of `alpha`.
+
+    Rows with exactly the same exponent are permutations of one another: they share one
+    log-sum-exp and one set of top logits, so candidates of different parents tie exactly in
+    real arithmetic and no finite-precision implementation can reproduce the order of those
+    ties.  The small jitter keeps the Zipf shape and makes every comparison a real one.
+    """
+    while True:
+        a = int(g.integers(1, V))
+        if math.gcd(a, V) == 1:
+            break
+    c = int(g.integers(0, V))
+    return zipf_row(V, alpha * (1.0 + 0.02 * g.uniform(-1.0, 1.0)), a, c)
+
+
 def _recipe_for(cfg: WorkloadConfig, b: int):
     r = cfg.recipe
     if isinstance(r[0], tuple):
@@ -96,21 +112,11 @@ def logits_row(cfg: WorkloadConfig, seed: int, b: int, node: int) -> np.ndarray:
         x = g.standard_normal(cfg.V, dtype=np.float32) * np.float32(beta)
     elif rec[0] == "zipf_mix":
         if node % 2 == 0:
-            while True:
-                a = int(g.integers(1, cfg.V))
-                if math.gcd(a, cfg.V) == 1:
-                    break
-            c = int(g.integers(0, cfg.V))
-            x = zipf_row(cfg.V, rec[1], a, c)
+            x = _zipf_keyed(g, cfg.V, rec[1])
         else:
             x = g.standard_normal(cfg.V, dtype=np.float32) * np.float32(rec[2])
     elif rec[0] == "zipf":
-        while True:
-            a = int(g.integers(1, cfg.V))
-            if math.gcd(a, cfg.V) == 1:
-                break
-        c = int(g.integers(0, cfg.V))
-        x = zipf_row(cfg.V, rec[1], a, c)
+        x = _zipf_keyed(g, cfg.V, rec[1])
     else:
         raise ValueError(rec)
     return _store(x, cfg.logits_dtype)
