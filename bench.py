@@ -1,0 +1,228 @@
+#!/usr/bin/env python3
+"""Benchmark of the Talon hot path on one MI355X.
+
+One step = tree init + the whole budget-driven expansion loop (vocab scan + budget
+selection per layer) + tree-mask build + one tree-attention call, for one batch of
+synthetic inputs already resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c2]
+
+The default workload is the Llama-3-8B-shaped configuration the headline metric is quoted
+on.  Inputs rotate over several independently generated pools and KV buffers so that
+consecutive steps do not find their rows in the 256 MB Infinity Cache.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="c2", help="c1..c5 (default c2: the headline workload)")
+    ap.add_argument("--slots", type=int, default=0, help="rotating input sets (0 = enough to exceed 512 MB)")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget for the oracle timing sample")
+    return ap.parse_args()
+
+
+class Slot:
+    """One set of inputs (logits pool, Q/K/V) on the device."""
+
+    def __init__(self, cfg, seed, torch, H):
+        import numpy as np
+        from workloads import attention_inputs
+        seeds = [seed] * cfg.B
+        self.seed = seed
+        pool = H.build_pool(cfg, seeds)
+        self.logits = H.to_device_logits(pool)
+        xs = [attention_inputs(cfg, seed, b) for b in range(cfg.B)]
+        self.q = H.bf16_to_device(np.stack([x["q"] for x in xs]))
+        self.kp = H.bf16_to_device(np.stack([x["k_prefix"] for x in xs]))
+        self.vp = H.bf16_to_device(np.stack([x["v_prefix"] for x in xs]))
+        self.kt = H.bf16_to_device(np.stack([x["k_tree"] for x in xs]))
+        self.vt = H.bf16_to_device(np.stack([x["v_tree"] for x in xs]))
+        self.graph = None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding or collectives are part of it); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2601_07353_amd as T
+    from tests import harness as H
+    from workloads import CONFIGS
+
+    cfg = CONFIGS[args.config.lower()]
+    T.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    elem = cfg.elem_bytes
+    pool_bytes = cfg.B * cfg.N_pad * cfg.V * elem
+    kv_bytes = 2 * cfg.B * cfg.L * cfg.Hkv * cfg.Dh * 2
+    n_slots = args.slots or max(2, min(32, int(np.ceil(512e6 / (pool_bytes + kv_bytes)))))
+    slots = [Slot(cfg, cfg.seed + 1000 * i, torch, H) for i in range(n_slots)]
+
+    st = T.TreeState(cfg.B, cfg.N)
+    cand = T.Candidates(cfg.B, st.N_pad, cfg.K)
+    dt = T.TALON_DTYPE_F32 if cfg.logits_dtype == "f32" else T.TALON_DTYPE_BF16
+    ws_expand = T.make_expand_workspace(cfg.B, st.N_pad, cfg.V, cfg.K, dt)
+    roots = torch.from_numpy(H.root_tokens(cfg)).cuda()
+    mask = torch.zeros(cfg.B, st.N_pad, st.N_pad // 64, dtype=torch.int64, device=dev)
+    out = torch.zeros(cfg.B, st.N_pad, cfg.Hq, cfg.Dh, dtype=torch.bfloat16, device=dev)
+    plen = torch.full((cfg.B,), cfg.L, dtype=torch.int32, device=dev)
+    nb = T.talon_tree_attention_workspace_bytes(cfg.B, st.N_pad, cfg.Hq, cfg.Hkv, cfg.Dh, cfg.L)
+    ws_attn = torch.empty(max(nb, 256), dtype=torch.uint8, device=dev)
+
+    def expand(s):
+        T.talon_tree_init(st, roots)
+        T.talon_expand_tree(s.logits, st, cfg.K, cfg.mu, cfg.K, 1, cfg.Dmax, cand, ws_expand)
+
+    def attention(s):
+        T.talon_tree_attention(s.q, s.kp, s.vp, s.kt, s.vt, mask, st.n_nodes, plen, cfg.L, out, None, ws_attn)
+
+    def step(s):
+        expand(s)
+        T.talon_build_tree_mask(st, mask)
+        attention(s)
+
+    # ---- warmup (also records the per-slot work: rows scanned, attention FLOPs)
+    rows_scanned, attn_flops, n_nodes_mean = [], [], []
+    for i in range(max(args.warmup, n_slots)):
+        s = slots[i % n_slots]
+        step(s)
+        if i < n_slots:
+            torch.cuda.synchronize()
+            n = st.n_nodes.cpu().numpy().astype(np.int64)
+            fc = st.frontier_count.cpu().numpy().astype(np.int64)
+            depth = st.depth.cpu().numpy()
+            rows_scanned.append(int((n - fc).sum()))
+            keys = sum(int((cfg.L + depth[b, :n[b]] + 1).sum()) for b in range(cfg.B))
+            attn_flops.append(4.0 * cfg.Hq * cfg.Dh * keys)
+            n_nodes_mean.append(float(n.mean()))
+    torch.cuda.synchronize()
+
+    use_graph = not args.no_graph
+    if use_graph:
+        for s in slots:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                step(s)
+            s.graph = g
+        for s in slots:
+            s.graph.replay()
+        torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        s = slots[i % n_slots]
+        if use_graph:
+            s.graph.replay()
+        else:
+            step(s)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    steps_per_s = args.steps / (t1 - t0)
+
+    # ---- kernel timing region: the same K steps launched eagerly with HIP events around the
+    # expansion loop and around the tree-attention call (events on the launch stream)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    for i in range(args.steps):
+        s = slots[i % n_slots]
+        e = ev[i]
+        e[0].record(); expand(s); e[1].record()
+        T.talon_build_tree_mask(st, mask)
+        e[2].record(); attention(s); e[3].record()
+    torch.cuda.synchronize()
+    expand_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    attn_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in ev]))
+
+    used = [i % n_slots for i in range(args.steps)]
+    mean_rows = float(np.mean([rows_scanned[u] for u in used]))
+    mean_flops = float(np.mean([attn_flops[u] for u in used]))
+    scan_bytes = mean_rows * cfg.V * elem
+    attn_bytes = (2.0 * cfg.B * cfg.L * cfg.Hkv * cfg.Dh * 2 +
+                  2.0 * float(np.mean(n_nodes_mean)) * cfg.B * (cfg.Hq + cfg.Hkv) * cfg.Dh * 2)
+
+    kernels = {
+        "expand_loop": {"ms": expand_ms, "rows_scanned": mean_rows, "bytes": scan_bytes,
+                        "GBps": scan_bytes / (expand_ms * 1e-3) / 1e9 if expand_ms > 0 else None,
+                        "launches": 2 * min(cfg.Dmax, cfg.N - 1)},
+        "tree_attention": {"ms": attn_ms, "flops": mean_flops, "bytes": attn_bytes,
+                           "TFLOPs": mean_flops / (attn_ms * 1e-3) / 1e12 if attn_ms > 0 else None},
+    }
+    if attn_ms >= expand_ms / max(1, min(cfg.Dmax, cfg.N - 1)):
+        # dominant single kernel: tree attention (a dense bf16 contraction)
+        ach = mean_flops / (attn_ms * 1e-3) / 1e12
+        roofline = {"kernel": "tree_attention_kernel", "bound": "mfma", "achieved": ach,
+                    "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
+                    "traffic": None}
+    else:
+        per_launch_ms = expand_ms / min(cfg.Dmax, cfg.N - 1)
+        ach = scan_bytes / min(cfg.Dmax, cfg.N - 1) / (per_launch_ms * 1e-3) / 1e9
+        roofline = {"kernel": "expand_kernel", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None}
+
+    result = {
+        "metric": "tree expand+verify steps/s", "value": steps_per_s, "unit": "steps/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if cfg.logits_dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "B": cfg.B, "vocab": cfg.V, "K": cfg.K, "N": cfg.N, "Dmax": cfg.Dmax,
+                   "mu": cfg.mu, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "Dh": cfg.Dh, "prefix_len": cfg.L,
+                   "input_slots": n_slots, "hip_graph": use_graph},
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, args.cpu_seconds, H)
+    print(json.dumps(result))
+
+
+def cpu_baseline(cfg, budget_s, H):
+    """The CPU oracle, as it stands, timed on this host on whole steps of the same workload."""
+    from threadpoolctl import threadpool_limits
+    n_done, t_total, seed = 0, 0.0, cfg.seed
+    with threadpool_limits(limits=1):
+        while True:
+            seeds = [seed + 1000 * n_done] * cfg.B
+            pool = H.build_pool(cfg, seeds)           # input generation is not timed
+            from workloads import attention_inputs
+            attn = [attention_inputs(cfg, seeds[b], b) for b in range(cfg.B)]
+            t0 = time.perf_counter()
+            H.run_oracle_step(cfg, seeds, pool=pool, attn=attn)
+            t_total += time.perf_counter() - t0
+            n_done += 1
+            if t_total >= budget_s or n_done >= 50:
+                break
+    return {"value": n_done / t_total, "unit": "steps/s", "cores": 1, "kind": "oracle",
+            "sample": "%d whole steps of %s (expansion + mask + attention over all nodes and heads), "
+                      "numpy fp64, BLAS pinned to one thread" % (n_done, cfg.name)}
+
+
+if __name__ == "__main__":
+    main()

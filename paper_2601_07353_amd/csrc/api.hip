@@ -124,11 +124,24 @@ ExpandArgs make_expand_args(const void* logits, int64_t row_stride, int64_t seq_
   return a;
 }
 
-// Workgroups for the scan: enough to hold every (row, chunk) item of the largest possible
-// layer, capped at 8 resident workgroups on each of the 256 compute units.
-int expand_grid(const talon_tree_state* st, int chunks) {
-  const long long rows = static_cast<long long>(st->B) * (st->N > 1 ? st->N - 1 : 1);
-  long long items = rows * chunks;
+// Workgroups for the scan of layer `layer` (-1: unknown): one per (row, chunk) item of the
+// widest frontier that layer can have, capped at 8 resident workgroups on each of the 256
+// compute units.  Layer 0 has the root only; every later frontier is bounded by k children
+// per parent, by K_init on top-K layers and by the budget left after one node per earlier layer.
+int expand_grid(const talon_tree_state* st, int chunks, int layer, int k, int K_init, int init_layers) {
+  long long f = st->N > 1 ? st->N - 1 : 1;
+  if (layer >= 0) {
+    long long w = 1;
+    for (int d = 1; d <= layer; ++d) {
+      w *= k;
+      if (d - 1 < init_layers && w > K_init) w = K_init;
+      const long long left = st->N - d;
+      if (w > left) w = left;
+      if (w < 1) w = 1;
+    }
+    f = w;
+  }
+  long long items = static_cast<long long>(st->B) * f * chunks;
   if (items > 2048) items = 2048;
   if (items < 1) items = 1;
   return static_cast<int>(items);
@@ -172,7 +185,7 @@ int talon_expand_layer(const void* logits, int dtype, int64_t row_stride, int64_
   if (rc) return rc;
   const ExpandArgs a = make_expand_args(logits, row_stride, seq_stride, row_mode, st, vocab, k, cand_token,
                                         cand_logit, cand_prob, cand_edge_logp, row_max, row_lse, workspace, L);
-  return check_hip(launch_expand(a, dtype, expand_grid(st, L.chunks), static_cast<hipStream_t>(stream)), "expand launch");
+  return check_hip(launch_expand(a, dtype, expand_grid(st, L.chunks, -1, k, 0, 0), static_cast<hipStream_t>(stream)), "expand launch");
 }
 
 int talon_select_budget(const talon_tree_state* st, int32_t k, const int32_t* cand_token, const float* cand_prob,
@@ -202,12 +215,11 @@ int talon_expand_tree(const void* logits, int dtype, int64_t row_stride, int64_t
   SelectArgs sa;
   sa.st = *st; sa.k = k; sa.cand_token = cand_token; sa.cand_prob = cand_prob; sa.cand_edge_logp = cand_edge_logp;
   sa.log_mu = log(static_cast<double>(mu)); sa.K_init = K_init; sa.init_layers = init_layers; sa.max_depth = max_depth;
-  const int grid = expand_grid(st, L.chunks);
   hipStream_t s = static_cast<hipStream_t>(stream);
   // a tree of N nodes has at most N-1 layers: later iterations could not add anything
   const int layers = max_depth < st->N - 1 ? max_depth : (st->N > 1 ? st->N - 1 : 0);
   for (int d = 0; d < layers; ++d) {
-    rc = check_hip(launch_expand(ea, dtype, grid, s), "expand launch");
+    rc = check_hip(launch_expand(ea, dtype, expand_grid(st, L.chunks, d, k, K_init, init_layers), s), "expand launch");
     if (rc) return rc;
     rc = check_hip(launch_select(sa, s), "select launch");
     if (rc) return rc;

@@ -6,31 +6,89 @@
 
 namespace talon {
 
-__device__ __forceinline__ float wave_max_f32(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-  return v;
+// ---- cross-lane moves without the LDS crossbar: DPP inside a row of 16 lanes, lane-swap
+// instructions across rows.  Each helper returns the value held by the partner lane.
+template <int CTRL>
+__device__ __forceinline__ int dpp_i32(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, false);
 }
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // lane i <- lane 7-i of its group of 8
+constexpr int kDppMirror = 0x140;     // lane i <- lane 15-i of its row
 
-__device__ __forceinline__ double wave_sum_f64(double v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-  return v;
+// All-reduce over the 64 lanes; OP(a, b) must be commutative and associative on 32-bit ints
+// reinterpreted by the caller.  The two swap steps return {own, partner} in some order.
+#define TALON_WAVE_ALLREDUCE_32(v, COMBINE)                                   \
+  do {                                                                        \
+    v = COMBINE(v, dpp_i32<kDppXor1>(v));                                     \
+    v = COMBINE(v, dpp_i32<kDppXor2>(v));                                     \
+    v = COMBINE(v, dpp_i32<kDppHalfMirror>(v));                               \
+    v = COMBINE(v, dpp_i32<kDppMirror>(v));                                   \
+    auto p16_ = __builtin_amdgcn_permlane16_swap(v, v, false, false);         \
+    v = COMBINE(static_cast<int>(p16_[0]), static_cast<int>(p16_[1]));        \
+    auto p32_ = __builtin_amdgcn_permlane32_swap(v, v, false, false);         \
+    v = COMBINE(static_cast<int>(p32_[0]), static_cast<int>(p32_[1]));        \
+  } while (0)
+
+__device__ __forceinline__ int combine_max_f32(int a, int b) {
+  return __float_as_int(fmaxf(__int_as_float(a), __int_as_float(b)));
+}
+__device__ __forceinline__ int combine_add_i32(int a, int b) { return a + b; }
+
+__device__ __forceinline__ float wave_max_f32(float x) {
+  int v = __float_as_int(x);
+  TALON_WAVE_ALLREDUCE_32(v, combine_max_f32);
+  return __int_as_float(v);
 }
 
 __device__ __forceinline__ int wave_sum_i32(int v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  TALON_WAVE_ALLREDUCE_32(v, combine_add_i32);
   return v;
 }
 
-__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    unsigned long long w = __shfl_xor(v, o);
-    v = w > v ? w : v;
-  }
-  return v;
+// 64-bit all-reduces move the two halves separately.
+#define TALON_WAVE_ALLREDUCE_64(T, x, COMBINE)                                               \
+  do {                                                                                       \
+    union { T t; int w[2]; } a_, b_;                                                         \
+    a_.t = x;                                                                                \
+    b_.w[0] = dpp_i32<kDppXor1>(a_.w[0]); b_.w[1] = dpp_i32<kDppXor1>(a_.w[1]);              \
+    a_.t = COMBINE(a_.t, b_.t);                                                              \
+    b_.w[0] = dpp_i32<kDppXor2>(a_.w[0]); b_.w[1] = dpp_i32<kDppXor2>(a_.w[1]);              \
+    a_.t = COMBINE(a_.t, b_.t);                                                              \
+    b_.w[0] = dpp_i32<kDppHalfMirror>(a_.w[0]); b_.w[1] = dpp_i32<kDppHalfMirror>(a_.w[1]);  \
+    a_.t = COMBINE(a_.t, b_.t);                                                              \
+    b_.w[0] = dpp_i32<kDppMirror>(a_.w[0]); b_.w[1] = dpp_i32<kDppMirror>(a_.w[1]);          \
+    a_.t = COMBINE(a_.t, b_.t);                                                              \
+    {                                                                                        \
+      auto l_ = __builtin_amdgcn_permlane16_swap(a_.w[0], a_.w[0], false, false);            \
+      auto h_ = __builtin_amdgcn_permlane16_swap(a_.w[1], a_.w[1], false, false);            \
+      a_.w[0] = l_[0]; a_.w[1] = h_[0]; b_.w[0] = l_[1]; b_.w[1] = h_[1];                    \
+      a_.t = COMBINE(a_.t, b_.t);                                                            \
+    }                                                                                        \
+    {                                                                                        \
+      auto l_ = __builtin_amdgcn_permlane32_swap(a_.w[0], a_.w[0], false, false);            \
+      auto h_ = __builtin_amdgcn_permlane32_swap(a_.w[1], a_.w[1], false, false);            \
+      a_.w[0] = l_[0]; a_.w[1] = h_[0]; b_.w[0] = l_[1]; b_.w[1] = h_[1];                    \
+      a_.t = COMBINE(a_.t, b_.t);                                                            \
+    }                                                                                        \
+    x = a_.t;                                                                                \
+  } while (0)
+
+__device__ __forceinline__ double combine_add_f64(double a, double b) { return a + b; }
+__device__ __forceinline__ unsigned long long combine_max_u64(unsigned long long a, unsigned long long b) {
+  return a > b ? a : b;
+}
+
+// Note: the lane order of the additions is fixed, so the sum is reproducible run to run.
+__device__ __forceinline__ double wave_sum_f64(double x) {
+  TALON_WAVE_ALLREDUCE_64(double, x, combine_add_f64);
+  return x;
+}
+
+__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long x) {
+  TALON_WAVE_ALLREDUCE_64(unsigned long long, x, combine_max_u64);
+  return x;
 }
 
 // Inclusive prefix sum across the 64 lanes of a wavefront.

@@ -25,6 +25,15 @@ namespace {
 
 constexpr float kNegInf = -__builtin_huge_valf();
 
+// Phase timestamps (100 MHz wall clock) of workgroup 0, and of the merging workgroup for
+// phases >= 8; compiled only into tuning builds with -DTALON_PHASE_TIMING.
+#ifdef TALON_PHASE_TIMING
+__device__ unsigned long long g_phase[16];
+#define PHASE(i) do { if (threadIdx.x == 0 && (blockIdx.x == 0 || ((i) >= 8 && (i) <= 9))) g_phase[i] = wall_clock64(); } while (0)
+#else
+#define PHASE(i) do { } while (0)
+#endif
+
 template <int EPL>
 struct RowVec;
 template <>
@@ -58,6 +67,33 @@ struct RowVec<8> {  // bf16: one 16-byte vector = 8 logits
   }
 };
 
+// Partial results cross workgroups (and the per-XCD L2 caches) inside one launch.  They are
+// written and read with agent-scope atomic accesses, which go to the device-coherent level
+// directly, so no whole-cache write-back or invalidate is needed around the ticket.
+template <typename T>
+__device__ __forceinline__ void store_agent(T* p, T v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename T>
+__device__ __forceinline__ T load_agent(const T* p) {
+  return __hip_atomic_load(const_cast<T*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Number of keys in s[0..n) greater than key (LDS broadcast reads, 8 in flight).
+__device__ __forceinline__ int count_greater(const unsigned long long* s, int n, unsigned long long key) {
+  int r = 0;
+  int j = 0;
+  for (; j + 8 <= n; j += 8) {
+    unsigned long long v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = s[j + u];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) r += (v[u] > key) ? 1 : 0;
+  }
+  for (; j < n; ++j) r += (s[j] > key) ? 1 : 0;
+  return r;
+}
+
 __device__ __forceinline__ unsigned long long make_key(float x, int token) {
   return (static_cast<unsigned long long>(sortable_u32(x)) << 32) |
          static_cast<unsigned long long>(0xFFFFFFFFu - static_cast<uint32_t>(token));
@@ -81,6 +117,7 @@ __global__ __launch_bounds__(kThreads) void expand_kernel(ExpandArgs a) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
+  PHASE(0);
 
   // ---- frontier sizes of all sequences -> item map (identical in every workgroup)
   {
@@ -90,7 +127,11 @@ __global__ __launch_bounds__(kThreads) void expand_kernel(ExpandArgs a) {
     for (int j = 0; j < 4; ++j) {
       const int b = tid * 4 + j;
       int c = 0;
-      if (b < a.B && !(a.status[b] & kDoneMask)) c = a.frontier_count[b];
+      if (b < a.B) {  // both loads are issued together; the select below is register-only
+        const uint32_t stat = a.status[b];
+        const int fc = a.frontier_count[b];
+        c = (stat & kDoneMask) ? 0 : fc;
+      }
       cnt[j] = c;
       run += c;
     }
@@ -105,6 +146,7 @@ __global__ __launch_bounds__(kThreads) void expand_kernel(ExpandArgs a) {
     if (tid == 0) s_prefix[a.B] = total;
     __syncthreads();
   }
+  PHASE(1);
   const int total_rows = s_prefix[a.B];
   const long long n_items = static_cast<long long>(total_rows) * a.chunks;
   const int k = a.k;
@@ -139,6 +181,7 @@ __global__ __launch_bounds__(kThreads) void expand_kernel(ExpandArgs a) {
     float lane_max = kNegInf;
 #pragma unroll
     for (int i = 0; i < NX; ++i) lane_max = fmaxf(lane_max, x[i]);
+    PHASE(2);
     const float wmax = wave_max_f32(lane_max);
     float lane_sum = 0.f;
     if (wmax != kNegInf) {
@@ -162,6 +205,7 @@ __global__ __launch_bounds__(kThreads) void expand_kernel(ExpandArgs a) {
         v = (v == cur) ? kNegInf : v;
       }
     }
+    PHASE(3);
     __syncthreads();  // s_ncand = 0 visible; previous iteration's readers of s_keys are done
 
     // ---- push every logit >= tau (rare: about k per wavefront on ordinary rows)
@@ -182,6 +226,7 @@ __global__ __launch_bounds__(kThreads) void expand_kernel(ExpandArgs a) {
       }
     }
     __syncthreads();
+    PHASE(4);
     const int ncand = s_ncand;
     unsigned long long* pk = a.part_keys + (static_cast<size_t>(out_row) * a.chunks + ch) * k;
 
@@ -189,11 +234,10 @@ __global__ __launch_bounds__(kThreads) void expand_kernel(ExpandArgs a) {
       // rank by counting: keys are distinct (distinct tokens)
       for (int i = tid; i < ncand; i += kThreads) {
         const unsigned long long ki = s_keys[i];
-        int r = 0;
-        for (int j = 0; j < ncand; ++j) r += (s_keys[j] > ki) ? 1 : 0;
-        if (r < k) pk[r] = ki;
+        const int r = count_greater(s_keys, ncand, ki);
+        if (r < k) store_agent(pk + r, ki);
       }
-      if (tid >= ncand && tid < k) pk[tid] = 0ull;  // fewer than k logits in this chunk
+      if (tid >= ncand && tid < k) store_agent(pk + tid, 0ull);  // fewer than k logits in this chunk
     } else {
       // heavy ties: exact k rounds of workgroup arg-max over the registers
       unsigned long long prev = ~0ull;
@@ -211,15 +255,16 @@ __global__ __launch_bounds__(kThreads) void expand_kernel(ExpandArgs a) {
           }
         }
         best = block_max_u64(best, s_red_u64);
-        if (tid == 0) pk[r] = best;
+        if (tid == 0) store_agent(pk + r, best);
         prev = best;
         if (best == 0ull) {
-          if (tid > r && tid < k) pk[tid] = 0ull;
+          if (tid > r && tid < k) store_agent(pk + tid, 0ull);
           break;
         }
       }
     }
 
+    PHASE(5);
     // ---- chunk statistics
     if (tid == 0) {
       const float m = fmaxf(fmaxf(s_wmax[0], s_wmax[1]), fmaxf(s_wmax[2], s_wmax[3]));
@@ -227,42 +272,45 @@ __global__ __launch_bounds__(kThreads) void expand_kernel(ExpandArgs a) {
 #pragma unroll
       for (int w = 0; w < 4; ++w)
         if (s_wmax[w] != kNegInf) sum += s_wsum[w] * exp(static_cast<double>(s_wmax[w]) - static_cast<double>(m));
-      a.part_max[static_cast<size_t>(out_row) * a.chunks + ch] = m;
-      a.part_sum[static_cast<size_t>(out_row) * a.chunks + ch] = sum;
+      store_agent(a.part_max + static_cast<size_t>(out_row) * a.chunks + ch, m);
+      store_agent(a.part_sum + static_cast<size_t>(out_row) * a.chunks + ch, sum);
     }
 
+    PHASE(6);
     // ---- ticket: the workgroup that finishes the row's last chunk merges the row
-    __threadfence();
+    // every partial store of this workgroup has completed before the ticket is taken
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
     if (tid == 0) {
-      const int old = atomicAdd(&a.ticket[out_row], 1);
+      const int old = __hip_atomic_fetch_add(&a.ticket[out_row], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       s_last = (old == a.chunks - 1) ? 1 : 0;
     }
     __syncthreads();
+    PHASE(7);
     if (s_last) {
-      __threadfence();
+      PHASE(8);
       const float* pm = a.part_max + static_cast<size_t>(out_row) * a.chunks;
       const double* ps = a.part_sum + static_cast<size_t>(out_row) * a.chunks;
       const unsigned long long* keys = a.part_keys + static_cast<size_t>(out_row) * a.chunks * k;
       const int nkeys = a.chunks * k;
-      for (int i = tid; i < nkeys; i += kThreads) s_keys[i] = keys[i];
+      for (int i = tid; i < nkeys; i += kThreads) s_keys[i] = load_agent(keys + i);
       float m = kNegInf;
-      for (int c = tid; c < a.chunks; c += kThreads) m = fmaxf(m, pm[c]);
+      for (int c = tid; c < a.chunks; c += kThreads) m = fmaxf(m, load_agent(pm + c));
       m = block_max_f32(m, s_red_f32);  // barrier inside: s_keys staged
       double sum = 0.0;
       for (int c = tid; c < a.chunks; c += kThreads) {
-        const float mc = pm[c];
-        if (mc != kNegInf) sum += ps[c] * exp(static_cast<double>(mc) - static_cast<double>(m));
+        const float mc = load_agent(pm + c);
+        if (mc != kNegInf) sum += load_agent(ps + c) * exp(static_cast<double>(mc) - static_cast<double>(m));
       }
       sum = block_sum_f64(sum, s_red_f64);
+      PHASE(9);
       const double lse = static_cast<double>(m) + log(sum);
       const int valid = a.vocab < k ? a.vocab : k;
       const size_t ob = static_cast<size_t>(out_row) * k;
       for (int i = tid; i < nkeys; i += kThreads) {
         const unsigned long long ki = s_keys[i];
         if (ki == 0ull) continue;
-        int r = 0;
-        for (int j = 0; j < nkeys; ++j) r += (s_keys[j] > ki) ? 1 : 0;
+        const int r = count_greater(s_keys, nkeys, ki);
         if (r < k) {
           const float lg = unsortable_f32(static_cast<uint32_t>(ki >> 32));
           const double edge = static_cast<double>(lg) - lse;
@@ -282,11 +330,13 @@ __global__ __launch_bounds__(kThreads) void expand_kernel(ExpandArgs a) {
         a.row_max[out_row] = m;
         a.row_lse[out_row] = lse;
         if (!(fabs(lse) <= 1.7e308)) atomicOr(&a.status[b], TALON_STATUS_BAD_ROW);
-        a.ticket[out_row] = 0;  // leave the workspace clean for the next layer
+        store_agent(a.ticket + out_row, 0);  // leave the workspace clean for the next layer
       }
     }
     __syncthreads();  // s_keys / s_last are reused by the next item
+    PHASE(10);
   }
+  PHASE(11);
 }
 
 __global__ __launch_bounds__(kThreads) void fill_zero_kernel(uint32_t* p, size_t n) {
@@ -322,6 +372,12 @@ hipError_t launch_expand(const ExpandArgs& a, int dtype, int grid, hipStream_t s
     hipLaunchKernelGGL(expand_kernel<8>, dim3(grid), dim3(kThreads), 0, s, a);
   return hipGetLastError();
 }
+
+#ifdef TALON_PHASE_TIMING
+extern "C" int talon_debug_read_phases(unsigned long long* host16) {
+  return static_cast<int>(hipMemcpyFromSymbol(host16, HIP_SYMBOL(g_phase), sizeof(unsigned long long) * 16));
+}
+#endif
 
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
   const size_t n = bytes / 4;
