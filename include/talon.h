@@ -41,7 +41,7 @@ extern "C" {
 /* limits */
 #define TALON_K_MAX 16     /* per-row candidate cap k                           */
 #define TALON_N_MAX 256    /* node budget N (root included)                     */
-#define TALON_B_MAX 1024   /* sequences per call                                */
+#define TALON_B_MAX 256    /* sequences per call                                */
 
 /* status[b] bits */
 #define TALON_STATUS_DONE_BUDGET 1u /* |T| reached N (Alg. 2 loop condition false)    */

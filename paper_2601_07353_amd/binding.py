@@ -24,7 +24,7 @@ TALON_DTYPE_F32 = 0
 TALON_DTYPE_BF16 = 1
 TALON_K_MAX = 16
 TALON_N_MAX = 256
-TALON_B_MAX = 1024
+TALON_B_MAX = 256
 TALON_STATUS_DONE_BUDGET = 1
 TALON_STATUS_DONE_DEPTH = 2
 TALON_STATUS_BAD_ROW = 4

@@ -3,6 +3,7 @@
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include "talon_internal.h"
@@ -106,6 +107,17 @@ int check_select_args(const talon_tree_state* st, int32_t k, const void* cand_to
   return TALON_OK;
 }
 
+// Items a scan launch aims for (tuning knob; TALON_EXPAND_TARGET_ITEMS overrides it).
+int expand_target_items() {
+  static int v = 0;
+  if (v == 0) {
+    const char* e = getenv("TALON_EXPAND_TARGET_ITEMS");
+    v = e ? atoi(e) : 2048;
+    if (v < 1) v = 2048;
+  }
+  return v;
+}
+
 ExpandArgs make_expand_args(const void* logits, int64_t row_stride, int64_t seq_stride, int row_mode,
                             const talon_tree_state* st, int32_t vocab, int32_t k, int32_t* cand_token,
                             float* cand_logit, float* cand_prob, double* cand_edge_logp, float* row_max,
@@ -113,6 +125,7 @@ ExpandArgs make_expand_args(const void* logits, int64_t row_stride, int64_t seq_
   ExpandArgs a;
   a.logits = logits; a.row_stride = row_stride; a.seq_stride = seq_stride; a.row_mode = row_mode;
   a.B = st->B; a.N_pad = st->N_pad; a.vocab = vocab; a.k = k; a.chunks = L.chunks;
+  a.target_items = expand_target_items();
   a.frontier_begin = st->frontier_begin; a.frontier_count = st->frontier_count; a.status = st->status;
   a.cand_token = cand_token; a.cand_logit = cand_logit; a.cand_prob = cand_prob;
   a.cand_edge_logp = cand_edge_logp; a.row_max = row_max; a.row_lse = row_lse;
@@ -125,8 +138,7 @@ ExpandArgs make_expand_args(const void* logits, int64_t row_stride, int64_t seq_
 }
 
 // Workgroups for the scan of layer `layer` (-1: unknown): one per (row, chunk) item of the
-// widest frontier that layer can have, capped at 8 resident workgroups on each of the 256
-// compute units.  Layer 0 has the root only; every later frontier is bounded by k children
+// widest frontier that layer can have, capped at the number of workgroups resident at once.  Layer 0 has the root only; every later frontier is bounded by k children
 // per parent, by K_init on top-K layers and by the budget left after one node per earlier layer.
 int expand_grid(const talon_tree_state* st, int chunks, int layer, int k, int K_init, int init_layers) {
   long long f = st->N > 1 ? st->N - 1 : 1;
@@ -142,7 +154,7 @@ int expand_grid(const talon_tree_state* st, int chunks, int layer, int k, int K_
     f = w;
   }
   long long items = static_cast<long long>(st->B) * f * chunks;
-  if (items > 2048) items = 2048;
+  if (items > 1024) items = 1024;   // 4 resident workgroups per compute unit; more only costs dispatch time
   if (items < 1) items = 1;
   return static_cast<int>(items);
 }

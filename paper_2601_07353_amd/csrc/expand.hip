@@ -2,20 +2,35 @@
 // pass over the row (candidate pool of Eq. 3 restricted to each parent's k best tokens;
 // Alg. 2 "gather" loop).  HBM-bandwidth bound: every logit is read exactly once.
 //
-// Work decomposition.  A row is cut into chunks of 16 KiB (8192 bf16 / 4096 f32 logits).
-// A fixed-size grid walks the (row, chunk) items of every unfinished sequence with a grid
-// stride, so the launch needs no host knowledge of the frontier sizes.  A workgroup
-// holds its whole chunk in registers (4 x 16-byte loads per thread, all in flight at
-// once) and produces a partial result: chunk max, sum of exp relative to that max, and
-// the chunk's k best (logit, token) keys.  The workgroup that completes a row's last
-// chunk (atomic ticket) merges the partials into the row's outputs.
+// Work decomposition.  A row is a sequence of 16 KiB blocks (8192 bf16 / 4096 f32 logits);
+// a block is what one workgroup holds in registers at a time (4 x 16-byte loads per
+// thread).  A row is cut into `chunks` runs of consecutive blocks; one (row, chunk) item is
+// streamed by one workgroup with the next block's loads in flight while the current one is
+// processed.  The number of chunks per row is chosen on the device from the total number
+// of frontier rows of the launch (few rows: many short chunks, so that a one-row layer
+// still spreads over the chip; many rows: one long chunk per row, so that the per-item
+// fixed work vanishes).  A fixed-size grid walks the items with a grid stride; nothing
+// about the frontier sizes is needed on the host.
+//
+// Inside a workgroup the four wavefronts stream independently, without barriers:
+//   - softmax: every lane keeps its own running max and a double-precision running sum of
+//     exp(logit - max), rescaled only when its max grows (rare after the first blocks);
+//   - top-k: every wavefront keeps its k best keys so far and a threshold tau.  The first
+//     group of 4 tiles sets tau to the k-th largest of the 64 per-lane maxima (at least k
+//     logits of the group reach it).  A lane whose 16-byte vector holds a logit that
+//     reaches tau drops the whole vector into an LDS buffer (a few instructions, no
+//     per-logit work); when the buffer runs full, and at the end, the buffered vectors are
+//     expanded, ranked against the k best, and tau rises to the new k-th best.  After such
+//     a cut a later logit EQUAL to the k-th best cannot enter (the wavefront meets tokens
+//     in ascending id order, so it loses the tie): tau becomes the next float above it,
+//     and rows full of ties cost nothing extra.
+// The workgroup then merges its four lists and statistics.  With one chunk per row it
+// writes the row's outputs directly; otherwise it stores a partial result and the
+// workgroup that completes the row's last chunk (atomic ticket) merges the partials.
 //
 // Exactness.  Ordering is by the 64-bit integer key (sortable(logit) << 32 | ~token), so
-// the order (logit descending, token ascending) is exact.  Per chunk, each wavefront finds
-// the k-th largest of its 64 per-lane maxima; every element of the chunk's top k is >=
-// that value, so only those are pushed to an LDS candidate list (a handful per chunk on
-// ordinary rows).  Rows with so many ties that the list overflows take an exact k-round
-// arg-max instead.
+// the order (logit descending, token ascending) is exact; floating point only enters the
+// softmax statistics.
 #include "device_utils.h"
 #include "talon_internal.h"
 
@@ -24,48 +39,55 @@ namespace talon {
 namespace {
 
 constexpr float kNegInf = -__builtin_huge_valf();
+constexpr int kHitTrigger = 64;                  // buffered vectors that trigger a cut before the next tile
+constexpr int kHitCap = kHitTrigger + 64;        // a tile adds at most 64 vectors
+constexpr int kSubBatch = 16;                    // vectors expanded per ranking round
+constexpr int kSubKeys = kSubBatch * 8 + TALON_K_MAX;  // keys ranked per round (<= 8 logits per vector)
 
-// Phase timestamps (100 MHz wall clock) of workgroup 0, and of the merging workgroup for
-// phases >= 8; compiled only into tuning builds with -DTALON_PHASE_TIMING.
+// Phase timestamps (100 MHz wall clock) of workgroup 0; compiled only into tuning builds
+// with -DTALON_PHASE_TIMING.
 #ifdef TALON_PHASE_TIMING
 __device__ unsigned long long g_phase[16];
-#define PHASE(i) do { if (threadIdx.x == 0 && (blockIdx.x == 0 || ((i) >= 8 && (i) <= 9))) g_phase[i] = wall_clock64(); } while (0)
+#define PHASE(i) do { if (threadIdx.x == 0 && blockIdx.x == 0) g_phase[i] = wall_clock64(); } while (0)
+#define PHASE_MAX(i) do { if (threadIdx.x == 0) atomicMax(&g_phase[i], wall_clock64()); } while (0)
 #else
 #define PHASE(i) do { } while (0)
+#define PHASE_MAX(i) do { } while (0)
 #endif
 
+// One 16-byte vector of a logits row, with -inf in the lanes past the end of the row.
 template <int EPL>
-struct RowVec;
-template <>
-struct RowVec<4> {  // f32: one 16-byte vector = 4 logits
-  __device__ static void load(const void* row, int e0, int vocab, float* x) {
-    const float* p = static_cast<const float*>(row);
-    if (e0 + 4 <= vocab) {
-      const float4 v = *reinterpret_cast<const float4*>(p + e0);
-      x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
-    } else {
+__device__ __forceinline__ uint4 load_vec(const char* row, int e0, int vocab) {
+  if (e0 + EPL <= vocab) return *reinterpret_cast<const uint4*>(row + static_cast<size_t>(e0) * (16 / EPL));
+  uint32_t w[4];
+  if constexpr (EPL == 4) {
+    const uint32_t* p = reinterpret_cast<const uint32_t*>(row);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) x[e] = (e0 + e < vocab) ? p[e0 + e] : kNegInf;
+    for (int e = 0; e < 4; ++e) w[e] = (e0 + e < vocab) ? p[e0 + e] : 0xFF800000u;
+  } else {
+    const uint16_t* p = reinterpret_cast<const uint16_t*>(row);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const uint32_t lo = (e0 + 2 * q < vocab) ? p[e0 + 2 * q] : 0xFF80u;
+      const uint32_t hi = (e0 + 2 * q + 1 < vocab) ? p[e0 + 2 * q + 1] : 0xFF80u;
+      w[q] = lo | (hi << 16);
     }
   }
-};
-template <>
-struct RowVec<8> {  // bf16: one 16-byte vector = 8 logits
-  __device__ static void load(const void* row, int e0, int vocab, float* x) {
-    const uint16_t* p = static_cast<const uint16_t*>(row);
-    if (e0 + 8 <= vocab) {
-      const uint4 v = *reinterpret_cast<const uint4*>(p + e0);
-      x[0] = __uint_as_float(v.x << 16); x[1] = __uint_as_float(v.x & 0xFFFF0000u);
-      x[2] = __uint_as_float(v.y << 16); x[3] = __uint_as_float(v.y & 0xFFFF0000u);
-      x[4] = __uint_as_float(v.z << 16); x[5] = __uint_as_float(v.z & 0xFFFF0000u);
-      x[6] = __uint_as_float(v.w << 16); x[7] = __uint_as_float(v.w & 0xFFFF0000u);
-    } else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e)
-        x[e] = (e0 + e < vocab) ? __uint_as_float(static_cast<uint32_t>(p[e0 + e]) << 16) : kNegInf;
-    }
+  return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+template <int EPL>
+__device__ __forceinline__ void unpack_vec(const uint4& v, float* x) {
+  if constexpr (EPL == 4) {
+    x[0] = __uint_as_float(v.x); x[1] = __uint_as_float(v.y);
+    x[2] = __uint_as_float(v.z); x[3] = __uint_as_float(v.w);
+  } else {
+    x[0] = __uint_as_float(v.x << 16); x[1] = __uint_as_float(v.x & 0xFFFF0000u);
+    x[2] = __uint_as_float(v.y << 16); x[3] = __uint_as_float(v.y & 0xFFFF0000u);
+    x[4] = __uint_as_float(v.z << 16); x[5] = __uint_as_float(v.z & 0xFFFF0000u);
+    x[6] = __uint_as_float(v.w << 16); x[7] = __uint_as_float(v.w & 0xFFFF0000u);
   }
-};
+}
 
 // Partial results cross workgroups (and the per-XCD L2 caches) inside one launch.  They are
 // written and read with agent-scope atomic accesses, which go to the device-coherent level
@@ -79,19 +101,30 @@ __device__ __forceinline__ T load_agent(const T* p) {
   return __hip_atomic_load(const_cast<T*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Number of keys in s[0..n) greater than key (LDS broadcast reads, 8 in flight).
+// Number of keys in s[0..n) greater than key (LDS broadcast reads, 4 in flight).
 __device__ __forceinline__ int count_greater(const unsigned long long* s, int n, unsigned long long key) {
   int r = 0;
   int j = 0;
-  for (; j + 8 <= n; j += 8) {
-    unsigned long long v[8];
+  for (; j + 4 <= n; j += 4) {
+    unsigned long long v[4];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = s[j + u];
+    for (int u = 0; u < 4; ++u) v[u] = s[j + u];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) r += (v[u] > key) ? 1 : 0;
+    for (int u = 0; u < 4; ++u) r += (v[u] > key) ? 1 : 0;
   }
   for (; j < n; ++j) r += (s[j] > key) ? 1 : 0;
   return r;
+}
+
+// Number of keys greater than `key` in a list sorted in descending order (zeros, if any, at
+// the end): binary search.
+__device__ __forceinline__ int count_greater_sorted(const unsigned long long* s, int n, unsigned long long key) {
+  int lo = 0, hi = n;   // invariant: s[i] > key for i < lo, s[i] <= key for i >= hi
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (s[mid] > key) lo = mid + 1; else hi = mid;
+  }
+  return lo;
 }
 
 __device__ __forceinline__ unsigned long long make_key(float x, int token) {
@@ -99,20 +132,94 @@ __device__ __forceinline__ unsigned long long make_key(float x, int token) {
          static_cast<unsigned long long>(0xFFFFFFFFu - static_cast<uint32_t>(token));
 }
 
+// Smallest float greater than x (x finite or -inf, not NaN): "v > x" is "v >= float_above(x)".
+__device__ __forceinline__ float float_above(float x) {
+  x = x + 0.0f;
+  const uint32_t u = __float_as_uint(x);
+  return __uint_as_float((u >> 31) ? u - 1u : u + 1u);
+}
+
+__device__ __forceinline__ float key_logit(unsigned long long key) {
+  return unsortable_f32(static_cast<uint32_t>(key >> 32));
+}
+
+// Write the outputs of one row from its candidate keys (in LDS) and softmax statistics.
+// `keys` holds `lists` lists of k keys, each sorted in descending order.
+__device__ __forceinline__ void write_row(const ExpandArgs& a, int b, int out_row, const unsigned long long* keys,
+                                          int lists, float m, double sum) {
+  const int tid = threadIdx.x;
+  const int k = a.k;
+  const double lse = static_cast<double>(m) + log(sum);
+  const size_t ob = static_cast<size_t>(out_row) * k;
+  // Rank by counting.  Thread t ranks keys t and t + 256 in one sweep over all keys (LDS
+  // broadcast reads, several in flight); a key's own list contributes its position.
+  const int nkeys = lists * k;
+  for (int i0 = 0; i0 < nkeys; i0 += 2 * kThreads) {
+    const int ia = i0 + tid, ib = i0 + kThreads + tid;
+    const unsigned long long ka = ia < nkeys ? keys[ia] : 0ull;
+    const unsigned long long kb = ib < nkeys ? keys[ib] : 0ull;
+    int ra = 0, rb = 0;
+    if (lists > 1) {
+      int j = 0;
+      for (; j + 4 <= nkeys; j += 4) {
+        unsigned long long v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = keys[j + u];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { ra += (v[u] > ka) ? 1 : 0; rb += (v[u] > kb) ? 1 : 0; }
+      }
+      for (; j < nkeys; ++j) { const unsigned long long v = keys[j]; ra += (v > ka) ? 1 : 0; rb += (v > kb) ? 1 : 0; }
+    } else {
+      ra = ia; rb = ib;   // a single sorted list
+    }
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const unsigned long long ki = h == 0 ? ka : kb;
+      const int r = h == 0 ? ra : rb;
+      if (ki != 0ull && r < k) {
+        const float lg = key_logit(ki);
+        const double edge = static_cast<double>(lg) - lse;
+        a.cand_token[ob + r] = static_cast<int32_t>(0xFFFFFFFFu - static_cast<uint32_t>(ki));
+        a.cand_logit[ob + r] = lg;
+        a.cand_edge_logp[ob + r] = edge;
+        a.cand_prob[ob + r] = static_cast<float>(exp(edge));
+      }
+    }
+  }
+  const int valid = a.vocab < k ? a.vocab : k;
+  if (tid >= valid && tid < k) {
+    a.cand_token[ob + tid] = -1;
+    a.cand_logit[ob + tid] = kNegInf;
+    a.cand_edge_logp[ob + tid] = -__builtin_huge_val();
+    a.cand_prob[ob + tid] = 0.f;
+  }
+  if (tid == 0) {
+    a.row_max[out_row] = m;
+    a.row_lse[out_row] = lse;
+    if (!(fabs(lse) <= 1.7e308)) atomicOr(&a.status[b], TALON_STATUS_BAD_ROW);
+  }
+}
+
 template <int EPL>
-__global__ __launch_bounds__(kThreads) void expand_kernel(ExpandArgs a) {
-  constexpr int NX = kScanTiles * EPL;          // logits per thread per chunk
-  constexpr int CHUNK = kThreads * NX;          // logits per chunk
+__global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
+  constexpr int NX = kScanTiles * EPL;          // logits per thread per block
+  constexpr int BLOCK = kThreads * NX;          // logits per block
   __shared__ int s_prefix[TALON_B_MAX + 1];     // exclusive prefix of frontier sizes
-  __shared__ unsigned long long s_keys[kMergeCap];  // chunk candidates, later merge staging
-  __shared__ unsigned long long s_red_u64[8];
+  __shared__ uint4 s_hitv[4][kHitCap];              // buffered vectors, per wavefront; later row-merge staging
+  __shared__ int s_hith[4][kHitCap];                //   ... and tile * 64 + lane of each
+  __shared__ unsigned long long s_ck[4][kSubKeys];  // ranking scratch per wavefront
+  __shared__ unsigned long long s_topw[4][TALON_K_MAX]; // k best keys of each wavefront, sorted
+  __shared__ unsigned long long s_top[TALON_K_MAX];
   __shared__ double s_red_f64[8];
   __shared__ float s_red_f32[8];
   __shared__ int s_red_i32[8];
   __shared__ float s_wmax[4];
   __shared__ double s_wsum[4];
-  __shared__ int s_ncand;
+  __shared__ int s_wcnt[4];
   __shared__ int s_last;
+  static_assert(sizeof(uint4) * 4 * kHitCap >= sizeof(unsigned long long) * kMergeCap,
+                "the vector buffers double as the row-merge staging array");
+  unsigned long long* s_keys = reinterpret_cast<unsigned long long*>(&s_hitv[0][0]);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -121,39 +228,40 @@ __global__ __launch_bounds__(kThreads) void expand_kernel(ExpandArgs a) {
 
   // ---- frontier sizes of all sequences -> item map (identical in every workgroup)
   {
-    int run = 0;  // B <= 1024: each thread owns up to 4 consecutive sequences
-    int cnt[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int b = tid * 4 + j;
-      int c = 0;
-      if (b < a.B) {  // both loads are issued together; the select below is register-only
-        const uint32_t stat = a.status[b];
-        const int fc = a.frontier_count[b];
-        c = (stat & kDoneMask) ? 0 : fc;
-      }
-      cnt[j] = c;
-      run += c;
+    static_assert(TALON_B_MAX <= kThreads, "one thread per sequence");
+    int c = 0;
+    if (tid < a.B) {  // both loads are issued together; the select below is register-only
+      const uint32_t stat = a.status[tid];
+      const int fc = a.frontier_count[tid];
+      c = (stat & kDoneMask) ? 0 : fc;
     }
     int total;
-    int base = block_exclusive_scan_i32(run, s_red_i32, &total);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int b = tid * 4 + j;
-      if (b < a.B) s_prefix[b] = base;
-      base += cnt[j];
-    }
+    const int base = block_exclusive_scan_i32(c, s_red_i32, &total);
+    if (tid < a.B) s_prefix[tid] = base;
     if (tid == 0) s_prefix[a.B] = total;
     __syncthreads();
   }
   PHASE(1);
+  PHASE_MAX(10);
   const int total_rows = s_prefix[a.B];
-  const long long n_items = static_cast<long long>(total_rows) * a.chunks;
+  if (total_rows == 0) return;
   const int k = a.k;
 
+  // ---- chunks per row from the width of this layer
+  const int blocks_per_row = a.chunks;
+  int chunks = (a.target_items + total_rows - 1) / total_rows;
+  chunks = chunks < 1 ? 1 : (chunks > blocks_per_row ? blocks_per_row : chunks);
+  const int bpc = (blocks_per_row + chunks - 1) / chunks;   // blocks per chunk
+  chunks = (blocks_per_row + bpc - 1) / bpc;
+  const long long n_items = static_cast<long long>(total_rows) * chunks;
+  uint4* hitv = s_hitv[wave];
+  int* hith = s_hith[wave];
+  unsigned long long* ck = s_ck[wave];
+  unsigned long long* topw = s_topw[wave];
+
   for (long long item = blockIdx.x; item < n_items; item += gridDim.x) {
-    const int rg = static_cast<int>(item / a.chunks);
-    const int ch = static_cast<int>(item - static_cast<long long>(rg) * a.chunks);
+    const int rg = static_cast<int>(item / chunks);
+    const int ch = static_cast<int>(item - static_cast<long long>(rg) * chunks);
     int lo = 0, hi = a.B;  // largest b with s_prefix[b] <= rg
     while (hi - lo > 1) {
       const int mid = (lo + hi) >> 1;
@@ -163,180 +271,274 @@ __global__ __launch_bounds__(kThreads) void expand_kernel(ExpandArgs a) {
     const int local = rg - s_prefix[b];
     const int node = a.frontier_begin[b] + local;
     const int in_row = a.row_mode == TALON_ROWS_BY_FRONTIER ? local : node;
-    const size_t esz = EPL == 4 ? 4 : 2;
     const char* row = static_cast<const char*>(a.logits) +
-                      (static_cast<int64_t>(b) * a.seq_stride + static_cast<int64_t>(in_row) * a.row_stride) * esz;
+                      (static_cast<int64_t>(b) * a.seq_stride + static_cast<int64_t>(in_row) * a.row_stride) * (16 / EPL);
     const int out_row = b * a.N_pad + node;
+    const int blk0 = ch * bpc;
+    const int blk1 = blk0 + bpc < blocks_per_row ? blk0 + bpc : blocks_per_row;
 
-    if (tid == 0) s_ncand = 0;
+    // ---- wavefront-local streaming state
+    int cnt = 0;            // buffered vectors
+    int tcnt = 0;           // keys in topw (<= k)
+    float tau = __builtin_huge_valf();   // a vector is buffered iff one of its logits is >= tau (set by the first group)
+    float m_l = kNegInf;    // this lane's running max
+    double s_l = 0.0;       // this lane's running sum of exp(logit - m_l)
 
-    // ---- the whole chunk into registers
-    float x[NX];
-    const int c0 = ch * CHUNK;
-#pragma unroll
-    for (int j = 0; j < kScanTiles; ++j)
-      RowVec<EPL>::load(row, c0 + (j * kThreads + tid) * EPL, a.vocab, x + j * EPL);
+    // A tile is one 16-byte vector per thread (256 * EPL logits); a block is 4 tiles.
+    // Groups of 4 tiles that lie wholly inside the row go through the fast loop, whose ring
+    // keeps the next group's loads in flight; the ragged end of the row (at most 4 tiles,
+    // only in the row's last chunk) goes tile by tile through the guarded path.
+    const int t0 = blk0 * kScanTiles;
+    const int tiles_in_row = (a.vocab + kThreads * EPL - 1) / (kThreads * EPL);
+    const int full_tiles = a.vocab / (kThreads * EPL);
+    const int t1 = blk1 * kScanTiles < tiles_in_row ? blk1 * kScanTiles : tiles_in_row;
+    int tf = blk1 * kScanTiles < full_tiles ? blk1 * kScanTiles : full_tiles;
+    tf = t0 + (tf > t0 ? (tf - t0) / kScanTiles * kScanTiles : 0);   // end of the fast loop
+    const char* lane_ptr = row + static_cast<size_t>(tid) * 16;
+    constexpr size_t kTileBytes = static_cast<size_t>(kThreads) * 16;
 
-    // ---- per-wavefront max and sum of exp relative to it
-    float lane_max = kNegInf;
-#pragma unroll
-    for (int i = 0; i < NX; ++i) lane_max = fmaxf(lane_max, x[i]);
+    // Buffer this lane's vector if one of its logits reaches tau.  Returns false (and buffers
+    // nothing) when the wavefront's buffer has no room for all hits of the tile.
+    auto buffer_hits = [&](const uint4& raw, float vmax, int tile) -> bool {
+      const bool hit = vmax >= tau;
+      const unsigned long long bal = __ballot(hit);
+      if (bal != 0ull) {
+        const int nh = __popcll(bal);
+        if (cnt + nh > kHitCap) return false;
+        const int pos = cnt + __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(bal >> 32),
+                                                        __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(bal), 0));
+        if (hit) { hitv[pos] = raw; hith[pos] = tile * 64 + lane; }
+        cnt += nh;
+      }
+      return true;
+    };
+
+    // Streaming state machine.  A step is a group of 4 whole tiles (fast) or one tile at the
+    // ragged end of the row (guarded).  Tiles whose hits do not fit the buffer are deferred,
+    // together with all later tiles of the step, to the single slow section below, which cuts
+    // the buffer and then re-reads them.
     PHASE(2);
-    const float wmax = wave_max_f32(lane_max);
-    float lane_sum = 0.f;
-    if (wmax != kNegInf) {
+    if (tf == t0) tau = kNegInf;   // short row: every vector is buffered and ranked
+    int tb = t0;
+    bool done = false;
+    while (!done) {
+      uint32_t deferred = 0;   // bit q: tile def_base + q still has to be buffered
+      int def_base = tb;
+      bool force = false;
+      if (tb < tf) {
+        // No software prefetch: many resident wavefronts, each with 4 loads in flight, hide
+        // the latency, and the loop stays small in registers.
+        uint4 raw[kScanTiles];
 #pragma unroll
-      for (int i = 0; i < NX; ++i) lane_sum += __expf(x[i] - wmax);
-    }
-    const double wsum = wave_sum_f64(static_cast<double>(lane_sum));
-    if (lane == 0) { s_wmax[wave] = wmax; s_wsum[wave] = wsum; }
+        for (int q = 0; q < kScanTiles; ++q)
+          raw[q] = *reinterpret_cast<const uint4*>(lane_ptr + (tb + q) * kTileBytes);
+        // lane maxima of the 4 tiles first; the running max moves at most once per group
+        float vmax4[kScanTiles];
+#pragma unroll
+        for (int q = 0; q < kScanTiles; ++q) {
+          float x[EPL];
+          unpack_vec<EPL>(raw[q], x);
+          float vmax = x[0];
+#pragma unroll
+          for (int e = 1; e < EPL; ++e) vmax = fmaxf(vmax, x[e]);
+          vmax4[q] = vmax;
+        }
+        const float gmax = fmaxf(fmaxf(vmax4[0], vmax4[1]), fmaxf(vmax4[2], vmax4[3]));
+        if (gmax > m_l) {
+          s_l = (m_l == kNegInf) ? 0.0 : s_l * static_cast<double>(__expf(m_l - gmax));
+          m_l = gmax;
+        }
+        // sum of 2^(x*log2e - c) with c = fl(m*log2e); the rounding of c is a common factor
+        // 2^(c - m*log2e) of the whole group, applied once below
+        const float kLog2e = 1.4426950408889634f;
+        const float mm = (m_l == kNegInf) ? 0.f : m_l;
+        const float c = mm * kLog2e;
+        const float c_err = __builtin_fmaf(mm, kLog2e, -c);   // m*log2e - c, exact
+        float acc = 0.f;
+#pragma unroll
+        for (int q = 0; q < kScanTiles; ++q) {
+          float x[EPL];
+          unpack_vec<EPL>(raw[q], x);
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) acc += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e], kLog2e, -c));
+        }
+        s_l += static_cast<double>(acc * __builtin_amdgcn_exp2f(-c_err));
+        if (tb == t0) {
+          // ---- first threshold: the k-th largest of the 64 lane maxima of this group (at
+          // least k logits of the group reach it)
+          float v = gmax;
+          int seen = 0;
+          for (int r = 0; r < k; ++r) {
+            const float top = wave_max_f32(v);
+            seen += __popcll(__ballot(v == top));
+            tau = top;
+            if (seen >= k) break;
+            v = (v == top) ? kNegInf : v;
+          }
+          force = true;
+        }
+#pragma unroll
+        for (int q = 0; q < kScanTiles; ++q)
+          if (deferred != 0u || !buffer_hits(raw[q], vmax4[q], tb + q)) deferred |= 1u << q;
+        tb += kScanTiles;
+      } else if (tb < t1) {
+        const uint4 raw = load_vec<EPL>(row, (tb * kThreads + tid) * EPL, a.vocab);
+        float x[EPL];
+        unpack_vec<EPL>(raw, x);
+        float vmax = x[0];
+#pragma unroll
+        for (int e = 1; e < EPL; ++e) vmax = fmaxf(vmax, x[e]);
+        if (vmax > m_l) {
+          s_l = (m_l == kNegInf) ? 0.0 : s_l * static_cast<double>(__expf(m_l - vmax));
+          m_l = vmax;
+        }
+        const float mm = (m_l == kNegInf) ? 0.f : m_l;
+        float bs = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) bs += __expf(x[e] - mm);
+        s_l += static_cast<double>(bs);
+        if (!buffer_hits(raw, vmax, tb)) deferred = 1u;
+        tb += 1;
+      } else {
+        force = cnt > 0;
+        done = true;
+      }
 
-    // ---- k-th largest lane maximum of this wavefront: lower bound of the chunk's top k
-    float tau = kNegInf;
-    {
-      float v = lane_max;
-      int cnt = 0;
-      for (int r = 0; r < k; ++r) {
-        const float cur = wave_max_f32(v);
-        const unsigned long long eq = __ballot(v == cur);
-        cnt += __popcll(eq);
-        tau = cur;
-        if (cnt >= k) break;
-        v = (v == cur) ? kNegInf : v;
+      if (force || deferred != 0u || cnt > kHitTrigger) {
+        // ---- slow section: cut the buffer to the k best; then buffer the deferred tiles
+        while (true) {
+          // Expand the buffered vectors, rank their logits that reach tau together with the k
+          // best so far, keep the k best.  Every buffered token id is below every id still to
+          // come (deferred tiles included), so afterwards a logit equal to the k-th best loses
+          // the tie and tau becomes the next float above it.
+          for (int base = 0; base < cnt; base += kSubBatch) {
+            float x[EPL];
+            int e0 = 0;
+            uint32_t hbits = 0;
+            if (lane < kSubBatch && base + lane < cnt) {
+              const uint4 raw = hitv[base + lane];
+              const int hdr = hith[base + lane];
+              e0 = (((hdr >> 6) * 4 + wave) * 64 + (hdr & 63)) * EPL;
+              unpack_vec<EPL>(raw, x);
+#pragma unroll
+              for (int e = 0; e < EPL; ++e)
+                if (x[e] >= tau && e0 + e < a.vocab) hbits |= 1u << e;
+            }
+            const int nh = __popc(hbits);
+            const int incl = wave_inclusive_scan_i32(nh);
+            const int total = __builtin_amdgcn_readlane(incl, 63);
+            if (lane < tcnt) ck[lane] = topw[lane];
+            int pos = tcnt + incl - nh;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e)
+              if (hbits & (1u << e)) ck[pos++] = make_key(x[e], e0 + e);
+            const int n = tcnt + total;
+            // LDS operations of one wavefront complete in order: ck is complete before it is read
+            for (int i = lane; i < n; i += 64) {
+              const unsigned long long key = ck[i];
+              const int r = count_greater(ck, n, key);
+              if (r < k) topw[r] = key;
+            }
+            tcnt = n < k ? n : k;
+            if (tcnt >= k) tau = fmaxf(tau, key_logit(topw[k - 1]));
+          }
+          cnt = 0;
+          if (tcnt >= k) tau = float_above(key_logit(topw[k - 1]));
+          if (deferred == 0u) break;
+#pragma unroll 1
+          for (int q = 0; q < kScanTiles; ++q) {
+            if (!((deferred >> q) & 1u)) continue;
+            const int tile = def_base + q;
+            const uint4 raw = load_vec<EPL>(row, (tile * kThreads + tid) * EPL, a.vocab);
+            float x[EPL];
+            unpack_vec<EPL>(raw, x);
+            float vmax = x[0];
+#pragma unroll
+            for (int e = 1; e < EPL; ++e) vmax = fmaxf(vmax, x[e]);
+            if (!buffer_hits(raw, vmax, tile)) break;   // full again: cut first
+            deferred &= ~(1u << q);
+          }
+        }
       }
     }
     PHASE(3);
-    __syncthreads();  // s_ncand = 0 visible; previous iteration's readers of s_keys are done
 
-    // ---- push every logit >= tau (rare: about k per wavefront on ordinary rows)
-#pragma unroll
-    for (int j = 0; j < kScanTiles; ++j) {
-      bool any = false;
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) any |= (x[j * EPL + e] >= tau);
-      if (any) {
-        const int e0 = c0 + (j * kThreads + tid) * EPL;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) {
-          if (x[j * EPL + e] >= tau && e0 + e < a.vocab) {
-            const int slot = atomicAdd(&s_ncand, 1);
-            if (slot < kCandCap) s_keys[slot] = make_key(x[j * EPL + e], e0 + e);
-          }
-        }
-      }
+    // ---- wavefront statistics
+    {
+      const float wmax = wave_max_f32(m_l);
+      const double sl = (m_l == kNegInf) ? 0.0 : s_l * exp(static_cast<double>(m_l) - static_cast<double>(wmax));
+      const double wsum = wave_sum_f64(sl);
+      if (lane == 0) { s_wmax[wave] = wmax; s_wsum[wave] = wsum; s_wcnt[wave] = tcnt; }
     }
     __syncthreads();
     PHASE(4);
-    const int ncand = s_ncand;
-    unsigned long long* pk = a.part_keys + (static_cast<size_t>(out_row) * a.chunks + ch) * k;
 
-    if (ncand <= kCandCap) {
-      // rank by counting: keys are distinct (distinct tokens)
-      for (int i = tid; i < ncand; i += kThreads) {
-        const unsigned long long ki = s_keys[i];
-        const int r = count_greater(s_keys, ncand, ki);
-        if (r < k) store_agent(pk + r, ki);
+    // ---- merge the four lists (each <= k keys) into the chunk's k best, sorted
+    const int c0 = s_wcnt[0], c1 = s_wcnt[1], c2 = s_wcnt[2], c3 = s_wcnt[3];
+    const int ctot = c0 + c1 + c2 + c3;
+    {
+      const int my_cnt = wave == 0 ? c0 : (wave == 1 ? c1 : (wave == 2 ? c2 : c3));
+      if (lane < my_cnt) {
+        const unsigned long long key = topw[lane];
+        const int r = count_greater_sorted(s_topw[0], c0, key) + count_greater_sorted(s_topw[1], c1, key) +
+                      count_greater_sorted(s_topw[2], c2, key) + count_greater_sorted(s_topw[3], c3, key);
+        if (r < k) s_top[r] = key;
       }
-      if (tid >= ncand && tid < k) store_agent(pk + tid, 0ull);  // fewer than k logits in this chunk
-    } else {
-      // heavy ties: exact k rounds of workgroup arg-max over the registers
-      unsigned long long prev = ~0ull;
-      for (int r = 0; r < k; ++r) {
-        unsigned long long best = 0ull;
-#pragma unroll
-        for (int j = 0; j < kScanTiles; ++j) {
-          const int e0 = c0 + (j * kThreads + tid) * EPL;
-#pragma unroll
-          for (int e = 0; e < EPL; ++e) {
-            if (e0 + e < a.vocab) {
-              const unsigned long long key = make_key(x[j * EPL + e], e0 + e);
-              if (key < prev && key > best) best = key;
-            }
-          }
-        }
-        best = block_max_u64(best, s_red_u64);
-        if (tid == 0) store_agent(pk + r, best);
-        prev = best;
-        if (best == 0ull) {
-          if (tid > r && tid < k) store_agent(pk + tid, 0ull);
-          break;
-        }
-      }
+      if (tid >= ctot && tid < k) s_top[tid] = 0ull;   // fewer than k logits in this chunk
     }
-
+    const float cm = fmaxf(fmaxf(s_wmax[0], s_wmax[1]), fmaxf(s_wmax[2], s_wmax[3]));
+    double csum = 0.0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+      if (s_wmax[w] != kNegInf) csum += s_wsum[w] * exp(static_cast<double>(s_wmax[w]) - static_cast<double>(cm));
+    __syncthreads();
     PHASE(5);
-    // ---- chunk statistics
-    if (tid == 0) {
-      const float m = fmaxf(fmaxf(s_wmax[0], s_wmax[1]), fmaxf(s_wmax[2], s_wmax[3]));
-      double sum = 0.0;
-#pragma unroll
-      for (int w = 0; w < 4; ++w)
-        if (s_wmax[w] != kNegInf) sum += s_wsum[w] * exp(static_cast<double>(s_wmax[w]) - static_cast<double>(m));
-      store_agent(a.part_max + static_cast<size_t>(out_row) * a.chunks + ch, m);
-      store_agent(a.part_sum + static_cast<size_t>(out_row) * a.chunks + ch, sum);
-    }
 
-    PHASE(6);
-    // ---- ticket: the workgroup that finishes the row's last chunk merges the row
-    // every partial store of this workgroup has completed before the ticket is taken
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __syncthreads();
-    if (tid == 0) {
-      const int old = __hip_atomic_fetch_add(&a.ticket[out_row], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      s_last = (old == a.chunks - 1) ? 1 : 0;
-    }
-    __syncthreads();
-    PHASE(7);
-    if (s_last) {
-      PHASE(8);
-      const float* pm = a.part_max + static_cast<size_t>(out_row) * a.chunks;
-      const double* ps = a.part_sum + static_cast<size_t>(out_row) * a.chunks;
-      const unsigned long long* keys = a.part_keys + static_cast<size_t>(out_row) * a.chunks * k;
-      const int nkeys = a.chunks * k;
-      for (int i = tid; i < nkeys; i += kThreads) s_keys[i] = load_agent(keys + i);
-      float m = kNegInf;
-      for (int c = tid; c < a.chunks; c += kThreads) m = fmaxf(m, load_agent(pm + c));
-      m = block_max_f32(m, s_red_f32);  // barrier inside: s_keys staged
-      double sum = 0.0;
-      for (int c = tid; c < a.chunks; c += kThreads) {
-        const float mc = load_agent(pm + c);
-        if (mc != kNegInf) sum += load_agent(ps + c) * exp(static_cast<double>(mc) - static_cast<double>(m));
-      }
-      sum = block_sum_f64(sum, s_red_f64);
-      PHASE(9);
-      const double lse = static_cast<double>(m) + log(sum);
-      const int valid = a.vocab < k ? a.vocab : k;
-      const size_t ob = static_cast<size_t>(out_row) * k;
-      for (int i = tid; i < nkeys; i += kThreads) {
-        const unsigned long long ki = s_keys[i];
-        if (ki == 0ull) continue;
-        const int r = count_greater(s_keys, nkeys, ki);
-        if (r < k) {
-          const float lg = unsortable_f32(static_cast<uint32_t>(ki >> 32));
-          const double edge = static_cast<double>(lg) - lse;
-          a.cand_token[ob + r] = static_cast<int32_t>(0xFFFFFFFFu - static_cast<uint32_t>(ki));
-          a.cand_logit[ob + r] = lg;
-          a.cand_edge_logp[ob + r] = edge;
-          a.cand_prob[ob + r] = static_cast<float>(exp(edge));
-        }
-      }
-      if (tid >= valid && tid < k) {
-        a.cand_token[ob + tid] = -1;
-        a.cand_logit[ob + tid] = kNegInf;
-        a.cand_edge_logp[ob + tid] = -__builtin_huge_val();
-        a.cand_prob[ob + tid] = 0.f;
-      }
+    if (chunks == 1) {
+      write_row(a, b, out_row, s_top, 1, cm, csum);
+    } else {
+      unsigned long long* pk = a.part_keys + (static_cast<size_t>(out_row) * blocks_per_row + ch) * k;
+      if (tid < k) store_agent(pk + tid, s_top[tid]);
       if (tid == 0) {
-        a.row_max[out_row] = m;
-        a.row_lse[out_row] = lse;
-        if (!(fabs(lse) <= 1.7e308)) atomicOr(&a.status[b], TALON_STATUS_BAD_ROW);
-        store_agent(a.ticket + out_row, 0);  // leave the workspace clean for the next layer
+        store_agent(a.part_max + static_cast<size_t>(out_row) * blocks_per_row + ch, cm);
+        store_agent(a.part_sum + static_cast<size_t>(out_row) * blocks_per_row + ch, csum);
+      }
+      // every partial store of this workgroup has completed before the ticket is taken
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      __syncthreads();
+      if (tid == 0) {
+        const int old = __hip_atomic_fetch_add(&a.ticket[out_row], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_last = (old == chunks - 1) ? 1 : 0;
+      }
+      __syncthreads();
+      PHASE(6);
+      if (s_last) {
+        const float* pm = a.part_max + static_cast<size_t>(out_row) * blocks_per_row;
+        const double* ps = a.part_sum + static_cast<size_t>(out_row) * blocks_per_row;
+        const unsigned long long* keys = a.part_keys + static_cast<size_t>(out_row) * blocks_per_row * k;
+        const int nkeys = chunks * k;
+        for (int i = tid; i < nkeys; i += kThreads) s_keys[i] = load_agent(keys + i);
+        float m = kNegInf;
+        for (int c = tid; c < chunks; c += kThreads) m = fmaxf(m, load_agent(pm + c));
+        m = block_max_f32(m, s_red_f32);  // barriers inside: s_keys is staged
+        double sum = 0.0;
+        for (int c = tid; c < chunks; c += kThreads) {
+          const float mc = load_agent(pm + c);
+          if (mc != kNegInf) sum += load_agent(ps + c) * exp(static_cast<double>(mc) - static_cast<double>(m));
+        }
+        sum = block_sum_f64(sum, s_red_f64);
+        PHASE(7);
+        PHASE_MAX(12);
+        write_row(a, b, out_row, s_keys, chunks, m, sum);
+        PHASE_MAX(13);
+        if (tid == 0) store_agent(a.ticket + out_row, 0);  // leave the workspace clean for the next layer
       }
     }
-    __syncthreads();  // s_keys / s_last are reused by the next item
-    PHASE(10);
+    __syncthreads();  // s_keys / s_top / s_w* are reused by the next item
+    PHASE(8);
+    PHASE_MAX(11);
   }
-  PHASE(11);
+  PHASE(9);
 }
 
 __global__ __launch_bounds__(kThreads) void fill_zero_kernel(uint32_t* p, size_t n) {
@@ -376,6 +578,10 @@ hipError_t launch_expand(const ExpandArgs& a, int dtype, int grid, hipStream_t s
 #ifdef TALON_PHASE_TIMING
 extern "C" int talon_debug_read_phases(unsigned long long* host16) {
   return static_cast<int>(hipMemcpyFromSymbol(host16, HIP_SYMBOL(g_phase), sizeof(unsigned long long) * 16));
+}
+extern "C" int talon_debug_clear_phases() {
+  unsigned long long z[16] = {0};
+  return static_cast<int>(hipMemcpyToSymbol(HIP_SYMBOL(g_phase), z, sizeof(z)));
 }
 #endif
 

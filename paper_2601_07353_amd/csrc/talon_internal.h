@@ -11,7 +11,6 @@ namespace talon {
 constexpr int kThreads = 256;       // every kernel here runs 4 wavefronts per workgroup
 constexpr int kScanTiles = 4;       // 16-byte vectors per thread per vocab chunk
 constexpr int kChunkBytes = kThreads * kScanTiles * 16;  // 16 KiB of a logits row per workgroup pass
-constexpr int kCandCap = 512;       // LDS candidate slots per chunk before the exact fallback
 constexpr int kMergeCap = 1024;     // chunks * k keys one row merge stages in LDS
 constexpr uint32_t kDoneMask = TALON_STATUS_DONE_BUDGET | TALON_STATUS_DONE_DEPTH;
 
@@ -24,7 +23,9 @@ struct ExpandArgs {
   const void* logits;
   int64_t row_stride, seq_stride;
   int row_mode;
-  int B, N_pad, vocab, k, chunks;
+  int B, N_pad, vocab, k;
+  int chunks;            // 16 KiB blocks per row = most chunks a row is ever cut into
+  int target_items;      // (row, chunk) items a launch aims for when it cuts rows into chunks
   const int32_t* frontier_begin;
   const int32_t* frontier_count;
   uint32_t* status;
