@@ -147,18 +147,29 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     steps_per_s = args.steps / (t1 - t0)
 
-    # ---- kernel timing region: the same K steps launched eagerly with HIP events around the
-    # expansion loop and around the tree-attention call (events on the launch stream)
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    # ---- kernel timing region: the same K steps launched eagerly, layer by layer, with HIP
+    # events (on the launch stream) around every vocab-scan launch and around the
+    # tree-attention call.  Launch shapes are the ones talon_expand_tree uses.
+    layers = min(cfg.Dmax, cfg.N - 1)
+    ev_scan = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(layers)]
+               for _ in range(args.steps)]
+    ev_attn = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     for i in range(args.steps):
         s = slots[i % n_slots]
-        e = ev[i]
-        e[0].record(); expand(s); e[1].record()
+        T.talon_tree_init(st, roots)
+        for d in range(layers):
+            e0, e1 = ev_scan[i][d]
+            e0.record()
+            T.talon_expand_layer(s.logits, st, cfg.K, cand, ws_expand, layer=d)
+            e1.record()
+            T.talon_select_budget(st, cfg.K, cand, cfg.mu, cfg.K, 1, cfg.Dmax)
         T.talon_build_tree_mask(st, mask)
-        e[2].record(); attention(s); e[3].record()
+        e0, e1 = ev_attn[i]
+        e0.record(); attention(s); e1.record()
     torch.cuda.synchronize()
-    expand_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
-    attn_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in ev]))
+    scan_ms_step = float(np.mean([sum(e0.elapsed_time(e1) for e0, e1 in step_ev) for step_ev in ev_scan]))
+    scan_ms_launch = scan_ms_step / layers
+    attn_ms = float(np.mean([e0.elapsed_time(e1) for e0, e1 in ev_attn]))
 
     used = [i % n_slots for i in range(args.steps)]
     mean_rows = float(np.mean([rows_scanned[u] for u in used]))
@@ -168,23 +179,26 @@ def main():
                   2.0 * float(np.mean(n_nodes_mean)) * cfg.B * (cfg.Hq + cfg.Hkv) * cfg.Dh * 2)
 
     kernels = {
-        "expand_loop": {"ms": expand_ms, "rows_scanned": mean_rows, "bytes": scan_bytes,
-                        "GBps": scan_bytes / (expand_ms * 1e-3) / 1e9 if expand_ms > 0 else None,
-                        "launches": 2 * min(cfg.Dmax, cfg.N - 1)},
+        "expand_kernel": {"launches_per_step": layers, "ms_per_step": scan_ms_step, "ms_per_launch": scan_ms_launch,
+                          "rows_scanned_per_step": mean_rows, "bytes_per_step": scan_bytes,
+                          "GBps": scan_bytes / (scan_ms_step * 1e-3) / 1e9},
         "tree_attention": {"ms": attn_ms, "flops": mean_flops, "bytes": attn_bytes,
-                           "TFLOPs": mean_flops / (attn_ms * 1e-3) / 1e12 if attn_ms > 0 else None},
+                           "TFLOPs": mean_flops / (attn_ms * 1e-3) / 1e12},
     }
-    if attn_ms >= expand_ms / max(1, min(cfg.Dmax, cfg.N - 1)):
-        # dominant single kernel: tree attention (a dense bf16 contraction)
+    traffic = read_traffic(cfg.name)
+    if scan_ms_step >= attn_ms:
+        # dominant kernel of the step: the vocab scan (HBM-bound: every logit is read once)
+        ach = scan_bytes / layers / (scan_ms_launch * 1e-3) / 1e9
+        roofline = {"kernel": "expand_kernel", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": traffic.get("expand_kernel"),
+                    "launches_per_step": layers, "avg_launch_us": scan_ms_launch * 1e3,
+                    "algorithmic_bytes_per_launch": scan_bytes / layers}
+    else:
         ach = mean_flops / (attn_ms * 1e-3) / 1e12
         roofline = {"kernel": "tree_attention_kernel", "bound": "mfma", "achieved": ach,
                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
-                    "traffic": None}
-    else:
-        per_launch_ms = expand_ms / min(cfg.Dmax, cfg.N - 1)
-        ach = scan_bytes / min(cfg.Dmax, cfg.N - 1) / (per_launch_ms * 1e-3) / 1e9
-        roofline = {"kernel": "expand_kernel", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None}
+                    "traffic": traffic.get("tree_attention_kernel"), "avg_launch_us": attn_ms * 1e3,
+                    "algorithmic_flops_per_launch": mean_flops}
 
     result = {
         "metric": "tree expand+verify steps/s", "value": steps_per_s, "unit": "steps/s", "n_gpus": 1,
@@ -201,6 +215,19 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, args.cpu_seconds, H)
     print(json.dumps(result))
+
+
+def read_traffic(workload):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by a
+    copy kernel of known size); the summary under profiles/ holds `kernel: bytes` lines."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % workload)
+    out = {}
+    if os.path.exists(path):
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch "):
+                _, kern, val = line.split()
+                out[kern] = float(val)
+    return out
 
 
 def cpu_baseline(cfg, budget_s, H):

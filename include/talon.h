@@ -99,6 +99,9 @@ int talon_expand_workspace_init(void* workspace, size_t workspace_bytes, void* s
  *               between rows of a sequence, seq_stride elements between sequences.
  *               Each row is read exactly once.  -inf entries are allowed (probability 0).
  *   row_mode    which row node i reads (TALON_ROWS_BY_NODE / _BY_FRONTIER).
+ *   layer       depth d of the layer being expanded if the caller knows it (all sequences
+ *               at the same depth), else -1.  Only sizes the launch: layer d of a tree has a
+ *               bounded frontier, so fewer workgroups are started; results do not depend on it.
  *   outputs, all indexed by [b][node id][rank], only rows of frontier nodes are written:
  *     cand_token     [B][N_pad][k] int32   token ids; -1 where vocab < k
  *     cand_logit     [B][N_pad][k] float   their logits (exact input values)
@@ -112,8 +115,8 @@ int talon_expand_workspace_init(void* workspace, size_t workspace_bytes, void* s
  *   what one merge supports), WORKSPACE (too small).
  */
 int talon_expand_layer(const void* logits, int dtype, int64_t row_stride, int64_t seq_stride,
-                       int row_mode, const talon_tree_state* st, int32_t vocab, int32_t k,
-                       int32_t* cand_token, float* cand_logit, float* cand_prob,
+                       int row_mode, int32_t layer, const talon_tree_state* st, int32_t vocab,
+                       int32_t k, int32_t* cand_token, float* cand_logit, float* cand_prob,
                        double* cand_edge_logp, float* row_max, double* row_lse,
                        void* workspace, size_t workspace_bytes, void* stream);
 

@@ -71,8 +71,8 @@ def load_library() -> ctypes.CDLL:
     lib.talon_expand_workspace_bytes.restype = c_size_t
     lib.talon_expand_workspace_bytes.argtypes = [c_int32, c_int32, c_int32, c_int32, c_int]
     lib.talon_expand_workspace_init.argtypes = [P, c_size_t, P]
-    lib.talon_expand_layer.argtypes = [P, c_int, c_int64, c_int64, c_int, POINTER(_CTreeState), c_int32, c_int32,
-                                       P, P, P, P, P, P, P, c_size_t, P]
+    lib.talon_expand_layer.argtypes = [P, c_int, c_int64, c_int64, c_int, c_int32, POINTER(_CTreeState), c_int32,
+                                       c_int32, P, P, P, P, P, P, P, c_size_t, P]
     lib.talon_select_budget.argtypes = [POINTER(_CTreeState), c_int32, P, P, P, c_float, c_int32, c_int32, c_int32, P]
     lib.talon_expand_tree.argtypes = [P, c_int, c_int64, c_int64, c_int, POINTER(_CTreeState), c_int32, c_int32,
                                       c_float, c_int32, c_int32, c_int32, P, P, P, P, P, P, P, c_size_t, P]
@@ -174,10 +174,11 @@ def make_expand_workspace(B, N_pad, vocab, k, dtype, device="cuda") -> torch.Ten
 
 
 def talon_expand_layer(logits, st: TreeState, k, cand: Candidates, workspace, row_mode=TALON_ROWS_BY_NODE,
-                       vocab=None, stream=None):
+                       layer=-1, vocab=None, stream=None):
     dt, row_stride, seq_stride, V = _logits_meta(logits)
     _check(load_library().talon_expand_layer(
-        _ptr(logits), dt, row_stride, seq_stride, row_mode, ctypes.byref(st.c), V if vocab is None else vocab, k,
+        _ptr(logits), dt, row_stride, seq_stride, row_mode, layer, ctypes.byref(st.c),
+        V if vocab is None else vocab, k,
         _ptr(cand.token), _ptr(cand.logit), _ptr(cand.prob), _ptr(cand.edge_logp), _ptr(cand.row_max),
         _ptr(cand.row_lse), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
 

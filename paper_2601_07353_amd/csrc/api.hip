@@ -188,7 +188,7 @@ int talon_expand_workspace_init(void* workspace, size_t workspace_bytes, void* s
 }
 
 int talon_expand_layer(const void* logits, int dtype, int64_t row_stride, int64_t seq_stride, int row_mode,
-                       const talon_tree_state* st, int32_t vocab, int32_t k, int32_t* cand_token,
+                       int32_t layer, const talon_tree_state* st, int32_t vocab, int32_t k, int32_t* cand_token,
                        float* cand_logit, float* cand_prob, double* cand_edge_logp, float* row_max,
                        double* row_lse, void* workspace, size_t workspace_bytes, void* stream) {
   ExpandLayout L;
@@ -197,7 +197,7 @@ int talon_expand_layer(const void* logits, int dtype, int64_t row_stride, int64_
   if (rc) return rc;
   const ExpandArgs a = make_expand_args(logits, row_stride, seq_stride, row_mode, st, vocab, k, cand_token,
                                         cand_logit, cand_prob, cand_edge_logp, row_max, row_lse, workspace, L);
-  return check_hip(launch_expand(a, dtype, expand_grid(st, L.chunks, -1, k, 0, 0), static_cast<hipStream_t>(stream)), "expand launch");
+  return check_hip(launch_expand(a, dtype, expand_grid(st, L.chunks, layer < 0 ? -1 : layer, k, k, 0), static_cast<hipStream_t>(stream)), "expand launch");
 }
 
 int talon_select_budget(const talon_tree_state* st, int32_t k, const int32_t* cand_token, const float* cand_prob,

@@ -21,6 +21,10 @@
 //
 // Split-KV partial results (unnormalised O, running max, denominator) go to a workspace
 // and are merged by a second kernel; with a single split the output is written directly.
+#include <stdlib.h>
+
+#include <type_traits>
+
 #include "device_utils.h"
 #include "talon_internal.h"
 
@@ -38,33 +42,44 @@ constexpr float kNegInfF = -__builtin_huge_valf();
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
+// LDS image of one 64-key tile: rows of DH bf16 without padding (the tiles are written by
+// direct global-to-LDS loads, which place the 64 lanes of a wavefront back to back).  Bank
+// conflicts are avoided by permuting the 16-byte chunks of every row, differently for K
+// (read as 16-byte fragments, 16 consecutive key rows at one chunk index) and for V (read
+// with the transposing load, 4 consecutive key rows by 32 bytes).
 template <int DH>
 struct Smem {
-  static constexpr int KSTR = DH + 8;    // 16 bytes of padding per key row (conflict-free 16-byte reads)
-  static constexpr int VSTR = DH + 32;   // 64 bytes of padding per key row (conflict-free transpose reads)
-  static constexpr int K_ELEMS = kKeyTile * KSTR;
-  static constexpr int V_ELEMS = kKeyTile * VSTR;
-  static constexpr int STAGE_ELEMS = K_ELEMS + V_ELEMS;
-  static constexpr int BYTES = 2 * STAGE_ELEMS * 2;
+  static constexpr int CPR = DH / 8;                     // 16-byte chunks per key row
+  static constexpr int T_ELEMS = kKeyTile * DH;          // one tensor, one tile
+  static constexpr int BYTES = 4 * T_ELEMS * 2;          // two K stages and two V stages
+  __device__ static int kswz(int row) { return DH == 128 ? (row & 15) : ((row >> 1) & 7); }
+  __device__ static int vswz(int row) { return DH == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2); }
 };
 
 template <int DH, int RB>
-__global__ __launch_bounds__(kThreads) void tree_attention_kernel(AttnArgs a) {
+__global__ __launch_bounds__(kThreads, 2) void tree_attention_kernel(AttnArgs a) {
   using SM = Smem<DH>;
   constexpr int DSTEPS = DH / 16;   // MFMA steps over the head dimension for S^T
   constexpr int DB = DH / 32;       // 32-row blocks of O^T
-  constexpr int CPR = DH / 8;       // 16-byte pieces per key row
-  constexpr int NLD = kKeyTile * CPR / kThreads;  // pieces per thread per tile and tensor
+  constexpr int CPR = DH / 8;       // 16-byte chunks per key row
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps LDS bases in scalar registers
   const int l32 = lane & 31;
   const int h = lane >> 5;
 
-  const int split = blockIdx.x;
-  const int bg = blockIdx.z;
+  // Workgroup -> work item.  The hardware deals consecutive workgroup ids round-robin to the
+  // 8 XCDs, each with its own L2.  The row tiles of one (sequence, KV head, split) read the
+  // same K/V tiles, so they are given ids that are congruent modulo 8 and adjacent in time:
+  // they share one L2 and the tile is fetched from HBM once, not once per row tile.
+  const int per_xcd = (a.total_items + 7) / 8;
+  const int item = static_cast<int>(blockIdx.x % 8) * per_xcd + static_cast<int>(blockIdx.x / 8);
+  if (item >= a.total_items) return;
+  const int rt = item % a.row_tiles;
+  const int split = (item / a.row_tiles) % a.splits;
+  const int bg = item / (a.row_tiles * a.splits);
   const int b = bg / a.Hkv;
   const int g = bg - b * a.Hkv;
   const int G = a.G;
@@ -72,7 +87,7 @@ __global__ __launch_bounds__(kThreads) void tree_attention_kernel(AttnArgs a) {
   int L = a.prefix_len[b];
   L = L < 0 ? 0 : (L > a.max_prefix_len ? a.max_prefix_len : L);
   const int rows = n * G;
-  const int row0 = blockIdx.y * (128 * RB);
+  const int row0 = rt * (128 * RB);
   if (row0 >= rows) return;
 
   const int nPT = (L + kKeyTile - 1) / kKeyTile;
@@ -125,112 +140,167 @@ __global__ __launch_bounds__(kThreads) void tree_attention_kernel(AttnArgs a) {
   const uint16_t* kt_base = a.k_tree + (static_cast<size_t>(b) * a.N_pad * a.Hkv + g) * DH;
   const uint16_t* vt_base = a.v_tree + (static_cast<size_t>(b) * a.N_pad * a.Hkv + g) * DH;
 
-  uint4 kreg[NLD], vreg[NLD];
-  auto load_tile = [&](int t) {
+  // One tile of K and V goes from global memory straight into LDS (no staging registers):
+  // every wavefront issues 16-byte-per-lane loads whose 64 lanes land back to back in LDS,
+  // i.e. whole key rows; the lane picks the global chunk that belongs at its LDS slot under
+  // the row's chunk permutation.  A key past the end of its segment reads the segment's last
+  // key instead: its score is masked to -inf below, so its probability is exactly 0 and the
+  // (finite) value row it brought along adds nothing.
+  constexpr int ROWS_PER_LOAD = 64 / CPR;                 // key rows per wavefront load
+  constexpr int LOADS = kKeyTile / ROWS_PER_LOAD / 4;     // loads per wavefront, tile and tensor
+  // LDS: two K stages then two V stages.
+  auto stage_k = [&](int st_) { return smem + st_ * SM::T_ELEMS; };
+  auto stage_v = [&](int st_) { return smem + (2 + st_) * SM::T_ELEMS; };
+  auto load_tensor = [&](int t, const uint16_t* pre_base, const uint16_t* tree_base, uint16_t* dst, bool is_k) {
     const bool is_prefix = t < nPT;
     const int key0 = (is_prefix ? t : t - nPT) * kKeyTile;
-    const int limit = is_prefix ? L : n;
+    const int last = (is_prefix ? L : n) - 1;
+    const size_t stride = is_prefix ? static_cast<size_t>(a.kv_stride_t) : tree_stride;
+    const uint16_t* base = is_prefix ? pre_base : tree_base;
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const int p = i * kThreads + tid;
-      const int key = key0 + p / CPR;
-      const int c = p % CPR;
-      uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
-      if (key < limit) {
-        const size_t off = is_prefix ? static_cast<size_t>(key) * a.kv_stride_t : static_cast<size_t>(key) * tree_stride;
-        const uint16_t* ks = (is_prefix ? kp_base : kt_base) + off + c * 8;
-        const uint16_t* vs = (is_prefix ? vp_base : vt_base) + off + c * 8;
-        kv = *reinterpret_cast<const uint4*>(ks);
-        vv = *reinterpret_cast<const uint4*>(vs);
-      }
-      kreg[i] = kv;
-      vreg[i] = vv;
+    for (int i = 0; i < LOADS; ++i) {
+      const int row0_ = (wave * LOADS + i) * ROWS_PER_LOAD;
+      const int row = row0_ + lane / CPR;
+      const int cslot = lane % CPR;
+      int key = key0 + row;
+      key = key < last ? key : last;
+      const int chunk = cslot ^ (is_k ? SM::kswz(row) : SM::vswz(row));
+      const uint16_t* src = base + static_cast<size_t>(key) * stride + chunk * 8;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                       (__attribute__((address_space(3))) void*)(dst + row0_ * DH), 16, 0, 0);
     }
   };
-  auto store_tile = [&](int buf) {
-    uint16_t* sK = smem + buf * SM::STAGE_ELEMS;
-    uint16_t* sV = sK + SM::K_ELEMS;
+  // Fast path for a prefix tile that lies wholly below the prefix length: no clamping, and
+  // the address is a per-lane base plus tile and load offsets (no 64-bit multiplies).
+  const int lrow = lane / CPR;                       // key row of this lane inside one load
+  const size_t lane_off = static_cast<size_t>(wave * LOADS * ROWS_PER_LOAD + lrow) * a.kv_stride_t;
+  const uint16_t* kp_lane = kp_base + lane_off;
+  const uint16_t* vp_lane = vp_base + lane_off;
+  const size_t load_step = static_cast<size_t>(ROWS_PER_LOAD) * a.kv_stride_t;   // elements between loads
+  const size_t tile_step = static_cast<size_t>(kKeyTile) * a.kv_stride_t;       // elements between tiles
+  int kchunk[LOADS], vchunk[LOADS];                  // permuted chunk of this lane, in elements
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const int p = i * kThreads + tid;
-      const int key = p / CPR;
-      const int c = p % CPR;
-      *reinterpret_cast<uint4*>(sK + key * SM::KSTR + c * 8) = kreg[i];
-      *reinterpret_cast<uint4*>(sV + key * SM::VSTR + c * 8) = vreg[i];
+  for (int i = 0; i < LOADS; ++i) {
+    const int row = (wave * LOADS + i) * ROWS_PER_LOAD + lrow;
+    kchunk[i] = ((lane % CPR) ^ SM::kswz(row)) * 8;
+    vchunk[i] = ((lane % CPR) ^ SM::vswz(row)) * 8;
+  }
+  auto load_full_prefix = [&](int t, int kst, int vst, bool want_k, bool want_v) {
+    const uint16_t* kt_ = kp_lane + static_cast<size_t>(t) * tile_step;
+    const uint16_t* vt_ = vp_lane + static_cast<size_t>(t) * tile_step;
+    uint16_t* sK = stage_k(kst) + wave * LOADS * ROWS_PER_LOAD * DH;
+    uint16_t* sV = stage_v(vst) + wave * LOADS * ROWS_PER_LOAD * DH;
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+      if (want_k)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kt_ + i * load_step + kchunk[i]),
+                                         (__attribute__((address_space(3))) void*)(sK + i * ROWS_PER_LOAD * DH), 16, 0, 0);
+      if (want_v)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vt_ + i * load_step + vchunk[i]),
+                                         (__attribute__((address_space(3))) void*)(sV + i * ROWS_PER_LOAD * DH), 16, 0, 0);
     }
+  };
+  auto is_full_prefix = [&](int t) { return t < nPT && (t + 1) * kKeyTile <= L; };
+  auto load_k = [&](int t, int st_) {
+    if (is_full_prefix(t)) load_full_prefix(t, st_, 0, true, false);
+    else load_tensor(t, kp_base, kt_base, stage_k(st_), true);
+  };
+  auto load_v = [&](int t, int st_) {
+    if (is_full_prefix(t)) load_full_prefix(t, 0, st_, false, true);
+    else load_tensor(t, vp_base, vt_base, stage_v(st_), false);
+  };
+  auto tile_landed = [&]() {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
   };
 
   const float c2 = a.scale_log2e;
 
-  if (t_begin < t_end) {
-    load_tile(t_begin);
-    store_tile(0);
-  }
-  __syncthreads();
-
-  int buf = 0;
-  for (int t = t_begin; t < t_end; ++t) {
-    const bool have_next = t + 1 < t_end;
-    if (have_next) load_tile(t + 1);
-
-    const uint16_t* sK = smem + buf * SM::STAGE_ELEMS;
-    const uint16_t* sV = sK + SM::K_ELEMS;
-
-    // ---- S^T = K . Q^T for the 64 keys of the tile
-    floatx16 s[2][RB];
+  // S^T = K . Q^T for the 64 keys of one K stage
+  auto qk = [&](const uint16_t* sK, floatx16 (&s)[2][RB]) {
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[kb][rb][r] = 0.f;
-      const uint16_t* krow = sK + (32 * kb + l32) * SM::KSTR + 8 * h;
+      const int krow_i = 32 * kb + l32;
+      const uint16_t* krow = sK + krow_i * DH;
+      const int ksw = SM::kswz(krow_i);
 #pragma unroll
       for (int ds = 0; ds < DSTEPS; ++ds) {
-        const bf16x8 ak = as_bf16x8(*reinterpret_cast<const uint4*>(krow + 16 * ds));
+        const bf16x8 ak = as_bf16x8(*reinterpret_cast<const uint4*>(krow + ((2 * ds + h) ^ ksw) * 8));
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
           s[kb][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, bq[rb][ds], s[kb][rb], 0, 0, 0);
       }
     }
+  };
 
-    // ---- mask: ancestor bits on tree tiles, length bound on the ragged prefix tile
+  // Mask of tile t: ancestor bits on tree tiles, length bound on the ragged prefix tile.
+  auto mask_scores = [&](int t, floatx16 (&s)[2][RB]) {
     const bool is_prefix = t < nPT;
     const int key0 = (is_prefix ? t : t - nPT) * kKeyTile;
     const bool full = is_prefix && key0 + kKeyTile <= L;
-    if (!full) {
+    if (full) return;
 #pragma unroll
-      for (int rb = 0; rb < RB; ++rb) {
-        unsigned long long allow;
-        if (is_prefix) allow = (1ull << (L - key0)) - 1ull;
-        else allow = valid_rb[rb] ? a.mask[(static_cast<size_t>(b) * a.N_pad + node_rb[rb]) * words + (t - nPT)] : 0ull;
+    for (int rb = 0; rb < RB; ++rb) {
+      unsigned long long allow;
+      if (is_prefix) allow = (1ull << (L - key0)) - 1ull;
+      else allow = valid_rb[rb] ? a.mask[(static_cast<size_t>(b) * a.N_pad + node_rb[rb]) * words + (t - nPT)] : 0ull;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-          const uint32_t w = static_cast<uint32_t>(allow >> (32 * kb)) >> (4 * h);
+      for (int kb = 0; kb < 2; ++kb) {
+        const uint32_t w = static_cast<uint32_t>(allow >> (32 * kb)) >> (4 * h);
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int bit = 8 * (r / 4) + (r % 4);
-            if (!((w >> bit) & 1u)) s[kb][rb][r] = kNegInfF;
-          }
+        for (int r = 0; r < 16; ++r) {
+          const int bit = 8 * (r / 4) + (r % 4);
+          if (!((w >> bit) & 1u)) s[kb][rb][r] = kNegInfF;
         }
       }
     }
+  };
 
-    // ---- online softmax (base 2), per query = per lane pair (lane, lane ^ 32)
+  // One pipelined step for tile t = t_begin + i, whose (masked) scores are already in s:
+  //   start the loads of K(t+2) and V(t+1); compute the scores of tile t+1 into s_nxt (matrix
+  //   pipe) while the softmax of tile t runs (vector pipe); then O^T += V(t)^T . P^T.
+  const int nt = t_end - t_begin;
+  auto step = [&](int i, floatx16 (&s)[2][RB], floatx16 (&s_nxt)[2][RB], auto has_next) {
+    constexpr bool kHasNext = decltype(has_next)::value;   // a tile t+1 exists in this split
+    const int t = t_begin + i;
+    if (i + 2 < nt) load_k(t + 2, i & 1);          // the stage K(t) has just left
+    if constexpr (kHasNext) load_v(t + 1, (i + 1) & 1);
+    const uint16_t* sV = stage_v(i & 1);
+    static_assert(RB == 1, "the pipelined step is written for one row block per wavefront");
+
+    // ---- online softmax (base 2), per query = per lane pair (lane, lane ^ 32); s holds the
+    // masked scores of tile t
     bf16x8 pb[2][2][RB];
+    float mx = kNegInfF;
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-      float mx = kNegInfF;
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][0][r]);
+    {
+      const int mi = __float_as_int(mx);
+      const auto sw = __builtin_amdgcn_permlane32_swap(mi, mi, false, false);   // {own, lane ^ 32} in some order
+      mx = fmaxf(__int_as_float(static_cast<int>(sw[0])), __int_as_float(static_cast<int>(sw[1])));
+    }
+    const float m_new = fmaxf(m_run[0], mx * c2);
+    const float m_safe = m_new == kNegInfF ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(m_run[0] - m_safe);
+    m_run[0] = m_new;
+    if (__ballot(alpha != 1.f) != 0ull) {   // after the first tiles the running max rarely moves
 #pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][rb][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run[rb], mx * c2);
-      const float m_safe = m_new == kNegInfF ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m_run[rb] - m_safe);
-      m_run[rb] = m_new;
-      float sum = 0.f;
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[db][0][r] *= alpha;
+    }
+    // From here to the mask of the next tile there is no branch: the matrix instructions of
+    // the next tile's scores and the exponentials of this tile are independent and are
+    // scheduled against each other.
+    if constexpr (kHasNext) qk(stage_k((i + 1) & 1), s_nxt);
+    {
+      float sum0 = 0.f, sum1 = 0.f;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
@@ -238,36 +308,55 @@ __global__ __launch_bounds__(kThreads) void tree_attention_kernel(AttnArgs a) {
           bf16x8 pk;
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
-            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][rb][8 * sp + e], c2, -m_safe));
-            sum += p;
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][0][8 * sp + e], c2, -m_safe));
+            if (e & 1) sum1 += p; else sum0 += p;
             pk[e] = static_cast<__bf16>(p);
           }
-          pb[kb][sp][rb] = pk;
+          pb[kb][sp][0] = pk;
         }
       }
-      l_run[rb] = l_run[rb] * alpha + sum;
+      l_run[0] = l_run[0] * alpha + (sum0 + sum1);
+    }
+    if constexpr (kHasNext) {
+      // ask the scheduler for: one LDS fragment read, one matrix instruction, a handful of
+      // vector instructions, repeated; then keep the probabilities from sinking past the
+      // branch below (which would undo the overlap)
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
+      for (int g_ = 0; g_ < 2 * DSTEPS; ++g_) {
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+        __builtin_amdgcn_sched_group_barrier(0x002, DH == 128 ? 7 : 14, 0);   // VALU
+      }
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o[db][rb][r] *= alpha;
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int sp = 0; sp < 2; ++sp) {
+          uint4 pin = __builtin_bit_cast(uint4, pb[kb][sp][0]);
+          asm volatile("" : "+v"(pin.x), "+v"(pin.y), "+v"(pin.z), "+v"(pin.w));
+          pb[kb][sp][0] = __builtin_bit_cast(bf16x8, pin);
+        }
+      mask_scores(t + 1, s_nxt);
     }
 
     // ---- O^T += V^T . P^T
     {
       const int i16 = lane & 15;
       const int dhblk = (lane >> 4) & 1;
-      const uint16_t* vbase = sV + (4 * h + (i16 >> 2)) * SM::VSTR + 16 * dhblk + 4 * (i16 & 3);
+      const int vrow_l = 4 * h + (i16 >> 2);          // + 32*kb + 16*sp (+ 8 for the second read)
+      const int vsw = SM::vswz(vrow_l);               // the added row offsets are multiples of 8
+      const int vch = 2 * dhblk + ((i16 & 3) >> 1);   // + 4*db: chunk of this lane's 4 values
+      const int vsub = (i16 & 1) * 4;                 // element offset inside the chunk
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
         for (int sp = 0; sp < 2; ++sp) {
 #pragma unroll
           for (int db = 0; db < DB; ++db) {
-            const uint16_t* vp = vbase + (32 * kb + 16 * sp) * SM::VSTR + 32 * db;
+            const uint16_t* vp = sV + (32 * kb + 16 * sp + vrow_l) * DH + ((4 * db + vch) ^ vsw) * 8 + vsub;
             const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                 (__attribute__((address_space(3))) short4v*)(vp));
             const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (__attribute__((address_space(3))) short4v*)(vp + 8 * SM::VSTR));
+                (__attribute__((address_space(3))) short4v*)(vp + 8 * DH));
             typedef short short8v __attribute__((ext_vector_type(8)));
             const short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             const bf16x8 av = __builtin_bit_cast(bf16x8, both);
@@ -278,16 +367,45 @@ __global__ __launch_bounds__(kThreads) void tree_attention_kernel(AttnArgs a) {
         }
       }
     }
+    // loads of K(t+2), V(t+1) have landed; every wavefront is done with K(t+1) and V(t)
+    tile_landed();
+  };
 
-    if (have_next) store_tile(buf ^ 1);
-    __syncthreads();
-    buf ^= 1;
+  floatx16 s_a[2][RB], s_b[2][RB];
+  if (nt > 0) {
+    load_k(t_begin, 0);
+    load_v(t_begin, 0);
+    if (nt > 1) load_k(t_begin + 1, 1);
+    tile_landed();
+    qk(stage_k(0), s_a);
+    mask_scores(t_begin, s_a);
+    __syncthreads();   // K stage 0 is free for K(t_begin + 2)
+  }
+  {
+    constexpr std::true_type more{};
+    constexpr std::false_type last{};
+    int i = 0;
+    for (; i + 2 < nt; i += 2) {   // two steps per trip so that the score registers swap roles
+      step(i, s_a, s_b, more);
+      step(i + 1, s_b, s_a, more);
+    }
+    if (i + 1 < nt) {
+      step(i, s_a, s_b, more);
+      step(i + 1, s_b, s_a, last);
+    } else if (i < nt) {
+      step(i, s_a, s_b, last);
+    }
   }
 
   // ---- epilogue
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
-    const float l_tot = l_run[rb] + __shfl_xor(l_run[rb], 32);
+    float l_tot;
+    {
+      const int li = __float_as_int(l_run[rb]);
+      const auto sw = __builtin_amdgcn_permlane32_swap(li, li, false, false);
+      l_tot = __int_as_float(static_cast<int>(sw[0])) + __int_as_float(static_cast<int>(sw[1]));
+    }
     if (!valid_rb[rb]) continue;
     if (a.splits == 1) {
       const float inv = 1.f / l_tot;
@@ -369,8 +487,10 @@ __global__ __launch_bounds__(kThreads) void tree_attention_combine_kernel(AttnAr
 }
 
 template <int DH, int RB>
-hipError_t launch_one(const AttnArgs& a, hipStream_t s) {
-  const int row_tiles = (a.N_pad * a.G + 128 * RB - 1) / (128 * RB);
+hipError_t launch_one(const AttnArgs& a_in, hipStream_t s) {
+  AttnArgs a = a_in;
+  a.row_tiles = (a.N_pad * a.G + 128 * RB - 1) / (128 * RB);
+  a.total_items = a.row_tiles * a.splits * a.B * a.Hkv;
   auto kern = tree_attention_kernel<DH, RB>;
   static bool attr_set = false;
   if (!attr_set) {
@@ -379,7 +499,7 @@ hipError_t launch_one(const AttnArgs& a, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3(a.splits, row_tiles, a.B * a.Hkv), dim3(kThreads), Smem<DH>::BYTES, s, a);
+  hipLaunchKernelGGL(kern, dim3(8 * ((a.total_items + 7) / 8)), dim3(kThreads), Smem<DH>::BYTES, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (a.splits > 1) {
@@ -393,21 +513,28 @@ hipError_t launch_one(const AttnArgs& a, hipStream_t s) {
 
 }  // namespace
 
-// Launch plan: rows per workgroup (128 or 256) and the number of KV splits, chosen so that
-// the grid holds at least two workgroups per compute unit when the problem allows it.
+// Launch plan: the number of KV splits.  Two workgroups fit one compute unit, so the grid
+// aims at 512 workgroups; but a split must keep enough key tiles to amortise its fixed work
+// (query load, first tile, the partial result it writes and the merge reads back).
 void attention_plan(int B, int N_pad, int Hq, int Hkv, int Dh, int max_prefix_len, int* splits,
                     int* tiles_per_split, int* rows_pad) {
   (void)Dh;
+  static int min_tiles = 0;   // tuning knob: TALON_ATTN_MIN_TILES
+  if (min_tiles == 0) {
+    const char* e = getenv("TALON_ATTN_MIN_TILES");
+    min_tiles = e ? atoi(e) : 4;
+    if (min_tiles < 1) min_tiles = 4;
+  }
   const int G = Hq / Hkv;
   const int rows = N_pad * G;
-  const int rb = 1;
-  const int mt = 128 * rb;
+  const int mt = 128;
   const int row_tiles = (rows + mt - 1) / mt;
   const int tiles = (max_prefix_len + kKeyTile - 1) / kKeyTile + N_pad / kKeyTile;
   const long long base = static_cast<long long>(B) * Hkv * row_tiles;
   long long want = (512 + base - 1) / base;
+  const long long cap = tiles / min_tiles > 1 ? tiles / min_tiles : 1;
+  if (want > cap) want = cap;
   if (want < 1) want = 1;
-  if (want > tiles) want = tiles;
   const int tps = static_cast<int>((tiles + want - 1) / want);
   *tiles_per_split = tps;
   *splits = (tiles + tps - 1) / tps;

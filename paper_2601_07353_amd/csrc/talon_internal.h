@@ -72,6 +72,8 @@ struct AttnArgs {
   float* part_m;         // [B][Hkv][splits][rows_pad]      running max (base-2 units)
   float* part_l;         // [B][Hkv][splits][rows_pad]      running denominator
   int rows_pad;          // N_pad * G rounded up to the row tile
+  int row_tiles;         // row tiles per (sequence, KV head)
+  int total_items;       // row_tiles * splits * B * Hkv work items of the main kernel
 };
 
 // launchers (each checks nothing: arguments were validated by the ABI layer)

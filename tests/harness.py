@@ -130,8 +130,8 @@ def run_gpu_expand(cfg: WorkloadConfig, pool_dev, init_layers=1, mu=None, K_init
     K_init = cfg.K if K_init is None else K_init
     T.talon_tree_init(st, roots)
     if layerwise:
-        for _ in range(cfg.Dmax):
-            T.talon_expand_layer(pool_dev, st, cfg.K, cand, ws)
+        for d in range(cfg.Dmax):
+            T.talon_expand_layer(pool_dev, st, cfg.K, cand, ws, layer=d if d % 2 == 0 else -1)
             T.talon_select_budget(st, cfg.K, cand, mu, K_init, init_layers, cfg.Dmax)
     else:
         T.talon_expand_tree(pool_dev, st, cfg.K, mu, K_init, init_layers, cfg.Dmax, cand, ws)

@@ -48,7 +48,7 @@ P = 0x7000000  # aligned fake device address
 
 def expand_call(lib, st, logits=P, dtype=1, row_stride=1024, seq_stride=1024 * 64, row_mode=0, vocab=1024, k=4,
                 ws=P, ws_bytes=1 << 30, out=P):
-    return lib.talon_expand_layer(logits, dtype, row_stride, seq_stride, row_mode, ctypes.byref(st), vocab, k,
+    return lib.talon_expand_layer(logits, dtype, row_stride, seq_stride, row_mode, -1, ctypes.byref(st), vocab, k,
                                   out, out, out, out, out, out, ws, ws_bytes, None)
 
 
