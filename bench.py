@@ -36,6 +36,9 @@ def parse_args():
     ap.add_argument("--slots", type=int, default=0, help="rotating input sets (0 = enough to exceed 512 MB)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run plain device copies of 1 GiB (reads 1 GiB, writes 1 GiB each): the "
+                         "reference that scales the FETCH_SIZE / WRITE_SIZE counters of a --pmc run")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget for the oracle timing sample")
     return ap.parse_args()
 
@@ -76,6 +79,15 @@ def main():
     T.load_library()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read": 1 << 30, "bytes_written": 1 << 30, "copies": 10}}))
+        return
 
     elem = cfg.elem_bytes
     pool_bytes = cfg.B * cfg.N_pad * cfg.V * elem
