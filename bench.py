@@ -159,27 +159,23 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     steps_per_s = args.steps / (t1 - t0)
 
-    # ---- kernel timing region: the same K steps launched eagerly, layer by layer, with HIP
-    # events (on the launch stream) around every vocab-scan launch and around the
-    # tree-attention call.  Launch shapes are the ones talon_expand_tree uses.
+    # ---- kernel timing region: the same K steps launched eagerly, with HIP events (on the
+    # launch stream) around every vocab-scan launch (recorded by the library's measurement
+    # hook inside talon_expand_tree) and around the tree-attention call.
     layers = min(cfg.Dmax, cfg.N - 1)
-    ev_scan = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(layers)]
-               for _ in range(args.steps)]
     ev_attn = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    T.talon_profile_scan_launches(True)
     for i in range(args.steps):
         s = slots[i % n_slots]
-        T.talon_tree_init(st, roots)
-        for d in range(layers):
-            e0, e1 = ev_scan[i][d]
-            e0.record()
-            T.talon_expand_layer(s.logits, st, cfg.K, cand, ws_expand, layer=d)
-            e1.record()
-            T.talon_select_budget(st, cfg.K, cand, cfg.mu, cfg.K, 1, cfg.Dmax)
+        expand(s)
         T.talon_build_tree_mask(st, mask)
         e0, e1 = ev_attn[i]
         e0.record(); attention(s); e1.record()
     torch.cuda.synchronize()
-    scan_ms_step = float(np.mean([sum(e0.elapsed_time(e1) for e0, e1 in step_ev) for step_ev in ev_scan]))
+    scan_us, n_rec = T.talon_profile_read(args.steps * layers)
+    T.talon_profile_scan_launches(False)
+    assert n_rec == args.steps * layers, (n_rec, args.steps, layers)
+    scan_ms_step = float(np.sum(scan_us)) * 1e-3 / args.steps
     scan_ms_launch = scan_ms_step / layers
     attn_ms = float(np.mean([e0.elapsed_time(e1) for e0, e1 in ev_attn]))
 

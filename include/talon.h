@@ -139,9 +139,23 @@ int talon_select_budget(const talon_tree_state* st, int32_t k, const int32_t* ca
                         int32_t K_init, int32_t init_layers, int32_t max_depth, void* stream);
 
 /*
- * The whole while-loop of Alg. 2 enqueued in one call: max_depth times
- * { talon_expand_layer ; talon_select_budget }.  Finished sequences cost nothing in the
- * later iterations.  Arguments as in the two calls above.
+ * One iteration of the while-loop of Alg. 2 in a single launch: the vocabulary scan of
+ * talon_expand_layer with the budget selection of talon_select_budget run in its tail, per
+ * sequence, by the workgroup that writes the last row of that sequence's frontier.  Same
+ * results as the two calls in a row; arguments and errors as theirs.  `workspace` must have
+ * been initialised by talon_expand_workspace_init.
+ */
+int talon_expand_select_layer(const void* logits, int dtype, int64_t row_stride, int64_t seq_stride,
+                              int row_mode, int32_t layer, const talon_tree_state* st, int32_t vocab,
+                              int32_t k, float mu, int32_t K_init, int32_t init_layers,
+                              int32_t max_depth, int32_t* cand_token, float* cand_logit,
+                              float* cand_prob, double* cand_edge_logp, float* row_max,
+                              double* row_lse, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The whole while-loop of Alg. 2 enqueued in one call: min(max_depth, N-1) fused
+ * scan+selection launches (see talon_expand_select_layer).  Finished sequences cost nothing
+ * in the later iterations.  Arguments as in the calls above.
  */
 int talon_expand_tree(const void* logits, int dtype, int64_t row_stride, int64_t seq_stride,
                       int row_mode, const talon_tree_state* st, int32_t vocab, int32_t k,
@@ -149,6 +163,17 @@ int talon_expand_tree(const void* logits, int dtype, int64_t row_stride, int64_t
                       int32_t* cand_token, float* cand_logit, float* cand_prob,
                       double* cand_edge_logp, float* row_max, double* row_lse,
                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Measurement hook (no counterpart in the paper).  While enabled, talon_expand_tree and
+ * talon_expand_select_layer record a HIP event on the launch stream before and after every
+ * fused scan launch; talon_profile_read waits for them, writes the first `capacity`
+ * durations in microseconds (launch order) to the host array `durations_us`, stores the
+ * number of launches recorded since the last read in *n_launches and starts over.  Not to
+ * be enabled while a stream is being captured into a graph.  Not thread-safe.
+ */
+int talon_profile_scan_launches(int enable);
+int talon_profile_read(float* durations_us, int32_t capacity, int32_t* n_launches);
 
 /*
  * Tree attention mask (Fig. 5(b); App. B): bit j of row i is set iff node j is node i or

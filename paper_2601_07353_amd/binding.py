@@ -33,7 +33,8 @@ TALON_ROWS_BY_FRONTIER = 1
 
 EXPORTS = [
     "talon_last_error_string", "talon_tree_init", "talon_expand_workspace_bytes",
-    "talon_expand_workspace_init", "talon_expand_layer", "talon_select_budget", "talon_expand_tree",
+    "talon_expand_workspace_init", "talon_expand_layer", "talon_select_budget", "talon_expand_select_layer",
+    "talon_expand_tree", "talon_profile_scan_launches", "talon_profile_read",
     "talon_build_tree_mask", "talon_tree_attention_workspace_bytes", "talon_tree_attention",
 ]
 
@@ -76,6 +77,11 @@ def load_library() -> ctypes.CDLL:
     lib.talon_select_budget.argtypes = [POINTER(_CTreeState), c_int32, P, P, P, c_float, c_int32, c_int32, c_int32, P]
     lib.talon_expand_tree.argtypes = [P, c_int, c_int64, c_int64, c_int, POINTER(_CTreeState), c_int32, c_int32,
                                       c_float, c_int32, c_int32, c_int32, P, P, P, P, P, P, P, c_size_t, P]
+    lib.talon_expand_select_layer.argtypes = [P, c_int, c_int64, c_int64, c_int, c_int32, POINTER(_CTreeState),
+                                              c_int32, c_int32, c_float, c_int32, c_int32, c_int32, P, P, P, P, P, P,
+                                              P, c_size_t, P]
+    lib.talon_profile_scan_launches.argtypes = [c_int]
+    lib.talon_profile_read.argtypes = [POINTER(c_float), c_int32, POINTER(c_int32)]
     lib.talon_build_tree_mask.argtypes = [POINTER(_CTreeState), P, P]
     lib.talon_tree_attention_workspace_bytes.restype = c_size_t
     lib.talon_tree_attention_workspace_bytes.argtypes = [c_int32] * 6
@@ -197,6 +203,28 @@ def talon_expand_tree(logits, st: TreeState, k, mu, K_init, init_layers, max_dep
         c_float(mu), K_init, init_layers, max_depth, _ptr(cand.token), _ptr(cand.logit), _ptr(cand.prob),
         _ptr(cand.edge_logp), _ptr(cand.row_max), _ptr(cand.row_lse), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def talon_expand_select_layer(logits, st: TreeState, k, mu, K_init, init_layers, max_depth, cand: Candidates,
+                              workspace, layer=-1, row_mode=TALON_ROWS_BY_NODE, vocab=None, stream=None):
+    dt, row_stride, seq_stride, V = _logits_meta(logits)
+    _check(load_library().talon_expand_select_layer(
+        _ptr(logits), dt, row_stride, seq_stride, row_mode, layer, ctypes.byref(st.c), V if vocab is None else vocab,
+        k, c_float(mu), K_init, init_layers, max_depth, _ptr(cand.token), _ptr(cand.logit), _ptr(cand.prob),
+        _ptr(cand.edge_logp), _ptr(cand.row_max), _ptr(cand.row_lse), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def talon_profile_scan_launches(enable: bool):
+    _check(load_library().talon_profile_scan_launches(1 if enable else 0))
+
+
+def talon_profile_read(capacity: int):
+    """Durations (microseconds, launch order) of the fused scan launches recorded since the last read."""
+    buf = (c_float * max(capacity, 1))()
+    n = c_int32(0)
+    _check(load_library().talon_profile_read(buf, capacity, ctypes.byref(n)))
+    return [float(buf[i]) for i in range(min(n.value, capacity))], n.value
 
 
 def talon_build_tree_mask(st: TreeState, mask: torch.Tensor, stream=None):

@@ -8,6 +8,8 @@
 
 #include "talon_internal.h"
 
+#include <vector>
+
 namespace talon {
 
 static thread_local char g_err[512] = "";
@@ -47,7 +49,7 @@ int check_state(const talon_tree_state* st) {
 }
 
 struct ExpandLayout {
-  size_t off_max, off_sum, off_keys, off_ticket, total;
+  size_t off_max, off_sum, off_keys, off_ticket, off_seq_ticket, off_desc, total;
   int chunks;
 };
 
@@ -65,7 +67,9 @@ int expand_layout(int B, int N_pad, int vocab, int k, int dtype, ExpandLayout* L
   const size_t rows = static_cast<size_t>(B) * N_pad;
   L->chunks = static_cast<int>(chunks);
   L->off_ticket = 0;
-  L->off_max = align_up(rows * sizeof(int32_t), 256);
+  L->off_seq_ticket = align_up(rows * sizeof(int32_t), 256);
+  L->off_desc = L->off_seq_ticket + align_up(static_cast<size_t>(B) * sizeof(int32_t), 256);
+  L->off_max = L->off_desc + align_up(static_cast<size_t>(B) * 4 * sizeof(int32_t), 256);
   L->off_sum = L->off_max + align_up(rows * chunks * sizeof(float), 256);
   L->off_keys = L->off_sum + align_up(rows * chunks * sizeof(double), 256);
   L->total = L->off_keys + align_up(rows * chunks * k * sizeof(uint64_t), 256);
@@ -131,6 +135,10 @@ ExpandArgs make_expand_args(const void* logits, int64_t row_stride, int64_t seq_
   a.cand_edge_logp = cand_edge_logp; a.row_max = row_max; a.row_lse = row_lse;
   char* w = static_cast<char*>(workspace);
   a.ticket = reinterpret_cast<int32_t*>(w + L.off_ticket);
+  a.seq_ticket = reinterpret_cast<int32_t*>(w + L.off_seq_ticket);
+  a.desc = reinterpret_cast<int32_t*>(w + L.off_desc);
+  a.launch_idx = 0;
+  memset(&a.sel, 0, sizeof(a.sel));
   a.part_max = reinterpret_cast<float*>(w + L.off_max);
   a.part_sum = reinterpret_cast<double*>(w + L.off_sum);
   a.part_keys = reinterpret_cast<unsigned long long*>(w + L.off_keys);
@@ -197,7 +205,7 @@ int talon_expand_layer(const void* logits, int dtype, int64_t row_stride, int64_
   if (rc) return rc;
   const ExpandArgs a = make_expand_args(logits, row_stride, seq_stride, row_mode, st, vocab, k, cand_token,
                                         cand_logit, cand_prob, cand_edge_logp, row_max, row_lse, workspace, L);
-  return check_hip(launch_expand(a, dtype, expand_grid(st, L.chunks, layer < 0 ? -1 : layer, k, k, 0), static_cast<hipStream_t>(stream)), "expand launch");
+  return check_hip(launch_expand(a, dtype, expand_grid(st, L.chunks, layer < 0 ? -1 : layer, k, k, 0), false, static_cast<hipStream_t>(stream)), "expand launch");
 }
 
 int talon_select_budget(const talon_tree_state* st, int32_t k, const int32_t* cand_token, const float* cand_prob,
@@ -211,31 +219,108 @@ int talon_select_budget(const talon_tree_state* st, int32_t k, const int32_t* ca
   return check_hip(launch_select(a, static_cast<hipStream_t>(stream)), "select launch");
 }
 
-int talon_expand_tree(const void* logits, int dtype, int64_t row_stride, int64_t seq_stride, int row_mode,
-                      const talon_tree_state* st, int32_t vocab, int32_t k, float mu, int32_t K_init,
-                      int32_t init_layers, int32_t max_depth, int32_t* cand_token, float* cand_logit,
-                      float* cand_prob, double* cand_edge_logp, float* row_max, double* row_lse,
-                      void* workspace, size_t workspace_bytes, void* stream) {
+namespace {
+
+// Measurement hook state: pairs of events recorded around each fused scan launch.
+struct ScanProfile {
+  bool enabled = false;
+  std::vector<hipEvent_t> events;   // pool, two per launch
+  size_t used = 0;
+};
+ScanProfile g_profile;
+
+hipError_t profile_record(hipStream_t s) {
+  if (g_profile.used == g_profile.events.size()) {
+    hipEvent_t e;
+    hipError_t err = hipEventCreate(&e);
+    if (err != hipSuccess) return err;
+    g_profile.events.push_back(e);
+  }
+  return hipEventRecord(g_profile.events[g_profile.used++], s);
+}
+
+// Fused launches of `layers` consecutive layers starting from the public tree state.
+int run_fused_layers(const void* logits, int dtype, int64_t row_stride, int64_t seq_stride, int row_mode,
+                     int first_layer, int layers, const talon_tree_state* st, int32_t vocab, int32_t k, float mu,
+                     int32_t K_init, int32_t init_layers, int32_t max_depth, int32_t* cand_token, float* cand_logit,
+                     float* cand_prob, double* cand_edge_logp, float* row_max, double* row_lse, void* workspace,
+                     size_t workspace_bytes, void* stream) {
   ExpandLayout L;
   int rc = check_expand_args(logits, dtype, row_stride, seq_stride, row_mode, st, vocab, k, cand_token, cand_logit,
                              cand_prob, cand_edge_logp, row_max, row_lse, workspace, workspace_bytes, &L);
   if (rc) return rc;
   rc = check_select_args(st, k, cand_token, cand_prob, cand_edge_logp, mu, K_init, init_layers, max_depth);
   if (rc) return rc;
-  const ExpandArgs ea = make_expand_args(logits, row_stride, seq_stride, row_mode, st, vocab, k, cand_token,
-                                         cand_logit, cand_prob, cand_edge_logp, row_max, row_lse, workspace, L);
+  ExpandArgs ea = make_expand_args(logits, row_stride, seq_stride, row_mode, st, vocab, k, cand_token,
+                                   cand_logit, cand_prob, cand_edge_logp, row_max, row_lse, workspace, L);
   SelectArgs sa;
   sa.st = *st; sa.k = k; sa.cand_token = cand_token; sa.cand_prob = cand_prob; sa.cand_edge_logp = cand_edge_logp;
   sa.log_mu = log(static_cast<double>(mu)); sa.K_init = K_init; sa.init_layers = init_layers; sa.max_depth = max_depth;
+  ea.sel = sa;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  // a tree of N nodes has at most N-1 layers: later iterations could not add anything
-  const int layers = max_depth < st->N - 1 ? max_depth : (st->N > 1 ? st->N - 1 : 0);
+  if (layers <= 0) return TALON_OK;
+  rc = check_hip(launch_desc_init(*st, ea.desc, s), "descriptor init launch");
+  if (rc) return rc;
   for (int d = 0; d < layers; ++d) {
-    rc = check_hip(launch_expand(ea, dtype, expand_grid(st, L.chunks, d, k, K_init, init_layers), s), "expand launch");
+    ea.launch_idx = d;
+    const int layer = first_layer < 0 ? -1 : first_layer + d;
+    if (g_profile.enabled && (rc = check_hip(profile_record(s), "profile event"))) return rc;
+    rc = check_hip(launch_expand(ea, dtype, expand_grid(st, L.chunks, layer, k, K_init, init_layers), true, s), "expand launch");
     if (rc) return rc;
-    rc = check_hip(launch_select(sa, s), "select launch");
-    if (rc) return rc;
+    if (g_profile.enabled && (rc = check_hip(profile_record(s), "profile event"))) return rc;
   }
+  return TALON_OK;
+}
+
+}  // namespace
+
+int talon_expand_select_layer(const void* logits, int dtype, int64_t row_stride, int64_t seq_stride, int row_mode,
+                              int32_t layer, const talon_tree_state* st, int32_t vocab, int32_t k, float mu,
+                              int32_t K_init, int32_t init_layers, int32_t max_depth, int32_t* cand_token,
+                              float* cand_logit, float* cand_prob, double* cand_edge_logp, float* row_max,
+                              double* row_lse, void* workspace, size_t workspace_bytes, void* stream) {
+  return run_fused_layers(logits, dtype, row_stride, seq_stride, row_mode, layer, 1, st, vocab, k, mu, K_init,
+                          init_layers, max_depth, cand_token, cand_logit, cand_prob, cand_edge_logp, row_max,
+                          row_lse, workspace, workspace_bytes, stream);
+}
+
+int talon_expand_tree(const void* logits, int dtype, int64_t row_stride, int64_t seq_stride, int row_mode,
+                      const talon_tree_state* st, int32_t vocab, int32_t k, float mu, int32_t K_init,
+                      int32_t init_layers, int32_t max_depth, int32_t* cand_token, float* cand_logit,
+                      float* cand_prob, double* cand_edge_logp, float* row_max, double* row_lse,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+  // a tree of N nodes has at most N-1 layers: later iterations could not add anything.
+  // One launch per layer: the scan runs each sequence's budget selection in its tail.
+  int layers = 0;
+  if (st && max_depth > 0) layers = max_depth < st->N - 1 ? max_depth : (st->N > 1 ? st->N - 1 : 0);
+  return run_fused_layers(logits, dtype, row_stride, seq_stride, row_mode, 0, layers, st, vocab, k, mu, K_init,
+                          init_layers, max_depth, cand_token, cand_logit, cand_prob, cand_edge_logp, row_max,
+                          row_lse, workspace, workspace_bytes, stream);
+}
+
+int talon_profile_scan_launches(int enable) {
+  g_profile.enabled = enable != 0;
+  g_profile.used = 0;
+  return TALON_OK;
+}
+
+int talon_profile_read(float* durations_us, int32_t capacity, int32_t* n_launches) {
+  if (!n_launches || (capacity > 0 && !durations_us) || capacity < 0) {
+    set_error("talon_profile_read: null output or negative capacity");
+    return TALON_ERR_INVALID_ARG;
+  }
+  const size_t pairs = g_profile.used / 2;
+  *n_launches = static_cast<int32_t>(pairs);
+  const size_t n = pairs < static_cast<size_t>(capacity) ? pairs : static_cast<size_t>(capacity);
+  for (size_t i = 0; i < n; ++i) {
+    int rc = check_hip(hipEventSynchronize(g_profile.events[2 * i + 1]), "profile event synchronize");
+    if (rc) return rc;
+    float ms = 0.f;
+    rc = check_hip(hipEventElapsedTime(&ms, g_profile.events[2 * i], g_profile.events[2 * i + 1]), "profile elapsed time");
+    if (rc) return rc;
+    durations_us[i] = ms * 1000.f;
+  }
+  g_profile.used = 0;
   return TALON_OK;
 }
 

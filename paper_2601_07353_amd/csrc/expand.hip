@@ -31,8 +31,7 @@
 // Exactness.  Ordering is by the 64-bit integer key (sortable(logit) << 32 | ~token), so
 // the order (logit descending, token ascending) is exact; floating point only enters the
 // softmax statistics.
-#include "device_utils.h"
-#include "talon_internal.h"
+#include "select_device.h"
 
 namespace talon {
 
@@ -145,6 +144,9 @@ __device__ __forceinline__ float key_logit(unsigned long long key) {
 
 // Write the outputs of one row from its candidate keys (in LDS) and softmax statistics.
 // `keys` holds `lists` lists of k keys, each sorted in descending order.
+// FUSED: the candidates are read by another workgroup of this launch (the one that runs the
+// sequence's selection), so they are stored at the device-coherent level.
+template <bool FUSED>
 __device__ __forceinline__ void write_row(const ExpandArgs& a, int b, int out_row, const unsigned long long* keys,
                                           int lists, float m, double sum) {
   const int tid = threadIdx.x;
@@ -179,19 +181,33 @@ __device__ __forceinline__ void write_row(const ExpandArgs& a, int b, int out_ro
       if (ki != 0ull && r < k) {
         const float lg = key_logit(ki);
         const double edge = static_cast<double>(lg) - lse;
-        a.cand_token[ob + r] = static_cast<int32_t>(0xFFFFFFFFu - static_cast<uint32_t>(ki));
+        const int32_t tok = static_cast<int32_t>(0xFFFFFFFFu - static_cast<uint32_t>(ki));
+        const float pr = __expf(static_cast<float>(edge));
         a.cand_logit[ob + r] = lg;
-        a.cand_edge_logp[ob + r] = edge;
-        a.cand_prob[ob + r] = static_cast<float>(exp(edge));
+        if constexpr (FUSED) {
+          store_agent(a.cand_token + ob + r, tok);
+          store_agent(a.cand_edge_logp + ob + r, edge);
+          store_agent(a.cand_prob + ob + r, pr);
+        } else {
+          a.cand_token[ob + r] = tok;
+          a.cand_edge_logp[ob + r] = edge;
+          a.cand_prob[ob + r] = pr;
+        }
       }
     }
   }
   const int valid = a.vocab < k ? a.vocab : k;
   if (tid >= valid && tid < k) {
-    a.cand_token[ob + tid] = -1;
     a.cand_logit[ob + tid] = kNegInf;
-    a.cand_edge_logp[ob + tid] = -__builtin_huge_val();
-    a.cand_prob[ob + tid] = 0.f;
+    if constexpr (FUSED) {
+      store_agent(a.cand_token + ob + tid, -1);
+      store_agent(a.cand_edge_logp + ob + tid, -__builtin_huge_val());
+      store_agent(a.cand_prob + ob + tid, 0.f);
+    } else {
+      a.cand_token[ob + tid] = -1;
+      a.cand_edge_logp[ob + tid] = -__builtin_huge_val();
+      a.cand_prob[ob + tid] = 0.f;
+    }
   }
   if (tid == 0) {
     a.row_max[out_row] = m;
@@ -200,14 +216,27 @@ __device__ __forceinline__ void write_row(const ExpandArgs& a, int b, int out_ro
   }
 }
 
-template <int EPL>
+template <int EPL, bool FUSED>
 __global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
   constexpr int NX = kScanTiles * EPL;          // logits per thread per block
   constexpr int BLOCK = kThreads * NX;          // logits per block
   __shared__ int s_prefix[TALON_B_MAX + 1];     // exclusive prefix of frontier sizes
-  __shared__ uint4 s_hitv[4][kHitCap];              // buffered vectors, per wavefront; later row-merge staging
-  __shared__ int s_hith[4][kHitCap];                //   ... and tile * 64 + lane of each
-  __shared__ unsigned long long s_ck[4][kSubKeys];  // ranking scratch per wavefront
+  // One LDS pool: the scan's buffers (buffered vectors per wavefront, their tile*64+lane tags,
+  // ranking scratch per wavefront; the vector buffers double as row-merge staging) and, in
+  // fused mode, the key array and histogram of the budget selection, which runs when the
+  // scan buffers are idle.
+  constexpr int kHitvBytes = sizeof(uint4) * 4 * kHitCap;
+  constexpr int kHithBytes = sizeof(int) * 4 * kHitCap;
+  constexpr int kCkBytes = sizeof(unsigned long long) * 4 * kSubKeys;
+  constexpr int kScanBytes = kHitvBytes + kHithBytes + kCkBytes;
+  constexpr int kSelBytes = sizeof(unsigned long long) * kSelectKeySlots + sizeof(int) * 256;
+  constexpr int kPoolBytes = (FUSED && kSelBytes > kScanBytes) ? kSelBytes : kScanBytes;
+  __shared__ __attribute__((aligned(16))) unsigned char s_pool[kPoolBytes];
+  uint4 (*s_hitv)[kHitCap] = reinterpret_cast<uint4 (*)[kHitCap]>(s_pool);
+  int (*s_hith)[kHitCap] = reinterpret_cast<int (*)[kHitCap]>(s_pool + kHitvBytes);
+  unsigned long long (*s_ck)[kSubKeys] = reinterpret_cast<unsigned long long (*)[kSubKeys]>(s_pool + kHitvBytes + kHithBytes);
+  __shared__ unsigned long long s_red_u64[8];
+  __shared__ int s_misc[2];
   __shared__ unsigned long long s_topw[4][TALON_K_MAX]; // k best keys of each wavefront, sorted
   __shared__ unsigned long long s_top[TALON_K_MAX];
   __shared__ double s_red_f64[8];
@@ -230,10 +259,16 @@ __global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
   {
     static_assert(TALON_B_MAX <= kThreads, "one thread per sequence");
     int c = 0;
-    if (tid < a.B) {  // both loads are issued together; the select below is register-only
-      const uint32_t stat = a.status[tid];
-      const int fc = a.frontier_count[tid];
-      c = (stat & kDoneMask) ? 0 : fc;
+    if (tid < a.B) {
+      if constexpr (FUSED) {
+        c = a.desc[((a.launch_idx & 1) * a.B + tid) * 2 + 1];
+      } else {  // both loads are issued together; the select below is register-only
+        const uint32_t stat = a.status[tid];
+        const int fc = a.frontier_count[tid];
+        c = (stat & kDoneMask) ? 0 : fc;
+      }
+      // a finished sequence gets no selection in this launch: carry its empty frontier over
+      if (FUSED && blockIdx.x == 0 && c == 0) a.desc[(((a.launch_idx + 1) & 1) * a.B + tid) * 2 + 1] = 0;
     }
     int total;
     const int base = block_exclusive_scan_i32(c, s_red_i32, &total);
@@ -269,7 +304,8 @@ __global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
     }
     const int b = lo;
     const int local = rg - s_prefix[b];
-    const int node = a.frontier_begin[b] + local;
+    const int fbegin = FUSED ? a.desc[((a.launch_idx & 1) * a.B + b) * 2] : a.frontier_begin[b];
+    const int node = fbegin + local;
     const int in_row = a.row_mode == TALON_ROWS_BY_FRONTIER ? local : node;
     const char* row = static_cast<const char*>(a.logits) +
                       (static_cast<int64_t>(b) * a.seq_stride + static_cast<int64_t>(in_row) * a.row_stride) * (16 / EPL);
@@ -466,7 +502,8 @@ __global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
     // ---- wavefront statistics
     {
       const float wmax = wave_max_f32(m_l);
-      const double sl = (m_l == kNegInf) ? 0.0 : s_l * exp(static_cast<double>(m_l) - static_cast<double>(wmax));
+      // rescale factors are <= 1 and only need fp32 accuracy: their error is relative to a part of the sum
+      const double sl = (m_l == kNegInf) ? 0.0 : s_l * static_cast<double>(__expf(m_l - wmax));
       const double wsum = wave_sum_f64(sl);
       if (lane == 0) { s_wmax[wave] = wmax; s_wsum[wave] = wsum; s_wcnt[wave] = tcnt; }
     }
@@ -490,12 +527,14 @@ __global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
     double csum = 0.0;
 #pragma unroll
     for (int w = 0; w < 4; ++w)
-      if (s_wmax[w] != kNegInf) csum += s_wsum[w] * exp(static_cast<double>(s_wmax[w]) - static_cast<double>(cm));
+      if (s_wmax[w] != kNegInf) csum += s_wsum[w] * static_cast<double>(__expf(s_wmax[w] - cm));
     __syncthreads();
     PHASE(5);
 
+    bool row_written = false;   // this workgroup has just written a whole row's outputs
     if (chunks == 1) {
-      write_row(a, b, out_row, s_top, 1, cm, csum);
+      write_row<FUSED>(a, b, out_row, s_top, 1, cm, csum);
+      row_written = true;
     } else {
       unsigned long long* pk = a.part_keys + (static_cast<size_t>(out_row) * blocks_per_row + ch) * k;
       if (tid < k) store_agent(pk + tid, s_top[tid]);
@@ -524,14 +563,42 @@ __global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
         double sum = 0.0;
         for (int c = tid; c < chunks; c += kThreads) {
           const float mc = load_agent(pm + c);
-          if (mc != kNegInf) sum += load_agent(ps + c) * exp(static_cast<double>(mc) - static_cast<double>(m));
+          if (mc != kNegInf) sum += load_agent(ps + c) * static_cast<double>(__expf(mc - m));
         }
         sum = block_sum_f64(sum, s_red_f64);
         PHASE(7);
         PHASE_MAX(12);
-        write_row(a, b, out_row, s_keys, chunks, m, sum);
+        write_row<FUSED>(a, b, out_row, s_keys, chunks, m, sum);
         PHASE_MAX(13);
         if (tid == 0) store_agent(a.ticket + out_row, 0);  // leave the workspace clean for the next layer
+        row_written = true;
+      }
+    }
+    if constexpr (FUSED) {
+      if (row_written) {
+        // ---- sequence ticket: the workgroup that writes the last row of a sequence's frontier
+        // runs that sequence's budget selection
+        const int F = s_prefix[b + 1] - s_prefix[b];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __syncthreads();
+        if (tid == 0) {
+          const int old = __hip_atomic_fetch_add(&a.seq_ticket[b], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          s_last = (old == F - 1) ? 1 : 0;
+          if (s_last) store_agent(a.seq_ticket + b, 0);
+        }
+        __syncthreads();
+        if (s_last) {
+          const uint32_t status = __hip_atomic_load(&a.status[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          int* next_desc = a.desc + (((a.launch_idx + 1) & 1) * a.B + b) * 2;
+          if (status & TALON_STATUS_BAD_ROW) {   // a row could not be normalised: stop the sequence here
+            if (tid == 0) { a.sel.st.frontier_count[b] = 0; next_desc[0] = fbegin; next_desc[1] = 0; }
+          } else {
+            const SelectLds lds{reinterpret_cast<unsigned long long*>(s_pool),
+                                reinterpret_cast<int*>(s_pool + sizeof(unsigned long long) * kSelectKeySlots),
+                                s_red_u64, s_red_i32, s_misc};
+            select_sequence<true>(a.sel, b, F, fbegin, status, lds, next_desc);
+          }
+        }
       }
     }
     __syncthreads();  // s_keys / s_top / s_w* are reused by the next item
@@ -567,11 +634,27 @@ __global__ __launch_bounds__(kThreads) void tree_init_kernel(talon_tree_state st
 
 int expand_chunk_elems(int dtype) { return dtype == TALON_DTYPE_F32 ? kChunkBytes / 4 : kChunkBytes / 2; }
 
-hipError_t launch_expand(const ExpandArgs& a, int dtype, int grid, hipStream_t s) {
-  if (dtype == TALON_DTYPE_F32)
-    hipLaunchKernelGGL(expand_kernel<4>, dim3(grid), dim3(kThreads), 0, s, a);
-  else
-    hipLaunchKernelGGL(expand_kernel<8>, dim3(grid), dim3(kThreads), 0, s, a);
+// Frontier descriptors of the first fused launch, from the public tree state.
+__global__ void desc_init_kernel(talon_tree_state st, int32_t* desc) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= st.B) return;
+  desc[2 * b] = st.frontier_begin[b];
+  desc[2 * b + 1] = (st.status[b] & kDoneMask) ? 0 : st.frontier_count[b];
+}
+
+hipError_t launch_desc_init(const talon_tree_state& st, int32_t* desc, hipStream_t s) {
+  hipLaunchKernelGGL(desc_init_kernel, dim3((st.B + 255) / 256), dim3(256), 0, s, st, desc);
+  return hipGetLastError();
+}
+
+hipError_t launch_expand(const ExpandArgs& a, int dtype, int grid, bool fused, hipStream_t s) {
+  if (dtype == TALON_DTYPE_F32) {
+    if (fused) hipLaunchKernelGGL((expand_kernel<4, true>), dim3(grid), dim3(kThreads), 0, s, a);
+    else hipLaunchKernelGGL((expand_kernel<4, false>), dim3(grid), dim3(kThreads), 0, s, a);
+  } else {
+    if (fused) hipLaunchKernelGGL((expand_kernel<8, true>), dim3(grid), dim3(kThreads), 0, s, a);
+    else hipLaunchKernelGGL((expand_kernel<8, false>), dim3(grid), dim3(kThreads), 0, s, a);
+  }
   return hipGetLastError();
 }
 

@@ -1,0 +1,195 @@
+// Budget selection of one layer for one sequence, as a workgroup-wide device function shared
+// by the stand-alone select kernel and by the vocab-scan kernel that runs it in its tail.
+//
+// Hybrid allocation of the remaining node budget (Sec. 5.2; Alg. 2 "Hybrid Expansion
+// Strategy" and "Budget Check"), all candidates of the layer resident in LDS:
+//   score(u) = logp[v] + edge_logp(v, rank)                    (log of p(u) = p(v) P(w|x<=v))
+//   layer < init_layers: keep the K_init best                   (Eq. 5)
+//   else: anchor m_d = max score, keep score >= log(mu) + m_d   (Eq. 4)
+//   more than R = N - |T| left: keep the R best                 (budget check)
+// The R-th best score is found by an 8-pass radix select over order-preserving 64-bit
+// images of the fp64 scores; equal scores are taken in (parent, rank) order.  Kept
+// candidates are appended by a prefix-sum compaction, which yields node ids ordered
+// (parent ascending, rank ascending) without a sort.
+#pragma once
+
+#include "device_utils.h"
+#include "talon_internal.h"
+
+namespace talon {
+
+constexpr int kMaxCand = TALON_N_MAX * TALON_K_MAX;  // frontier <= N-1 rows of k candidates
+constexpr int kPerThread = kMaxCand / kThreads;      // at most 16 consecutive candidates per thread
+constexpr int kSelectKeySlots = kThreads * (kPerThread + 1);
+
+// LDS the selection needs; the caller provides it (the scan kernel carves it out of buffers
+// that are idle by then).
+struct SelectLds {
+  unsigned long long* key;      // [kSelectKeySlots]
+  int* hist;                    // [256]
+  unsigned long long* red_u64;  // [8]
+  int* red_i32;                 // [8]
+  int* misc;                    // [2]
+};
+
+__device__ __forceinline__ double unsortable_f64(unsigned long long s) {
+  const unsigned long long u = (s >> 63) ? (s ^ 0x8000000000000000ull) : ~s;
+  return __longlong_as_double(static_cast<long long>(u));
+}
+
+// AGENT: the candidates were written by other workgroups of the same launch; read them at
+// the device-coherent level.
+template <bool AGENT, typename T>
+__device__ __forceinline__ T ld(const T* p) {
+  if constexpr (AGENT) return __hip_atomic_load(const_cast<T*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else return *p;
+}
+
+// Runs on all 256 threads of the workgroup.  F, fb: the frontier being expanded.  next_desc
+// (optional): receives {begin, count} of the new frontier, count 0 if the sequence is done.
+template <bool AGENT>
+__device__ __forceinline__ void select_sequence(const SelectArgs& a, int b, int F, int fb, uint32_t status,
+                                                const SelectLds& lds, int* next_desc) {
+  const talon_tree_state& st = a.st;
+  const int tid = threadIdx.x;
+  unsigned long long* s_key = lds.key;
+  int* s_hist = lds.hist;
+  unsigned long long* s_red_u64 = lds.red_u64;
+  int* s_red_i32 = lds.red_i32;
+  int& s_digit = lds.misc[0];
+  int& s_remaining = lds.misc[1];
+  const int n = st.n_nodes[b];
+  const int d = st.depth_cur[b];
+  const int R = st.N - n;
+  const int k = a.k;
+  const int C = F * k;
+  const size_t base = static_cast<size_t>(b) * st.N_pad;
+
+  // Thread t owns the `per` consecutive candidates [t*per, t*per+per) of the flat
+  // (parent, rank) order.  Its LDS slots start at t*stride with stride odd, so that the
+  // 64-bit accesses of a wavefront fall on distinct banks.
+  const int per = (C + kThreads - 1) / kThreads;
+  const int stride = per | 1;
+  const int c_begin = tid * per;
+  unsigned long long* my = s_key + tid * stride;
+
+  // ---- path scores of the pool, as sortable keys (0 = no candidate)
+  unsigned long long anchor_key = 0ull;
+  for (int i = 0; i < per; ++i) {
+    const int c = c_begin + i;
+    unsigned long long key = 0ull;
+    if (c < C) {
+      const int p = c / k;
+      const size_t ci = (base + fb + p) * k + (c - p * k);
+      const double s = st.logp[base + fb + p] + ld<AGENT, double>(a.cand_edge_logp + ci);
+      if (ld<AGENT, int32_t>(a.cand_token + ci) >= 0 && s == s) {
+        key = sortable_u64(s);
+        if (key == 0ull) key = 1ull;
+      }
+    }
+    my[i] = key;
+    anchor_key = key > anchor_key ? key : anchor_key;
+  }
+  anchor_key = block_max_u64(anchor_key, s_red_u64);
+
+  const bool init = d < a.init_layers;
+  const int limit = init ? (a.K_init < R ? a.K_init : R) : R;
+  unsigned long long thr_key = 1ull;
+  if (!init && anchor_key != 0ull) {
+    thr_key = sortable_u64(a.log_mu + unsortable_f64(anchor_key));
+    if (thr_key == 0ull) thr_key = 1ull;
+  }
+
+  int n_pass_local = 0;
+  for (int i = 0; i < per; ++i) n_pass_local += (my[i] >= thr_key) ? 1 : 0;
+  const int n_pass = block_sum_i32(n_pass_local, s_red_i32);
+
+  unsigned long long T = thr_key;     // keep key > T, and the first need_eq keys == T
+  int need_eq = 0x7FFFFFFF;
+  if (n_pass > limit) {
+    // ---- radix select: the limit-th largest key, 8 bits per pass from the top
+    unsigned long long prefix = 0ull;
+    int remaining = limit;
+    for (int pass = 0; pass < 8; ++pass) {
+      const int shift = 56 - 8 * pass;
+      s_hist[tid] = 0;
+      __syncthreads();
+      for (int i = 0; i < per; ++i) {
+        const unsigned long long key = my[i];
+        const bool match = pass == 0 || ((key ^ prefix) >> ((shift + 8) & 63)) == 0ull;
+        if (match && key != 0ull) atomicAdd(&s_hist[static_cast<int>(key >> shift) & 255], 1);
+      }
+      __syncthreads();
+      if (tid < 64) {
+        // lane l owns digits 255-4l .. 252-4l, walked from the largest digit down
+        int h[4], lane_sum = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { h[j] = s_hist[255 - 4 * tid - j]; lane_sum += h[j]; }
+        const int incl = wave_inclusive_scan_i32(lane_sum);
+        const unsigned long long hit = __ballot(incl >= remaining);
+        const int first = __ffsll(static_cast<long long>(hit)) - 1;
+        if (tid == first) {
+          int before = incl - lane_sum;
+          int dg = 255 - 4 * tid;
+#pragma unroll
+          for (int j = 0; j < 3; ++j) {
+            if (before + h[j] < remaining) { before += h[j]; --dg; } else break;
+          }
+          s_digit = dg;
+          s_remaining = remaining - before;
+        }
+      }
+      __syncthreads();
+      prefix |= static_cast<unsigned long long>(s_digit) << shift;
+      remaining = s_remaining;
+      __syncthreads();
+    }
+    T = prefix;
+    need_eq = remaining;
+  }
+
+  // ---- keep flags, ranks among equal keys, compaction
+  int eq_local = 0;
+  for (int i = 0; i < per; ++i) eq_local += (my[i] == T) ? 1 : 0;
+  int eq_total;
+  int eq_rank = block_exclusive_scan_i32(eq_local, s_red_i32, &eq_total);
+  unsigned int keep_bits = 0u;
+  int keep_local = 0;
+  for (int i = 0; i < per; ++i) {
+    const unsigned long long key = my[i];
+    bool keep = key > T;
+    if (key == T) { keep = eq_rank < need_eq; ++eq_rank; }
+    if (key == 0ull) keep = false;
+    if (keep) { keep_bits |= 1u << i; ++keep_local; }
+  }
+  int n_keep;
+  int pos = block_exclusive_scan_i32(keep_local, s_red_i32, &n_keep);
+  for (int i = 0; i < per; ++i) {
+    if (keep_bits & (1u << i)) {
+      const int c = c_begin + i;
+      const int p = c / k;
+      const size_t ci = (base + fb + p) * k + (c - p * k);
+      const size_t o = base + n + pos;
+      st.token[o] = ld<AGENT, int32_t>(a.cand_token + ci);
+      st.parent[o] = fb + p;
+      st.depth[o] = d + 1;
+      st.prob[o] = ld<AGENT, float>(a.cand_prob + ci);
+      st.logp[o] = st.logp[base + fb + p] + ld<AGENT, double>(a.cand_edge_logp + ci);
+      ++pos;
+    }
+  }
+  if (tid == 0) {
+    const int n_new = n + n_keep;
+    uint32_t s = status;
+    if (n_new >= st.N) s |= TALON_STATUS_DONE_BUDGET;
+    else if (d + 1 >= a.max_depth) s |= TALON_STATUS_DONE_DEPTH;
+    st.n_nodes[b] = n_new;
+    st.frontier_begin[b] = n;
+    st.frontier_count[b] = n_keep;
+    st.depth_cur[b] = d + 1;
+    st.status[b] = s;
+    if (next_desc) { next_desc[0] = n; next_desc[1] = (s & kDoneMask) ? 0 : n_keep; }
+  }
+}
+
+}  // namespace talon

@@ -19,6 +19,16 @@ int check_hip(hipError_t e, const char* what);
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+struct SelectArgs {
+  talon_tree_state st;
+  int k;
+  const int32_t* cand_token;
+  const float* cand_prob;
+  const double* cand_edge_logp;
+  double log_mu;
+  int K_init, init_layers, max_depth;
+};
+
 struct ExpandArgs {
   const void* logits;
   int64_t row_stride, seq_stride;
@@ -39,16 +49,16 @@ struct ExpandArgs {
   double* part_sum;      // [rows][chunks]
   unsigned long long* part_keys;  // [rows][chunks][k]
   int32_t* ticket;       // [rows]
-};
-
-struct SelectArgs {
-  talon_tree_state st;
-  int k;
-  const int32_t* cand_token;
-  const float* cand_prob;
-  const double* cand_edge_logp;
-  double log_mu;
-  int K_init, init_layers, max_depth;
+  // Fused mode (the scan runs the budget selection of a sequence in its tail, when the last
+  // row of that sequence's frontier has been written): selection parameters, the index of
+  // this launch in the loop, per-sequence row tickets and ping-pong frontier descriptors
+  // {begin, count} [2][B]: launch i reads parity i&1 (parity 0 of launch 0 is copied from the public tree state) and
+  // its selections write parity (i+1)&1, so a workgroup that starts late still sees the
+  // frontier of its own layer.
+  SelectArgs sel;
+  int launch_idx;
+  int32_t* seq_ticket;   // [B]
+  int32_t* desc;         // [2][B][2]
 };
 
 struct AttnArgs {
@@ -79,7 +89,8 @@ struct AttnArgs {
 // launchers (each checks nothing: arguments were validated by the ABI layer)
 hipError_t launch_tree_init(const talon_tree_state& st, const int32_t* root_token, hipStream_t s);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
-hipError_t launch_expand(const ExpandArgs& a, int dtype, int grid, hipStream_t s);
+hipError_t launch_desc_init(const talon_tree_state& st, int32_t* desc, hipStream_t s);
+hipError_t launch_expand(const ExpandArgs& a, int dtype, int grid, bool fused, hipStream_t s);
 hipError_t launch_select(const SelectArgs& a, hipStream_t s);
 hipError_t launch_mask(const talon_tree_state& st, uint64_t* mask, hipStream_t s);
 hipError_t launch_attention(const AttnArgs& a, hipStream_t s);

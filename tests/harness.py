@@ -117,8 +117,9 @@ def bf16_to_device(bits: np.ndarray):
 
 
 def run_gpu_expand(cfg: WorkloadConfig, pool_dev, init_layers=1, mu=None, K_init=None, layerwise=False):
-    """Whole expansion loop on the GPU.  layerwise=True drives the two per-layer entry points
-    from the host instead of the single talon_expand_tree call."""
+    """Whole expansion loop on the GPU.  layerwise=True (or "split") drives the two per-layer
+    entry points from the host, layerwise="fused" the one-launch-per-layer entry point, instead
+    of the single talon_expand_tree call."""
     import torch
     import paper_2601_07353_amd as T
     st = T.TreeState(cfg.B, cfg.N)
@@ -129,7 +130,11 @@ def run_gpu_expand(cfg: WorkloadConfig, pool_dev, init_layers=1, mu=None, K_init
     mu = cfg.mu if mu is None else mu
     K_init = cfg.K if K_init is None else K_init
     T.talon_tree_init(st, roots)
-    if layerwise:
+    if layerwise == "fused":
+        for d in range(cfg.Dmax):
+            T.talon_expand_select_layer(pool_dev, st, cfg.K, mu, K_init, init_layers, cfg.Dmax, cand, ws,
+                                        layer=d if d % 2 == 0 else -1)
+    elif layerwise:
         for d in range(cfg.Dmax):
             T.talon_expand_layer(pool_dev, st, cfg.K, cand, ws, layer=d if d % 2 == 0 else -1)
             T.talon_select_budget(st, cfg.K, cand, mu, K_init, init_layers, cfg.Dmax)

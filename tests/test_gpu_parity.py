@@ -39,13 +39,23 @@ def test_c1_tiny_step():
     assert ref["trees"][0].n == 16
 
 
-def test_c1_layerwise_entry_points_match_single_call():
+@pytest.mark.parametrize("mode", ["split", "fused"])
+def test_c1_layerwise_entry_points_match_single_call(mode):
     cfg = CONFIGS["c1"]
     seeds = admissible_seeds(cfg)
-    a = H.run_gpu_step(cfg, seeds, with_attention=False, layerwise=True)
+    a = H.run_gpu_step(cfg, seeds, with_attention=False, layerwise=mode)
     b = H.run_gpu_step(cfg, seeds, with_attention=False, layerwise=False)
     for key in ("token", "parent", "depth", "n_nodes", "status", "mask", "prob", "logp"):
         np.testing.assert_array_equal(a[key], b[key])
+
+
+@pytest.mark.parametrize("mode", ["split", "fused"])
+def test_layerwise_entry_points_against_oracle(mode):
+    """The per-layer entry points (scan and selection as two launches, or as one) on a batch
+    of three sequences with different logit recipes, several chunks per row."""
+    cfg = small(name="layerwise-" + mode, V=40000, logits_dtype="bf16", K=8, N=130, Dmax=20, B=3, Hq=8, Hkv=2,
+                Dh=128, L=200, recipe=(("gauss", 6.0, 8.0), ("gauss", 0.5, 1.0), ("zipf_mix", 1.2, 0.05)))
+    step_and_compare(cfg, with_attention=False, layerwise=mode)
 
 
 def test_c2_llama3_8b_step_full_size():
