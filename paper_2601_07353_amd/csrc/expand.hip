@@ -316,7 +316,7 @@ __global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
     // ---- wavefront-local streaming state
     int cnt = 0;            // buffered vectors
     int tcnt = 0;           // keys in topw (<= k)
-    float tau = __builtin_huge_valf();   // a vector is buffered iff one of its logits is >= tau (set by the first group)
+    float tau = __builtin_huge_valf();   // a vector is buffered iff one of its logits is >= tau (set by the first step)
     float m_l = kNegInf;    // this lane's running max
     double s_l = 0.0;       // this lane's running sum of exp(logit - m_l)
 
@@ -349,12 +349,24 @@ __global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
       return true;
     };
 
+    // First threshold of an item: the k-th largest of the 64 lane maxima of its first group or
+    // tile (at least k logits reach it; -inf if fewer than k lanes hold a logit).
+    auto first_threshold = [&](float v) {
+      int seen = 0;
+      for (int r = 0; r < k; ++r) {
+        const float top = wave_max_f32(v);
+        seen += __popcll(__ballot(v == top));
+        tau = top;
+        if (seen >= k) break;
+        v = (v == top) ? kNegInf : v;
+      }
+    };
+
     // Streaming state machine.  A step is a group of 4 whole tiles (fast) or one tile at the
     // ragged end of the row (guarded).  Tiles whose hits do not fit the buffer are deferred,
     // together with all later tiles of the step, to the single slow section below, which cuts
     // the buffer and then re-reads them.
     PHASE(2);
-    if (tf == t0) tau = kNegInf;   // short row: every vector is buffered and ranked
     int tb = t0;
     bool done = false;
     while (!done) {
@@ -399,20 +411,7 @@ __global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
           for (int e = 0; e < EPL; ++e) acc += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e], kLog2e, -c));
         }
         s_l += static_cast<double>(acc * __builtin_amdgcn_exp2f(-c_err));
-        if (tb == t0) {
-          // ---- first threshold: the k-th largest of the 64 lane maxima of this group (at
-          // least k logits of the group reach it)
-          float v = gmax;
-          int seen = 0;
-          for (int r = 0; r < k; ++r) {
-            const float top = wave_max_f32(v);
-            seen += __popcll(__ballot(v == top));
-            tau = top;
-            if (seen >= k) break;
-            v = (v == top) ? kNegInf : v;
-          }
-          force = true;
-        }
+        if (tb == t0) { first_threshold(gmax); force = true; }
 #pragma unroll
         for (int q = 0; q < kScanTiles; ++q)
           if (deferred != 0u || !buffer_hits(raw[q], vmax4[q], tb + q)) deferred |= 1u << q;
@@ -433,6 +432,7 @@ __global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
 #pragma unroll
         for (int e = 0; e < EPL; ++e) bs += __expf(x[e] - mm);
         s_l += static_cast<double>(bs);
+        if (tb == t0) { first_threshold(vmax); force = true; }   // an item made of ragged tiles only
         if (!buffer_hits(raw, vmax, tb)) deferred = 1u;
         tb += 1;
       } else {
