@@ -47,6 +47,7 @@ extern "C" {
 #define TALON_STATUS_DONE_BUDGET 1u /* |T| reached N (Alg. 2 loop condition false)    */
 #define TALON_STATUS_DONE_DEPTH 2u  /* max_depth layers built before the budget ran out */
 #define TALON_STATUS_BAD_ROW 4u     /* NaN / +inf logit or a row with no finite maximum */
+#define TALON_STATUS_ABORTED 8u     /* talon_expand_tree gave up waiting between two layers */
 
 /* logits row addressing for talon_expand_layer */
 #define TALON_ROWS_BY_NODE 0     /* row of node i of sequence b = i                        */

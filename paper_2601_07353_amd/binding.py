@@ -28,6 +28,7 @@ TALON_B_MAX = 256
 TALON_STATUS_DONE_BUDGET = 1
 TALON_STATUS_DONE_DEPTH = 2
 TALON_STATUS_BAD_ROW = 4
+TALON_STATUS_ABORTED = 8
 TALON_ROWS_BY_NODE = 0
 TALON_ROWS_BY_FRONTIER = 1
 

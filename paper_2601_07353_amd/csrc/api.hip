@@ -49,7 +49,7 @@ int check_state(const talon_tree_state* st) {
 }
 
 struct ExpandLayout {
-  size_t off_max, off_sum, off_keys, off_ticket, off_seq_ticket, off_desc, total;
+  size_t off_max, off_sum, off_keys, off_ticket, off_seq_ticket, off_desc, off_layer_done, total;
   int chunks;
 };
 
@@ -69,7 +69,8 @@ int expand_layout(int B, int N_pad, int vocab, int k, int dtype, ExpandLayout* L
   L->off_ticket = 0;
   L->off_seq_ticket = align_up(rows * sizeof(int32_t), 256);
   L->off_desc = L->off_seq_ticket + align_up(static_cast<size_t>(B) * sizeof(int32_t), 256);
-  L->off_max = L->off_desc + align_up(static_cast<size_t>(B) * 4 * sizeof(int32_t), 256);
+  L->off_layer_done = L->off_desc + align_up(static_cast<size_t>(N_pad) * B * 2 * sizeof(int32_t), 256);
+  L->off_max = L->off_layer_done + align_up(static_cast<size_t>(N_pad) * sizeof(uint32_t), 256);
   L->off_sum = L->off_max + align_up(rows * chunks * sizeof(float), 256);
   L->off_keys = L->off_sum + align_up(rows * chunks * sizeof(double), 256);
   L->total = L->off_keys + align_up(rows * chunks * k * sizeof(uint64_t), 256);
@@ -137,7 +138,10 @@ ExpandArgs make_expand_args(const void* logits, int64_t row_stride, int64_t seq_
   a.ticket = reinterpret_cast<int32_t*>(w + L.off_ticket);
   a.seq_ticket = reinterpret_cast<int32_t*>(w + L.off_seq_ticket);
   a.desc = reinterpret_cast<int32_t*>(w + L.off_desc);
+  a.layer_done = reinterpret_cast<uint32_t*>(w + L.off_layer_done);
   a.launch_idx = 0;
+  a.layers = 0;
+  a.spin_ticks = 0;
   memset(&a.sel, 0, sizeof(a.sel));
   a.part_max = reinterpret_cast<float*>(w + L.off_max);
   a.part_sum = reinterpret_cast<double*>(w + L.off_sum);
@@ -240,7 +244,23 @@ hipError_t profile_record(hipStream_t s) {
 }
 
 // Fused launches of `layers` consecutive layers starting from the public tree state.
-int run_fused_layers(const void* logits, int dtype, int64_t row_stride, int64_t seq_stride, int row_mode,
+// Resident workgroups of the single-launch kernel, per element type, queried once.
+int tree_grid_limit(int dtype) {
+  static int cached[2] = {-1, -1};
+  int& c = cached[dtype == TALON_DTYPE_F32 ? 0 : 1];
+  if (c < 0) c = expand_tree_max_grid(dtype);
+  return c;
+}
+
+// Bound of the wait between two layers of the single-launch kernel, in ticks of the 100 MHz
+// wall clock (default 0.2 s; TALON_SPIN_LIMIT_US overrides it).
+unsigned long long spin_limit_ticks() {
+  const char* e = getenv("TALON_SPIN_LIMIT_US");
+  const long long us = e ? atoll(e) : 200000;
+  return static_cast<unsigned long long>(us < 0 ? 0 : us) * 100ull;
+}
+
+int run_fused_layers(bool single_launch, const void* logits, int dtype, int64_t row_stride, int64_t seq_stride, int row_mode,
                      int first_layer, int layers, const talon_tree_state* st, int32_t vocab, int32_t k, float mu,
                      int32_t K_init, int32_t init_layers, int32_t max_depth, int32_t* cand_token, float* cand_logit,
                      float* cand_prob, double* cand_edge_logp, float* row_max, double* row_lse, void* workspace,
@@ -259,16 +279,35 @@ int run_fused_layers(const void* logits, int dtype, int64_t row_stride, int64_t 
   ea.sel = sa;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (layers <= 0) return TALON_OK;
-  rc = check_hip(launch_desc_init(*st, ea.desc, s), "descriptor init launch");
+  rc = check_hip(launch_fused_init(*st, ea, s), "fused init launch");
   if (rc) return rc;
-  for (int d = 0; d < layers; ++d) {
-    ea.launch_idx = d;
-    const int layer = first_layer < 0 ? -1 : first_layer + d;
-    if (g_profile.enabled && (rc = check_hip(profile_record(s), "profile event"))) return rc;
-    rc = check_hip(launch_expand(ea, dtype, expand_grid(st, L.chunks, layer, k, K_init, init_layers), true, s), "expand launch");
-    if (rc) return rc;
-    if (g_profile.enabled && (rc = check_hip(profile_record(s), "profile event"))) return rc;
+  if (!single_launch) {
+    for (int d = 0; d < layers; ++d) {
+      ea.launch_idx = d;
+      const int layer = first_layer < 0 ? -1 : first_layer + d;
+      if (g_profile.enabled && (rc = check_hip(profile_record(s), "profile event"))) return rc;
+      rc = check_hip(launch_expand(ea, dtype, expand_grid(st, L.chunks, layer, k, K_init, init_layers), true, s), "expand launch");
+      if (rc) return rc;
+      if (g_profile.enabled && (rc = check_hip(profile_record(s), "profile event"))) return rc;
+    }
+    return TALON_OK;
   }
+  // One launch walks all layers.  Its grid is the widest layer's, capped by what the device
+  // holds at once (the kernel's workgroups wait for each other between layers).
+  int grid = 1;
+  for (int d = 0; d < layers; ++d) {
+    const int g = expand_grid(st, L.chunks, first_layer + d, k, K_init, init_layers);
+    grid = g > grid ? g : grid;
+  }
+  const int resident = tree_grid_limit(dtype);
+  if (resident < 1) { set_error("occupancy query for the single-launch kernel failed"); return TALON_ERR_RUNTIME; }
+  grid = grid < resident ? grid : resident;
+  ea.layers = layers;
+  ea.spin_ticks = spin_limit_ticks();
+  if (g_profile.enabled && (rc = check_hip(profile_record(s), "profile event"))) return rc;
+  rc = check_hip(launch_expand_tree(ea, dtype, grid, s), "expand tree launch");
+  if (rc) return rc;
+  if (g_profile.enabled && (rc = check_hip(profile_record(s), "profile event"))) return rc;
   return TALON_OK;
 }
 
@@ -279,7 +318,7 @@ int talon_expand_select_layer(const void* logits, int dtype, int64_t row_stride,
                               int32_t K_init, int32_t init_layers, int32_t max_depth, int32_t* cand_token,
                               float* cand_logit, float* cand_prob, double* cand_edge_logp, float* row_max,
                               double* row_lse, void* workspace, size_t workspace_bytes, void* stream) {
-  return run_fused_layers(logits, dtype, row_stride, seq_stride, row_mode, layer, 1, st, vocab, k, mu, K_init,
+  return run_fused_layers(false, logits, dtype, row_stride, seq_stride, row_mode, layer, 1, st, vocab, k, mu, K_init,
                           init_layers, max_depth, cand_token, cand_logit, cand_prob, cand_edge_logp, row_max,
                           row_lse, workspace, workspace_bytes, stream);
 }
@@ -290,10 +329,11 @@ int talon_expand_tree(const void* logits, int dtype, int64_t row_stride, int64_t
                       float* cand_prob, double* cand_edge_logp, float* row_max, double* row_lse,
                       void* workspace, size_t workspace_bytes, void* stream) {
   // a tree of N nodes has at most N-1 layers: later iterations could not add anything.
-  // One launch per layer: the scan runs each sequence's budget selection in its tail.
+  // One launch for the whole loop: the scan runs each sequence's budget selection in its tail
+  // and the grid moves on to the next layer when every selection of a layer is done.
   int layers = 0;
   if (st && max_depth > 0) layers = max_depth < st->N - 1 ? max_depth : (st->N > 1 ? st->N - 1 : 0);
-  return run_fused_layers(logits, dtype, row_stride, seq_stride, row_mode, 0, layers, st, vocab, k, mu, K_init,
+  return run_fused_layers(true, logits, dtype, row_stride, seq_stride, row_mode, 0, layers, st, vocab, k, mu, K_init,
                           init_layers, max_depth, cand_token, cand_logit, cand_prob, cand_edge_logp, row_max,
                           row_lse, workspace, workspace_bytes, stream);
 }

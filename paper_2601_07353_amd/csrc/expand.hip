@@ -40,8 +40,8 @@ namespace {
 constexpr float kNegInf = -__builtin_huge_valf();
 constexpr int kHitTrigger = 64;                  // buffered vectors that trigger a cut before the next tile
 constexpr int kHitCap = kHitTrigger + 64;        // a tile adds at most 64 vectors
-constexpr int kSubBatch = 16;                    // vectors expanded per ranking round
-constexpr int kSubKeys = kSubBatch * 8 + TALON_K_MAX;  // keys ranked per round (<= 8 logits per vector)
+constexpr int kSubBatch = 32;                    // vectors expanded per ranking round (two lanes per vector)
+constexpr int kSubKeys = kSubBatch * 8 + TALON_K_MAX + 16;  // keys ranked per round (<= 8 logits per vector) + zero padding
 
 // Phase timestamps (100 MHz wall clock) of workgroup 0; compiled only into tuning builds
 // with -DTALON_PHASE_TIMING.
@@ -49,7 +49,14 @@ constexpr int kSubKeys = kSubBatch * 8 + TALON_K_MAX;  // keys ranked per round 
 __device__ unsigned long long g_phase[16];
 #define PHASE(i) do { if (threadIdx.x == 0 && blockIdx.x == 0) g_phase[i] = wall_clock64(); } while (0)
 #define PHASE_MAX(i) do { if (threadIdx.x == 0) atomicMax(&g_phase[i], wall_clock64()); } while (0)
+__device__ unsigned long long g_wg[1024][16];   // per-workgroup time stamps of its first item
+#define WG_MARK(i) do { if (threadIdx.x == 0 && item == blockIdx.x && blockIdx.x < 1024) g_wg[blockIdx.x][i] = wall_clock64(); } while (0)
+#define WG_MARK2(i) do { if (threadIdx.x == 0 && blockIdx.x < 1024) g_wg[blockIdx.x][i] = wall_clock64(); } while (0)
+#define WG_MARK_LOADED(i) do { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); WG_MARK(i); } while (0)
 #else
+#define WG_MARK(i) do { } while (0)
+#define WG_MARK2(i) do { } while (0)
+#define WG_MARK_LOADED(i) do { } while (0)
 #define PHASE(i) do { } while (0)
 #define PHASE_MAX(i) do { } while (0)
 #endif
@@ -115,6 +122,21 @@ __device__ __forceinline__ int count_greater(const unsigned long long* s, int n,
   return r;
 }
 
+// Number of keys in s[0..n) greater than key, for a 16-byte aligned array padded with zero keys
+// to a multiple of 16 keys: 8 two-key LDS broadcast reads in flight per round.
+__device__ __forceinline__ int count_greater_pad16(const unsigned long long* s, int n, unsigned long long key) {
+  const ulonglong2* kp = reinterpret_cast<const ulonglong2*>(s);
+  int r = 0;
+  for (int j = 0; j < n; j += 16) {
+    ulonglong2 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = kp[(j >> 1) + u];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) r += ((v[u].x > key) ? 1 : 0) + ((v[u].y > key) ? 1 : 0);
+  }
+  return r;
+}
+
 // Number of keys greater than `key` in a list sorted in descending order (zeros, if any, at
 // the end): binary search.
 __device__ __forceinline__ int count_greater_sorted(const unsigned long long* s, int n, unsigned long long key) {
@@ -142,6 +164,16 @@ __device__ __forceinline__ float key_logit(unsigned long long key) {
   return unsortable_f32(static_cast<uint32_t>(key >> 32));
 }
 
+// log of a softmax denominator (1 <= sum <= vocabulary size, or 0 / inf / NaN for a row that
+// cannot be normalised): sum = 2^e * f with f in [0.5, 1), log(sum) = e*ln2 + log(f); the
+// second term is small, so single precision gives it to about 1e-7 absolute.
+__device__ __forceinline__ double log_of_sum(double sum) {
+  if (!(sum > 0.0) || !(sum <= 1.7e308)) return log(sum);
+  int e;
+  const double f = frexp(sum, &e);
+  return static_cast<double>(e) * 0.69314718055994530942 + static_cast<double>(__logf(static_cast<float>(f)));
+}
+
 // Write the outputs of one row from its candidate keys (in LDS) and softmax statistics.
 // `keys` holds `lists` lists of k keys, each sorted in descending order.
 // FUSED: the candidates are read by another workgroup of this launch (the one that runs the
@@ -151,7 +183,7 @@ __device__ __forceinline__ void write_row(const ExpandArgs& a, int b, int out_ro
                                           int lists, float m, double sum) {
   const int tid = threadIdx.x;
   const int k = a.k;
-  const double lse = static_cast<double>(m) + log(sum);
+  const double lse = static_cast<double>(m) + log_of_sum(sum);
   const size_t ob = static_cast<size_t>(out_row) * k;
   // Rank by counting.  Thread t ranks keys t and t + 256 in one sweep over all keys (LDS
   // broadcast reads, several in flight); a key's own list contributes its position.
@@ -160,17 +192,21 @@ __device__ __forceinline__ void write_row(const ExpandArgs& a, int b, int out_ro
     const int ia = i0 + tid, ib = i0 + kThreads + tid;
     const unsigned long long ka = ia < nkeys ? keys[ia] : 0ull;
     const unsigned long long kb = ib < nkeys ? keys[ib] : 0ull;
+    const bool two = i0 + kThreads < nkeys;   // uniform: the second key of this sweep exists for some thread
     int ra = 0, rb = 0;
     if (lists > 1) {
-      int j = 0;
-      for (; j + 4 <= nkeys; j += 4) {
-        unsigned long long v[4];
+      // the key array is padded with zero keys to a multiple of 16
+      const ulonglong2* kp = reinterpret_cast<const ulonglong2*>(keys);
+      for (int j = 0; j < nkeys; j += 16) {
+        ulonglong2 v[8];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = keys[j + u];
+        for (int u = 0; u < 8; ++u) v[u] = kp[(j >> 1) + u];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) { ra += (v[u] > ka) ? 1 : 0; rb += (v[u] > kb) ? 1 : 0; }
+        for (int u = 0; u < 8; ++u) {
+          ra += ((v[u].x > ka) ? 1 : 0) + ((v[u].y > ka) ? 1 : 0);
+          if (two) rb += ((v[u].x > kb) ? 1 : 0) + ((v[u].y > kb) ? 1 : 0);
+        }
       }
-      for (; j < nkeys; ++j) { const unsigned long long v = keys[j]; ra += (v > ka) ? 1 : 0; rb += (v > kb) ? 1 : 0; }
     } else {
       ra = ia; rb = ib;   // a single sorted list
     }
@@ -196,6 +232,7 @@ __device__ __forceinline__ void write_row(const ExpandArgs& a, int b, int out_ro
       }
     }
   }
+  WG_MARK2(11);
   const int valid = a.vocab < k ? a.vocab : k;
   if (tid >= valid && tid < k) {
     a.cand_logit[ob + tid] = kNegInf;
@@ -216,8 +253,15 @@ __device__ __forceinline__ void write_row(const ExpandArgs& a, int b, int out_ro
   }
 }
 
-template <int EPL, bool FUSED>
-__global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
+// How a launch is used: scan only; scan with the selection in its tail (one layer per launch);
+// or one launch that walks all layers.
+constexpr int kModeSplit = 0, kModeFused = 1, kModeTree = 2;
+
+// One layer: returns the number of frontier rows it found (0: every sequence is finished).
+template <int EPL, int MODE>
+__device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch_idx) {
+  constexpr bool FUSED = MODE != kModeSplit;
+  constexpr bool TREE = MODE == kModeTree;
   constexpr int NX = kScanTiles * EPL;          // logits per thread per block
   constexpr int BLOCK = kThreads * NX;          // logits per block
   __shared__ int s_prefix[TALON_B_MAX + 1];     // exclusive prefix of frontier sizes
@@ -237,7 +281,8 @@ __global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
   unsigned long long (*s_ck)[kSubKeys] = reinterpret_cast<unsigned long long (*)[kSubKeys]>(s_pool + kHitvBytes + kHithBytes);
   __shared__ unsigned long long s_red_u64[8];
   __shared__ int s_misc[2];
-  __shared__ unsigned long long s_topw[4][TALON_K_MAX]; // k best keys of each wavefront, sorted
+  __shared__ __attribute__((aligned(16))) unsigned long long s_topw[4][TALON_K_MAX]; // k best keys of each wavefront, sorted
+  __shared__ int s_part[4][64];                         // partial ranks of the list merge
   __shared__ unsigned long long s_top[TALON_K_MAX];
   __shared__ double s_red_f64[8];
   __shared__ float s_red_f32[8];
@@ -261,14 +306,14 @@ __global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
     int c = 0;
     if (tid < a.B) {
       if constexpr (FUSED) {
-        c = a.desc[((a.launch_idx & 1) * a.B + tid) * 2 + 1];
+        c = ld<TREE, int32_t>(a.desc + (launch_idx * a.B + tid) * 2 + 1);
       } else {  // both loads are issued together; the select below is register-only
         const uint32_t stat = a.status[tid];
         const int fc = a.frontier_count[tid];
         c = (stat & kDoneMask) ? 0 : fc;
       }
       // a finished sequence gets no selection in this launch: carry its empty frontier over
-      if (FUSED && blockIdx.x == 0 && c == 0) a.desc[(((a.launch_idx + 1) & 1) * a.B + tid) * 2 + 1] = 0;
+      if (FUSED && blockIdx.x == 0 && c == 0) st_<TREE, int32_t>(a.desc + ((launch_idx + 1) * a.B + tid) * 2 + 1, 0);
     }
     int total;
     const int base = block_exclusive_scan_i32(c, s_red_i32, &total);
@@ -279,7 +324,7 @@ __global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
   PHASE(1);
   PHASE_MAX(10);
   const int total_rows = s_prefix[a.B];
-  if (total_rows == 0) return;
+  if (total_rows == 0) return 0;
   const int k = a.k;
 
   // ---- chunks per row from the width of this layer
@@ -304,7 +349,7 @@ __global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
     }
     const int b = lo;
     const int local = rg - s_prefix[b];
-    const int fbegin = FUSED ? a.desc[((a.launch_idx & 1) * a.B + b) * 2] : a.frontier_begin[b];
+    const int fbegin = FUSED ? ld<TREE, int32_t>(a.desc + (launch_idx * a.B + b) * 2) : a.frontier_begin[b];
     const int node = fbegin + local;
     const int in_row = a.row_mode == TALON_ROWS_BY_FRONTIER ? local : node;
     const char* row = static_cast<const char*>(a.logits) +
@@ -320,16 +365,14 @@ __global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
     float m_l = kNegInf;    // this lane's running max
     double s_l = 0.0;       // this lane's running sum of exp(logit - m_l)
 
-    // A tile is one 16-byte vector per thread (256 * EPL logits); a block is 4 tiles.
-    // Groups of 4 tiles that lie wholly inside the row go through the fast loop, whose ring
-    // keeps the next group's loads in flight; the ragged end of the row (at most 4 tiles,
-    // only in the row's last chunk) goes tile by tile through the guarded path.
+    // A tile is one 16-byte vector per thread (256 * EPL logits); a block is 4 tiles, and the
+    // scan advances by groups of 4 tiles.  A group that lies wholly inside the row is loaded
+    // with plain vector loads; the group at the ragged end of the row (only in the row's last
+    // chunk) with guarded loads that return -inf past the end.
     const int t0 = blk0 * kScanTiles;
     const int tiles_in_row = (a.vocab + kThreads * EPL - 1) / (kThreads * EPL);
     const int full_tiles = a.vocab / (kThreads * EPL);
     const int t1 = blk1 * kScanTiles < tiles_in_row ? blk1 * kScanTiles : tiles_in_row;
-    int tf = blk1 * kScanTiles < full_tiles ? blk1 * kScanTiles : full_tiles;
-    tf = t0 + (tf > t0 ? (tf - t0) / kScanTiles * kScanTiles : 0);   // end of the fast loop
     const char* lane_ptr = row + static_cast<size_t>(tid) * 16;
     constexpr size_t kTileBytes = static_cast<size_t>(kThreads) * 16;
 
@@ -349,37 +392,46 @@ __global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
       return true;
     };
 
-    // First threshold of an item: the k-th largest of the 64 lane maxima of its first group or
-    // tile (at least k logits reach it; -inf if fewer than k lanes hold a logit).
+    // First threshold of an item: the largest value with a 16-bit (sign, exponent, 7 mantissa
+    // bits) pattern that at least k of the 64 lane maxima of its first group reach, found
+    // bit by bit on the order-preserving integer image of the maxima (-inf if fewer than k
+    // lanes hold a logit).  For bf16 logits this is the k-th largest lane maximum itself.
     auto first_threshold = [&](float v) {
-      int seen = 0;
-      for (int r = 0; r < k; ++r) {
-        const float top = wave_max_f32(v);
-        seen += __popcll(__ballot(v == top));
-        tau = top;
-        if (seen >= k) break;
-        v = (v == top) ? kNegInf : v;
+      const uint32_t u = sortable_u32(v);
+      uint32_t prefix = 0u;
+#pragma unroll
+      for (int bit = 31; bit >= 16; --bit) {
+        const uint32_t cand = prefix | (1u << bit);
+        if (__popcll(__ballot(u >= cand)) >= k) prefix = cand;
       }
+      tau = prefix <= 0x007FFFFFu ? kNegInf : unsortable_f32(prefix);   // at or below the image of -inf
     };
 
-    // Streaming state machine.  A step is a group of 4 whole tiles (fast) or one tile at the
-    // ragged end of the row (guarded).  Tiles whose hits do not fit the buffer are deferred,
-    // together with all later tiles of the step, to the single slow section below, which cuts
-    // the buffer and then re-reads them.
+    // Streaming state machine.  A step is a group of 4 tiles.  Tiles whose hits do not fit the
+    // buffer are deferred, together with all later tiles of the group, to the single slow
+    // section below, which cuts the buffer and then re-reads them.
     PHASE(2);
+    WG_MARK(0);
     int tb = t0;
     bool done = false;
     while (!done) {
       uint32_t deferred = 0;   // bit q: tile def_base + q still has to be buffered
       int def_base = tb;
       bool force = false;
-      if (tb < tf) {
+      if (tb < t1) {
         // No software prefetch: many resident wavefronts, each with 4 loads in flight, hide
         // the latency, and the loop stays small in registers.
         uint4 raw[kScanTiles];
+        if (tb + kScanTiles <= full_tiles) {
 #pragma unroll
-        for (int q = 0; q < kScanTiles; ++q)
-          raw[q] = *reinterpret_cast<const uint4*>(lane_ptr + (tb + q) * kTileBytes);
+          for (int q = 0; q < kScanTiles; ++q)
+            raw[q] = *reinterpret_cast<const uint4*>(lane_ptr + (tb + q) * kTileBytes);
+        } else {
+#pragma unroll
+          for (int q = 0; q < kScanTiles; ++q)
+            raw[q] = load_vec<EPL>(row, ((tb + q) * kThreads + tid) * EPL, a.vocab);
+        }
+        WG_MARK_LOADED(5);
         // lane maxima of the 4 tiles first; the running max moves at most once per group
         float vmax4[kScanTiles];
 #pragma unroll
@@ -411,35 +463,19 @@ __global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
           for (int e = 0; e < EPL; ++e) acc += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e], kLog2e, -c));
         }
         s_l += static_cast<double>(acc * __builtin_amdgcn_exp2f(-c_err));
+        WG_MARK(6);
         if (tb == t0) { first_threshold(gmax); force = true; }
+        WG_MARK(7);
 #pragma unroll
         for (int q = 0; q < kScanTiles; ++q)
           if (deferred != 0u || !buffer_hits(raw[q], vmax4[q], tb + q)) deferred |= 1u << q;
         tb += kScanTiles;
-      } else if (tb < t1) {
-        const uint4 raw = load_vec<EPL>(row, (tb * kThreads + tid) * EPL, a.vocab);
-        float x[EPL];
-        unpack_vec<EPL>(raw, x);
-        float vmax = x[0];
-#pragma unroll
-        for (int e = 1; e < EPL; ++e) vmax = fmaxf(vmax, x[e]);
-        if (vmax > m_l) {
-          s_l = (m_l == kNegInf) ? 0.0 : s_l * static_cast<double>(__expf(m_l - vmax));
-          m_l = vmax;
-        }
-        const float mm = (m_l == kNegInf) ? 0.f : m_l;
-        float bs = 0.f;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) bs += __expf(x[e] - mm);
-        s_l += static_cast<double>(bs);
-        if (tb == t0) { first_threshold(vmax); force = true; }   // an item made of ragged tiles only
-        if (!buffer_hits(raw, vmax, tb)) deferred = 1u;
-        tb += 1;
       } else {
         force = cnt > 0;
         done = true;
       }
 
+      WG_MARK(8);
       if (force || deferred != 0u || cnt > kHitTrigger) {
         // ---- slow section: cut the buffer to the k best; then buffer the deferred tiles
         while (true) {
@@ -448,16 +484,23 @@ __global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
           // come (deferred tiles included), so afterwards a logit equal to the k-th best loses
           // the tie and tau becomes the next float above it.
           for (int base = 0; base < cnt; base += kSubBatch) {
-            float x[EPL];
+            constexpr int HPL = EPL / 2;   // logits per lane: a lane expands half a vector
+            float x[HPL];
             int e0 = 0;
             uint32_t hbits = 0;
-            if (lane < kSubBatch && base + lane < cnt) {
-              const uint4 raw = hitv[base + lane];
-              const int hdr = hith[base + lane];
-              e0 = (((hdr >> 6) * 4 + wave) * 64 + (hdr & 63)) * EPL;
-              unpack_vec<EPL>(raw, x);
+            if (base + (lane >> 1) < cnt) {
+              const int slot = base + (lane >> 1), half = lane & 1;
+              const uint2 raw = reinterpret_cast<const uint2*>(&hitv[slot])[half];
+              const int hdr = hith[slot];
+              e0 = (((hdr >> 6) * 4 + wave) * 64 + (hdr & 63)) * EPL + half * HPL;
+              if constexpr (EPL == 4) {
+                x[0] = __uint_as_float(raw.x); x[1] = __uint_as_float(raw.y);
+              } else {
+                x[0] = __uint_as_float(raw.x << 16); x[1] = __uint_as_float(raw.x & 0xFFFF0000u);
+                x[2] = __uint_as_float(raw.y << 16); x[3] = __uint_as_float(raw.y & 0xFFFF0000u);
+              }
 #pragma unroll
-              for (int e = 0; e < EPL; ++e)
+              for (int e = 0; e < HPL; ++e)
                 if (x[e] >= tau && e0 + e < a.vocab) hbits |= 1u << e;
             }
             const int nh = __popc(hbits);
@@ -466,19 +509,21 @@ __global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
             if (lane < tcnt) ck[lane] = topw[lane];
             int pos = tcnt + incl - nh;
 #pragma unroll
-            for (int e = 0; e < EPL; ++e)
+            for (int e = 0; e < HPL; ++e)
               if (hbits & (1u << e)) ck[pos++] = make_key(x[e], e0 + e);
             const int n = tcnt + total;
+            if (lane < 16) ck[n + lane] = 0ull;   // zero keys up to the next multiple of 16
             // LDS operations of one wavefront complete in order: ck is complete before it is read
             for (int i = lane; i < n; i += 64) {
               const unsigned long long key = ck[i];
-              const int r = count_greater(ck, n, key);
+              const int r = count_greater_pad16(ck, n, key);
               if (r < k) topw[r] = key;
             }
             tcnt = n < k ? n : k;
             if (tcnt >= k) tau = fmaxf(tau, key_logit(topw[k - 1]));
           }
           cnt = 0;
+          WG_MARK(9);
           if (tcnt >= k) tau = float_above(key_logit(topw[k - 1]));
           if (deferred == 0u) break;
 #pragma unroll 1
@@ -498,6 +543,8 @@ __global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
       }
     }
     PHASE(3);
+    PHASE_MAX(15);
+    WG_MARK(1);
 
     // ---- wavefront statistics
     {
@@ -506,22 +553,25 @@ __global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
       const double sl = (m_l == kNegInf) ? 0.0 : s_l * static_cast<double>(__expf(m_l - wmax));
       const double wsum = wave_sum_f64(sl);
       if (lane == 0) { s_wmax[wave] = wmax; s_wsum[wave] = wsum; s_wcnt[wave] = tcnt; }
+      if (lane >= tcnt && lane < 16) topw[lane] = 0ull;   // unused slots of the list: zero keys
     }
     __syncthreads();
     PHASE(4);
 
-    // ---- merge the four lists (each <= k keys) into the chunk's k best, sorted
-    const int c0 = s_wcnt[0], c1 = s_wcnt[1], c2 = s_wcnt[2], c3 = s_wcnt[3];
-    const int ctot = c0 + c1 + c2 + c3;
+    // ---- merge the four lists (each <= k keys, zero keys in the unused slots) into the
+    // chunk's k best, sorted.  Lane 16w+i of every wavefront holds key i of list w; wavefront v
+    // counts how many keys of list v are greater; the four counts add up to the rank.
+    const int ctot = s_wcnt[0] + s_wcnt[1] + s_wcnt[2] + s_wcnt[3];
+    const unsigned long long mkey = s_topw[lane >> 4][lane & 15];
     {
-      const int my_cnt = wave == 0 ? c0 : (wave == 1 ? c1 : (wave == 2 ? c2 : c3));
-      if (lane < my_cnt) {
-        const unsigned long long key = topw[lane];
-        const int r = count_greater_sorted(s_topw[0], c0, key) + count_greater_sorted(s_topw[1], c1, key) +
-                      count_greater_sorted(s_topw[2], c2, key) + count_greater_sorted(s_topw[3], c3, key);
-        if (r < k) s_top[r] = key;
-      }
-      if (tid >= ctot && tid < k) s_top[tid] = 0ull;   // fewer than k logits in this chunk
+      static_assert(TALON_K_MAX == 16, "16 slots per list");
+      s_part[wave][lane] = count_greater_pad16(s_topw[wave], 16, mkey);
+    }
+    __syncthreads();
+    if (wave == 0) {
+      const int r = s_part[0][lane] + s_part[1][lane] + s_part[2][lane] + s_part[3][lane];
+      if (mkey != 0ull && r < k) s_top[r] = mkey;
+      if (lane >= ctot && lane < k) s_top[lane] = 0ull;   // fewer than k logits in this chunk
     }
     const float cm = fmaxf(fmaxf(s_wmax[0], s_wmax[1]), fmaxf(s_wmax[2], s_wmax[3]));
     double csum = 0.0;
@@ -530,6 +580,7 @@ __global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
       if (s_wmax[w] != kNegInf) csum += s_wsum[w] * static_cast<double>(__expf(s_wmax[w] - cm));
     __syncthreads();
     PHASE(5);
+    WG_MARK(2);
 
     bool row_written = false;   // this workgroup has just written a whole row's outputs
     if (chunks == 1) {
@@ -551,25 +602,39 @@ __global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
       }
       __syncthreads();
       PHASE(6);
+      PHASE_MAX(14);
+      WG_MARK(3);
       if (s_last) {
         const float* pm = a.part_max + static_cast<size_t>(out_row) * blocks_per_row;
         const double* ps = a.part_sum + static_cast<size_t>(out_row) * blocks_per_row;
         const unsigned long long* keys = a.part_keys + static_cast<size_t>(out_row) * blocks_per_row * k;
         const int nkeys = chunks * k;
-        for (int i = tid; i < nkeys; i += kThreads) s_keys[i] = load_agent(keys + i);
-        float m = kNegInf;
-        for (int c = tid; c < chunks; c += kThreads) m = fmaxf(m, load_agent(pm + c));
-        m = block_max_f32(m, s_red_f32);  // barriers inside: s_keys is staged
-        double sum = 0.0;
-        for (int c = tid; c < chunks; c += kThreads) {
+        const int nkeys_pad = (nkeys + 15) & ~15;   // zero keys rank below every real key
+        // softmax statistics of the row: every wavefront merges the chunk statistics on its own
+        // (one chunk per lane, more only for very long rows), so that no workgroup-wide
+        // reduction is needed.  All loads of the first sweep are issued before any is used.
+        float mc0 = kNegInf;
+        double sc0 = 0.0;
+        if (lane < chunks) { mc0 = load_agent(pm + lane); sc0 = load_agent(ps + lane); }
+        const unsigned long long key0 = tid < nkeys ? load_agent(keys + tid) : 0ull;
+        if (tid < nkeys_pad) s_keys[tid] = key0;
+        for (int i = tid + kThreads; i < nkeys_pad; i += kThreads) s_keys[i] = i < nkeys ? load_agent(keys + i) : 0ull;
+        float m = mc0;
+        for (int c = lane + 64; c < chunks; c += 64) m = fmaxf(m, load_agent(pm + c));
+        m = wave_max_f32(m);
+        double sum = (mc0 != kNegInf) ? sc0 * static_cast<double>(__expf(mc0 - m)) : 0.0;
+        for (int c = lane + 64; c < chunks; c += 64) {
           const float mc = load_agent(pm + c);
           if (mc != kNegInf) sum += load_agent(ps + c) * static_cast<double>(__expf(mc - m));
         }
-        sum = block_sum_f64(sum, s_red_f64);
+        sum = wave_sum_f64(sum);
+        __syncthreads();   // s_keys is staged
+        WG_MARK2(10);
         PHASE(7);
         PHASE_MAX(12);
         write_row<FUSED>(a, b, out_row, s_keys, chunks, m, sum);
         PHASE_MAX(13);
+        WG_MARK2(12);
         if (tid == 0) store_agent(a.ticket + out_row, 0);  // leave the workspace clean for the next layer
         row_written = true;
       }
@@ -589,23 +654,71 @@ __global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
         __syncthreads();
         if (s_last) {
           const uint32_t status = __hip_atomic_load(&a.status[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          int* next_desc = a.desc + (((a.launch_idx + 1) & 1) * a.B + b) * 2;
+          int* next_desc = a.desc + ((launch_idx + 1) * a.B + b) * 2;
           if (status & TALON_STATUS_BAD_ROW) {   // a row could not be normalised: stop the sequence here
-            if (tid == 0) { a.sel.st.frontier_count[b] = 0; next_desc[0] = fbegin; next_desc[1] = 0; }
+            if (tid == 0) {
+              st_<TREE, int32_t>(a.sel.st.frontier_count + b, 0);
+              st_<TREE, int32_t>(next_desc, fbegin);
+              st_<TREE, int32_t>(next_desc + 1, 0);
+            }
           } else {
             const SelectLds lds{reinterpret_cast<unsigned long long*>(s_pool),
                                 reinterpret_cast<int*>(s_pool + sizeof(unsigned long long) * kSelectKeySlots),
                                 s_red_u64, s_red_i32, s_misc};
             select_sequence<true>(a.sel, b, F, fbegin, status, lds, next_desc);
           }
+          if constexpr (TREE) {
+            // everything this layer wrote for the sequence is complete before its rows are
+            // counted as done
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            __syncthreads();
+            if (tid == 0)
+              __hip_atomic_fetch_add(&a.layer_done[launch_idx], static_cast<uint32_t>(F), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
         }
       }
     }
     __syncthreads();  // s_keys / s_top / s_w* are reused by the next item
     PHASE(8);
+    WG_MARK(4);
     PHASE_MAX(11);
   }
   PHASE(9);
+  return total_rows;
+}
+
+template <int EPL, int MODE>
+__global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
+  static_assert(MODE != kModeTree, "the single-launch loop has its own kernel");
+  expand_body<EPL, MODE>(a, a.launch_idx);
+}
+
+// All layers in one launch.  The grid must be resident as a whole (the host sizes it from the
+// occupancy of this kernel): a workgroup waits, between two layers, for the selections of the
+// layer it has just left, which other workgroups run.  The wait is bounded; a workgroup that
+// gives up marks every sequence TALON_STATUS_ABORTED and leaves, and so do all others.
+template <int EPL>
+__global__ __launch_bounds__(kThreads, 4) void expand_tree_kernel(ExpandArgs a) {
+  __shared__ int s_go;
+  for (int d = 0; d < a.layers; ++d) {
+    const int rows = expand_body<EPL, kModeTree>(a, d);
+    if (rows == 0 || d + 1 == a.layers) return;   // uniform over the grid: every workgroup reads the same descriptors
+    if (threadIdx.x == 0) {
+      const unsigned long long t0 = wall_clock64();
+      int go = 1;
+      while (load_agent(a.layer_done + d) < static_cast<uint32_t>(rows)) {
+        if (wall_clock64() - t0 > a.spin_ticks) { go = 0; break; }
+        __builtin_amdgcn_s_sleep(4);
+      }
+      s_go = go;
+    }
+    __syncthreads();
+    if (!s_go) {
+      for (int b = threadIdx.x; b < a.B; b += kThreads) atomicOr(&a.status[b], TALON_STATUS_ABORTED);
+      return;
+    }
+    __syncthreads();   // s_go is rewritten in the next round
+  }
 }
 
 __global__ __launch_bounds__(kThreads) void fill_zero_kernel(uint32_t* p, size_t n) {
@@ -634,26 +747,52 @@ __global__ __launch_bounds__(kThreads) void tree_init_kernel(talon_tree_state st
 
 int expand_chunk_elems(int dtype) { return dtype == TALON_DTYPE_F32 ? kChunkBytes / 4 : kChunkBytes / 2; }
 
-// Frontier descriptors of the first fused launch, from the public tree state.
-__global__ void desc_init_kernel(talon_tree_state st, int32_t* desc) {
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= st.B) return;
-  desc[2 * b] = st.frontier_begin[b];
-  desc[2 * b + 1] = (st.status[b] & kDoneMask) ? 0 : st.frontier_count[b];
+// Start of a fused call: frontier descriptors of its first layer from the public tree state,
+// zero layer counters, and zero tickets (a launch that gave up may have left some taken).
+__global__ void fused_init_kernel(talon_tree_state st, int32_t* desc, uint32_t* layer_done, int32_t* ticket,
+                                  int32_t* seq_ticket) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < st.B * st.N_pad) ticket[i] = 0;
+  if (i < st.N_pad) layer_done[i] = 0u;
+  if (i >= st.B) return;
+  seq_ticket[i] = 0;
+  desc[2 * i] = st.frontier_begin[i];
+  desc[2 * i + 1] = (st.status[i] & kDoneMask) ? 0 : st.frontier_count[i];
 }
 
-hipError_t launch_desc_init(const talon_tree_state& st, int32_t* desc, hipStream_t s) {
-  hipLaunchKernelGGL(desc_init_kernel, dim3((st.B + 255) / 256), dim3(256), 0, s, st, desc);
+hipError_t launch_fused_init(const talon_tree_state& st, const ExpandArgs& a, hipStream_t s) {
+  static_assert(TALON_B_MAX <= 256 && TALON_N_MAX <= 256, "the first workgroup covers the per-sequence and per-layer arrays");
+  const int n = st.B * st.N_pad;
+  hipLaunchKernelGGL(fused_init_kernel, dim3((n + 255) / 256), dim3(256), 0, s, st, a.desc, a.layer_done, a.ticket,
+                     a.seq_ticket);
   return hipGetLastError();
+}
+
+hipError_t launch_expand_tree(const ExpandArgs& a, int dtype, int grid, hipStream_t s) {
+  if (dtype == TALON_DTYPE_F32) hipLaunchKernelGGL(expand_tree_kernel<4>, dim3(grid), dim3(kThreads), 0, s, a);
+  else hipLaunchKernelGGL(expand_tree_kernel<8>, dim3(grid), dim3(kThreads), 0, s, a);
+  return hipGetLastError();
+}
+
+// Workgroups of the single-launch kernel that the current device holds at once.
+int expand_tree_max_grid(int dtype) {
+  int dev = 0, per_cu = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 0;
+  const hipError_t e = dtype == TALON_DTYPE_F32
+      ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, expand_tree_kernel<4>, kThreads, 0)
+      : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, expand_tree_kernel<8>, kThreads, 0);
+  if (e != hipSuccess) return 0;
+  return per_cu * prop.multiProcessorCount;
 }
 
 hipError_t launch_expand(const ExpandArgs& a, int dtype, int grid, bool fused, hipStream_t s) {
   if (dtype == TALON_DTYPE_F32) {
-    if (fused) hipLaunchKernelGGL((expand_kernel<4, true>), dim3(grid), dim3(kThreads), 0, s, a);
-    else hipLaunchKernelGGL((expand_kernel<4, false>), dim3(grid), dim3(kThreads), 0, s, a);
+    if (fused) hipLaunchKernelGGL((expand_kernel<4, kModeFused>), dim3(grid), dim3(kThreads), 0, s, a);
+    else hipLaunchKernelGGL((expand_kernel<4, kModeSplit>), dim3(grid), dim3(kThreads), 0, s, a);
   } else {
-    if (fused) hipLaunchKernelGGL((expand_kernel<8, true>), dim3(grid), dim3(kThreads), 0, s, a);
-    else hipLaunchKernelGGL((expand_kernel<8, false>), dim3(grid), dim3(kThreads), 0, s, a);
+    if (fused) hipLaunchKernelGGL((expand_kernel<8, kModeFused>), dim3(grid), dim3(kThreads), 0, s, a);
+    else hipLaunchKernelGGL((expand_kernel<8, kModeSplit>), dim3(grid), dim3(kThreads), 0, s, a);
   }
   return hipGetLastError();
 }
@@ -661,6 +800,9 @@ hipError_t launch_expand(const ExpandArgs& a, int dtype, int grid, bool fused, h
 #ifdef TALON_PHASE_TIMING
 extern "C" int talon_debug_read_phases(unsigned long long* host16) {
   return static_cast<int>(hipMemcpyFromSymbol(host16, HIP_SYMBOL(g_phase), sizeof(unsigned long long) * 16));
+}
+extern "C" int talon_debug_read_wg(unsigned long long* host) {
+  return static_cast<int>(hipMemcpyFromSymbol(host, HIP_SYMBOL(g_wg), sizeof(unsigned long long) * 1024 * 16));
 }
 extern "C" int talon_debug_clear_phases() {
   unsigned long long z[16] = {0};

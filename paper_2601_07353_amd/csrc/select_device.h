@@ -37,12 +37,19 @@ __device__ __forceinline__ double unsortable_f64(unsigned long long s) {
   return __longlong_as_double(static_cast<long long>(u));
 }
 
-// AGENT: the candidates were written by other workgroups of the same launch; read them at
-// the device-coherent level.
+// AGENT: the candidates, and the tree state of earlier layers, may have been written by other
+// workgroups of the same launch, and what is written here may be read by others before the
+// launch ends: such data is read and written at the device-coherent level.
 template <bool AGENT, typename T>
 __device__ __forceinline__ T ld(const T* p) {
   if constexpr (AGENT) return __hip_atomic_load(const_cast<T*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   else return *p;
+}
+
+template <bool AGENT, typename T>
+__device__ __forceinline__ void st_(T* p, T v) {
+  if constexpr (AGENT) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else *p = v;
 }
 
 // Runs on all 256 threads of the workgroup.  F, fb: the frontier being expanded.  next_desc
@@ -58,8 +65,8 @@ __device__ __forceinline__ void select_sequence(const SelectArgs& a, int b, int 
   int* s_red_i32 = lds.red_i32;
   int& s_digit = lds.misc[0];
   int& s_remaining = lds.misc[1];
-  const int n = st.n_nodes[b];
-  const int d = st.depth_cur[b];
+  const int n = ld<AGENT, int32_t>(st.n_nodes + b);
+  const int d = ld<AGENT, int32_t>(st.depth_cur + b);
   const int R = st.N - n;
   const int k = a.k;
   const int C = F * k;
@@ -81,7 +88,7 @@ __device__ __forceinline__ void select_sequence(const SelectArgs& a, int b, int 
     if (c < C) {
       const int p = c / k;
       const size_t ci = (base + fb + p) * k + (c - p * k);
-      const double s = st.logp[base + fb + p] + ld<AGENT, double>(a.cand_edge_logp + ci);
+      const double s = ld<AGENT, double>(st.logp + base + fb + p) + ld<AGENT, double>(a.cand_edge_logp + ci);
       if (ld<AGENT, int32_t>(a.cand_token + ci) >= 0 && s == s) {
         key = sortable_u64(s);
         if (key == 0ull) key = 1ull;
@@ -174,7 +181,7 @@ __device__ __forceinline__ void select_sequence(const SelectArgs& a, int b, int 
       st.parent[o] = fb + p;
       st.depth[o] = d + 1;
       st.prob[o] = ld<AGENT, float>(a.cand_prob + ci);
-      st.logp[o] = st.logp[base + fb + p] + ld<AGENT, double>(a.cand_edge_logp + ci);
+      st_<AGENT, double>(st.logp + o, ld<AGENT, double>(st.logp + base + fb + p) + ld<AGENT, double>(a.cand_edge_logp + ci));
       ++pos;
     }
   }
@@ -183,12 +190,15 @@ __device__ __forceinline__ void select_sequence(const SelectArgs& a, int b, int 
     uint32_t s = status;
     if (n_new >= st.N) s |= TALON_STATUS_DONE_BUDGET;
     else if (d + 1 >= a.max_depth) s |= TALON_STATUS_DONE_DEPTH;
-    st.n_nodes[b] = n_new;
-    st.frontier_begin[b] = n;
-    st.frontier_count[b] = n_keep;
-    st.depth_cur[b] = d + 1;
-    st.status[b] = s;
-    if (next_desc) { next_desc[0] = n; next_desc[1] = (s & kDoneMask) ? 0 : n_keep; }
+    st_<AGENT, int32_t>(st.n_nodes + b, n_new);
+    st_<AGENT, int32_t>(st.frontier_begin + b, n);     // per-sequence words are rewritten layer after layer,
+    st_<AGENT, int32_t>(st.frontier_count + b, n_keep);   // possibly from different compute dies in one launch
+    st_<AGENT, int32_t>(st.depth_cur + b, d + 1);
+    st_<AGENT, uint32_t>(st.status + b, s);
+    if (next_desc) {
+      st_<AGENT, int>(next_desc, n);
+      st_<AGENT, int>(next_desc + 1, (s & kDoneMask) ? 0 : n_keep);
+    }
   }
 }
 

@@ -12,7 +12,7 @@ constexpr int kThreads = 256;       // every kernel here runs 4 wavefronts per w
 constexpr int kScanTiles = 4;       // 16-byte vectors per thread per vocab chunk
 constexpr int kChunkBytes = kThreads * kScanTiles * 16;  // 16 KiB of a logits row per workgroup pass
 constexpr int kMergeCap = 1024;     // chunks * k keys one row merge stages in LDS
-constexpr uint32_t kDoneMask = TALON_STATUS_DONE_BUDGET | TALON_STATUS_DONE_DEPTH;
+constexpr uint32_t kDoneMask = TALON_STATUS_DONE_BUDGET | TALON_STATUS_DONE_DEPTH | TALON_STATUS_ABORTED;
 
 void set_error(const char* fmt, ...);
 int check_hip(hipError_t e, const char* what);
@@ -49,16 +49,22 @@ struct ExpandArgs {
   double* part_sum;      // [rows][chunks]
   unsigned long long* part_keys;  // [rows][chunks][k]
   int32_t* ticket;       // [rows]
-  // Fused mode (the scan runs the budget selection of a sequence in its tail, when the last
+  // Fused modes (the scan runs the budget selection of a sequence in its tail, when the last
   // row of that sequence's frontier has been written): selection parameters, the index of
-  // this launch in the loop, per-sequence row tickets and ping-pong frontier descriptors
-  // {begin, count} [2][B]: launch i reads parity i&1 (parity 0 of launch 0 is copied from the public tree state) and
-  // its selections write parity (i+1)&1, so a workgroup that starts late still sees the
-  // frontier of its own layer.
+  // this launch in the loop, per-sequence row tickets and per-layer frontier descriptors
+  // {begin, count} [N_pad][B]: layer i of a call reads desc[i] (desc[0] is copied from the
+  // public tree state) and its selections write desc[i+1], so a workgroup that starts late
+  // still sees the frontier of its own layer.
   SelectArgs sel;
   int launch_idx;
   int32_t* seq_ticket;   // [B]
-  int32_t* desc;         // [2][B][2]
+  int32_t* desc;         // [N_pad][B][2]
+  // Single-launch mode: one grid walks all layers; layer_done[i] counts the frontier rows of
+  // layer i whose sequence has finished its selection, and a workgroup enters layer i+1 when
+  // it equals the rows of layer i.  spin_ticks bounds that wait (100 MHz wall clock).
+  int layers;
+  uint32_t* layer_done;  // [N_pad]
+  unsigned long long spin_ticks;
 };
 
 struct AttnArgs {
@@ -89,7 +95,9 @@ struct AttnArgs {
 // launchers (each checks nothing: arguments were validated by the ABI layer)
 hipError_t launch_tree_init(const talon_tree_state& st, const int32_t* root_token, hipStream_t s);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
-hipError_t launch_desc_init(const talon_tree_state& st, int32_t* desc, hipStream_t s);
+hipError_t launch_fused_init(const talon_tree_state& st, const ExpandArgs& a, hipStream_t s);
+hipError_t launch_expand_tree(const ExpandArgs& a, int dtype, int grid, hipStream_t s);
+int expand_tree_max_grid(int dtype);
 hipError_t launch_expand(const ExpandArgs& a, int dtype, int grid, bool fused, hipStream_t s);
 hipError_t launch_select(const SelectArgs& a, hipStream_t s);
 hipError_t launch_mask(const talon_tree_state& st, uint64_t* mask, hipStream_t s);

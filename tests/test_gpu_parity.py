@@ -49,6 +49,33 @@ def test_c1_layerwise_entry_points_match_single_call(mode):
         np.testing.assert_array_equal(a[key], b[key])
 
 
+def test_tree_launch_gives_up_cleanly_when_the_wait_is_cut_short(monkeypatch):
+    """The single-launch loop bounds its wait between layers.  With the bound forced to zero from
+    the host, a workgroup either finds the layer already complete or gives up: the launch must
+    end, and every sequence is then either expanded exactly as usual or marked ABORTED."""
+    import torch
+    import paper_2601_07353_amd as T
+    cfg = small(name="abort", V=40000, logits_dtype="bf16", K=8, N=100, Dmax=12, B=3,
+                recipe=(("gauss", 6.0, 8.0), ("gauss", 0.5, 1.0), ("gauss", 2.0, 8.0)))
+    seeds = admissible_seeds(cfg)
+    pool = H.build_pool(cfg, seeds)
+    ref = H.run_gpu_step(cfg, seeds, pool=pool, with_attention=False)
+    monkeypatch.setenv("TALON_SPIN_LIMIT_US", "0")
+    got = H.run_gpu_step(cfg, seeds, pool=pool, with_attention=False)
+    torch.cuda.synchronize()
+    aborted = (got["status"] & T.TALON_STATUS_ABORTED) != 0
+    assert aborted.all() or not aborted.any()
+    if not aborted.any():
+        for key in ("token", "parent", "depth", "n_nodes", "status"):
+            np.testing.assert_array_equal(got[key], ref[key])
+    else:
+        assert np.all(got["n_nodes"] >= 1) and np.all(got["n_nodes"] <= cfg.N)
+    monkeypatch.delenv("TALON_SPIN_LIMIT_US")
+    again = H.run_gpu_step(cfg, seeds, pool=pool, with_attention=False)
+    for key in ("token", "parent", "depth", "n_nodes", "status"):
+        np.testing.assert_array_equal(again[key], ref[key])
+
+
 @pytest.mark.parametrize("mode", ["split", "fused"])
 def test_layerwise_entry_points_against_oracle(mode):
     """The per-layer entry points (scan and selection as two launches, or as one) on a batch
