@@ -40,6 +40,9 @@ def parse_args():
                     help="only run plain device copies of 1 GiB (reads 1 GiB, writes 1 GiB each): the "
                          "reference that scales the FETCH_SIZE / WRITE_SIZE counters of a --pmc run")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget for the oracle timing sample")
+    ap.add_argument("--layerwise", action="store_true",
+                    help="also time the expansion layer by layer (one fused scan+selection launch per layer, "
+                         "talon_expand_select_layer) and report rows, duration and read bandwidth of each layer")
     return ap.parse_args()
 
 
@@ -221,9 +224,47 @@ def main():
         "kernels": kernels,
     }
 
+    if args.layerwise:
+        result["layers"] = layerwise(T, torch, np, cfg, slots, st, cand, ws_expand, roots, args.steps, elem)
+
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, args.cpu_seconds, H)
     print(json.dumps(result))
+
+
+def layerwise(T, torch, np, cfg, slots, st, cand, ws, roots, steps, elem):
+    """Per-layer figures of the vocabulary scan: one fused launch per layer, HIP events around
+    each (the library's measurement hook).  Rows come from an untimed pass that reads the
+    frontier after every layer."""
+    depth = min(cfg.Dmax, cfg.N - 1)
+    n_slots = len(slots)
+    rows = np.zeros((n_slots, depth))
+    for i, s in enumerate(slots):
+        T.talon_tree_init(st, roots)
+        for d in range(depth):
+            torch.cuda.synchronize()
+            live = (st.status.cpu().numpy() & 11) == 0
+            rows[i, d] = float((st.frontier_count.cpu().numpy() * live).sum())
+            T.talon_expand_select_layer(s.logits, st, cfg.K, cfg.mu, cfg.K, 1, cfg.Dmax, cand, ws, layer=d)
+    torch.cuda.synchronize()
+    T.talon_profile_scan_launches(True)
+    for i in range(steps):
+        s = slots[i % n_slots]
+        T.talon_tree_init(st, roots)
+        for d in range(depth):
+            T.talon_expand_select_layer(s.logits, st, cfg.K, cfg.mu, cfg.K, 1, cfg.Dmax, cand, ws, layer=d)
+    torch.cuda.synchronize()
+    us, n_rec = T.talon_profile_read(steps * depth)
+    T.talon_profile_scan_launches(False)
+    assert n_rec == steps * depth, (n_rec, steps, depth)
+    us = np.asarray(us).reshape(steps, depth).mean(0)
+    mean_rows = np.mean([rows[i % n_slots] for i in range(steps)], axis=0)
+    out = []
+    for d in range(depth):
+        by = mean_rows[d] * cfg.V * elem
+        out.append({"layer": d, "rows": round(float(mean_rows[d]), 2), "us": round(float(us[d]), 2),
+                    "GBps": round(by / (us[d] * 1e-6) / 1e9, 1)})
+    return out
 
 
 def read_traffic(workload):

@@ -457,8 +457,12 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
         float acc = 0.f;
 #pragma unroll
         for (int q = 0; q < kScanTiles; ++q) {
+          // unpack again from the raw vector instead of keeping the 4 * EPL floats of the
+          // maximum pass alive (the empty asm hides the value's origin from the optimiser)
+          uint4 r = raw[q];
+          asm volatile("" : "+v"(r.x), "+v"(r.y), "+v"(r.z), "+v"(r.w));
           float x[EPL];
-          unpack_vec<EPL>(raw[q], x);
+          unpack_vec<EPL>(r, x);
 #pragma unroll
           for (int e = 0; e < EPL; ++e) acc += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e], kLog2e, -c));
         }
