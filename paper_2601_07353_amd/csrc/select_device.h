@@ -107,16 +107,43 @@ __device__ __forceinline__ void select_sequence(const SelectArgs& a, int b, int 
     if (thr_key == 0ull) thr_key = 1ull;
   }
 
+  // candidates that pass the gate, and the lowest of their keys
   int n_pass_local = 0;
-  for (int i = 0; i < per; ++i) n_pass_local += (my[i] >= thr_key) ? 1 : 0;
-  const int n_pass = block_sum_i32(n_pass_local, s_red_i32);
+  unsigned long long inv_low = 0ull;   // max of ~key over the passing keys
+  for (int i = 0; i < per; ++i) {
+    const unsigned long long key = my[i];
+    if (key >= thr_key) { ++n_pass_local; inv_low = ~key > inv_low ? ~key : inv_low; }
+  }
+  n_pass_local = wave_sum_i32(n_pass_local);
+  inv_low = wave_max_u64(inv_low);
+  __syncthreads();
+  if ((tid & 63) == 0) { s_red_i32[tid >> 6] = n_pass_local; s_red_u64[tid >> 6] = inv_low; }
+  __syncthreads();
+  const int n_pass = s_red_i32[0] + s_red_i32[1] + s_red_i32[2] + s_red_i32[3];
 
   unsigned long long T = thr_key;     // keep key > T, and the first need_eq keys == T
   int need_eq = 0x7FFFFFFF;
   if (n_pass > limit) {
-    // ---- radix select: the limit-th largest key, 8 bits per pass from the top
+    // ---- radix select: the limit-th largest key, 8 bits per pass from the top.
+    // Path scores of one layer lie close together, so their keys share their leading bits.
+    // The keys are first moved to the range they span: key' = (key - lowest + 1) << s with s
+    // such that the largest key' has its top bit set (order and ties are preserved, keys
+    // below the gate become 0 = no candidate).  The digits of key' are spread over the bins,
+    // and the search usually ends after two or three passes: as soon as the bin that holds
+    // the limit-th key holds exactly as many keys as are still wanted.
+    unsigned long long a01 = s_red_u64[0] > s_red_u64[1] ? s_red_u64[0] : s_red_u64[1];
+    unsigned long long a23 = s_red_u64[2] > s_red_u64[3] ? s_red_u64[2] : s_red_u64[3];
+    const unsigned long long low_key = ~(a01 > a23 ? a01 : a23);
+    const int sh = __clzll(static_cast<long long>(anchor_key - low_key + 1ull));
+    for (int i = 0; i < per; ++i) {
+      const unsigned long long key = my[i];
+      my[i] = key >= thr_key ? (key - low_key + 1ull) << sh : 0ull;
+    }
     unsigned long long prefix = 0ull;
     int remaining = limit;
+    T = 0ull;
+    need_eq = 0;
+    bool found = false;
     for (int pass = 0; pass < 8; ++pass) {
       const int shift = 56 - 8 * pass;
       s_hist[tid] = 0;
@@ -138,21 +165,30 @@ __device__ __forceinline__ void select_sequence(const SelectArgs& a, int b, int 
         if (tid == first) {
           int before = incl - lane_sum;
           int dg = 255 - 4 * tid;
+          int j = 0;
 #pragma unroll
-          for (int j = 0; j < 3; ++j) {
+          for (; j < 3; ++j) {
             if (before + h[j] < remaining) { before += h[j]; --dg; } else break;
           }
-          s_digit = dg;
-          s_remaining = remaining - before;
+          const int want = remaining - before;
+          // the bin holds exactly the keys still wanted: all of them are kept
+          s_digit = dg | ((h[j] == want) ? 256 : 0);
+          s_remaining = want;
         }
       }
       __syncthreads();
-      prefix |= static_cast<unsigned long long>(s_digit) << shift;
+      const int dg = s_digit;
+      prefix |= static_cast<unsigned long long>(dg & 255) << shift;
       remaining = s_remaining;
       __syncthreads();
+      if (dg & 256) {   // keep every key >= prefix (lower digits zero): none equals prefix - 1 with a claim
+        T = prefix != 0ull ? prefix - 1ull : 0ull;   // prefix 0: every candidate left is kept
+        need_eq = 0;
+        found = true;
+        break;
+      }
     }
-    T = prefix;
-    need_eq = remaining;
+    if (!found) { T = prefix; need_eq = remaining; }
   }
 
   // ---- keep flags, ranks among equal keys, compaction
