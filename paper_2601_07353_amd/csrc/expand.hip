@@ -691,8 +691,10 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
   return total_rows;
 }
 
+// With the selection in its tail the kernel needs about 160 vector registers: three
+// workgroups per compute unit instead of four, rather than spilling.
 template <int EPL, int MODE>
-__global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
+__global__ __launch_bounds__(kThreads, MODE == kModeSplit ? 4 : 3) void expand_kernel(ExpandArgs a) {
   static_assert(MODE != kModeTree, "the single-launch loop has its own kernel");
   expand_body<EPL, MODE>(a, a.launch_idx);
 }
@@ -702,7 +704,7 @@ __global__ __launch_bounds__(kThreads, 4) void expand_kernel(ExpandArgs a) {
 // layer it has just left, which other workgroups run.  The wait is bounded; a workgroup that
 // gives up marks every sequence TALON_STATUS_ABORTED and leaves, and so do all others.
 template <int EPL>
-__global__ __launch_bounds__(kThreads, 4) void expand_tree_kernel(ExpandArgs a) {
+__global__ __launch_bounds__(kThreads, 3) void expand_tree_kernel(ExpandArgs a) {
   __shared__ int s_go;
   for (int d = 0; d < a.layers; ++d) {
     const int rows = expand_body<EPL, kModeTree>(a, d);
