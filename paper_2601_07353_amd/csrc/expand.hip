@@ -5,8 +5,7 @@
 // Work decomposition.  A row is a sequence of 16 KiB blocks (8192 bf16 / 4096 f32 logits);
 // a block is what one workgroup holds in registers at a time (4 x 16-byte loads per
 // thread).  A row is cut into `chunks` runs of consecutive blocks; one (row, chunk) item is
-// streamed by one workgroup with the next block's loads in flight while the current one is
-// processed.  The number of chunks per row is chosen on the device from the total number
+// streamed by one workgroup.  The number of chunks per row is chosen on the device from the total number
 // of frontier rows of the launch (few rows: many short chunks, so that a one-row layer
 // still spreads over the chip; many rows: one long chunk per row, so that the per-item
 // fixed work vanishes).  A fixed-size grid walks the items with a grid stride; nothing
@@ -16,8 +15,8 @@
 //   - softmax: every lane keeps its own running max and a double-precision running sum of
 //     exp(logit - max), rescaled only when its max grows (rare after the first blocks);
 //   - top-k: every wavefront keeps its k best keys so far and a threshold tau.  The first
-//     group of 4 tiles sets tau to the k-th largest of the 64 per-lane maxima (at least k
-//     logits of the group reach it).  A lane whose 16-byte vector holds a logit that
+//     group of 4 tiles sets tau from the 64 per-lane maxima, to a value that at least k of
+//     them reach.  A lane whose 16-byte vector holds a logit that
 //     reaches tau drops the whole vector into an LDS buffer (a few instructions, no
 //     per-logit work); when the buffer runs full, and at the end, the buffered vectors are
 //     expanded, ranked against the k best, and tau rises to the new k-th best.  After such
@@ -27,6 +26,13 @@
 // The workgroup then merges its four lists and statistics.  With one chunk per row it
 // writes the row's outputs directly; otherwise it stores a partial result and the
 // workgroup that completes the row's last chunk (atomic ticket) merges the partials.
+//
+// Three ways to run it.  Scan only (talon_expand_layer).  Scan with the budget selection
+// (Sec. 5.2, Alg. 2 "Hybrid Expansion Strategy" and "Budget Check") in its tail: the
+// workgroup that writes the last row of a sequence's frontier selects for that sequence, one
+// launch per layer (talon_expand_select_layer).  Or one launch for the whole loop of Alg. 2
+// (talon_expand_tree): the grid walks the layers and enters the next one when all selections
+// of the current one are published.
 //
 // Exactness.  Ordering is by the 64-bit integer key (sortable(logit) << 32 | ~token), so
 // the order (logit descending, token ascending) is exact; floating point only enters the

@@ -99,6 +99,36 @@ def test_select_rejects_bad_arguments(lib):
     assert lib.talon_select_budget(None, 4, P, P, P, ctypes.c_float(0.03), 4, 1, 8, None) == T.TALON_ERR_INVALID_ARG
 
 
+def fused_call(lib, fn, st, k=4, mu=0.03, K_init=4, init_layers=1, max_depth=8, vocab=1024, ws_bytes=1 << 30):
+    args = [P, 1, 1024, 1024 * 64, 0]
+    if fn == "talon_expand_select_layer":
+        args.append(-1)
+    args += [ctypes.byref(st), vocab, k, ctypes.c_float(mu), K_init, init_layers, max_depth, P, P, P, P, P, P, P,
+             ws_bytes, None]
+    return getattr(lib, fn)(*args)
+
+
+@pytest.mark.parametrize("fn", ["talon_expand_select_layer", "talon_expand_tree"])
+def test_fused_calls_reject_bad_arguments(lib, fn):
+    st = fake_state()
+    assert fused_call(lib, fn, st, k=0) == T.TALON_ERR_INVALID_ARG
+    assert fused_call(lib, fn, st, vocab=0) == T.TALON_ERR_INVALID_ARG
+    assert fused_call(lib, fn, st, mu=0.0) == T.TALON_ERR_INVALID_ARG and "mu" in err(lib)
+    assert fused_call(lib, fn, st, mu=2.0) == T.TALON_ERR_INVALID_ARG
+    assert fused_call(lib, fn, st, K_init=0) == T.TALON_ERR_INVALID_ARG
+    assert fused_call(lib, fn, st, max_depth=0) == T.TALON_ERR_INVALID_ARG
+    assert fused_call(lib, fn, st, ws_bytes=64) == T.TALON_ERR_WORKSPACE
+    assert fused_call(lib, fn, fake_state(B=0)) == T.TALON_ERR_INVALID_ARG
+
+
+def test_profile_hook_host_side(lib):
+    n = ctypes.c_int32(-1)
+    assert lib.talon_profile_read(None, 0, None) == T.TALON_ERR_INVALID_ARG
+    assert lib.talon_profile_read(None, 4, ctypes.byref(n)) == T.TALON_ERR_INVALID_ARG
+    assert lib.talon_profile_scan_launches(0) == T.TALON_OK
+    assert lib.talon_profile_read(None, 0, ctypes.byref(n)) == T.TALON_OK and n.value == 0
+
+
 def test_mask_and_init_reject_bad_arguments(lib):
     st = fake_state()
     assert lib.talon_build_tree_mask(ctypes.byref(st), None, None) == T.TALON_ERR_INVALID_ARG
