@@ -40,6 +40,9 @@ def parse_args():
                     help="only run plain device copies of 1 GiB (reads 1 GiB, writes 1 GiB each): the "
                          "reference that scales the FETCH_SIZE / WRITE_SIZE counters of a --pmc run")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget for the oracle timing sample")
+    ap.add_argument("--attainable", action="store_true",
+                    help="only run the library's two probes: a streaming read of 1 GiB and 512 MiB buffers (cold) "
+                         "and a register-resident bf16 MFMA loop; prints the rates they reach")
     ap.add_argument("--layerwise", action="store_true",
                     help="also time the expansion layer by layer (one fused scan+selection launch per layer, "
                          "talon_expand_select_layer) and report rows, duration and read bandwidth of each layer")
@@ -90,6 +93,10 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration": {"bytes_read": 1 << 30, "bytes_written": 1 << 30, "copies": 10}}))
+        return
+
+    if args.attainable:
+        print(json.dumps({"attainable": attainable(T, torch)}))
         return
 
     elem = cfg.elem_bytes
@@ -230,6 +237,34 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, args.cpu_seconds, H)
     print(json.dumps(result))
+
+
+def attainable(T, torch):
+    """Rates a plain kernel reaches on this device: read GB/s of a streaming pass over a buffer
+    that no cache holds (three 1 GiB buffers in rotation, then 512 MiB pieces of them), and
+    TFLOP/s of a register-resident bf16 MFMA loop on every SIMD (8 wavefronts per SIMD)."""
+    bufs = [torch.empty(1 << 30, dtype=torch.uint8, device="cuda").random_(0, 255) for _ in range(3)]
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    out = {}
+    for label, nbytes in (("read_1GiB", 1 << 30), ("read_512MiB", 1 << 29)):
+        evs = []
+        for i in range(12):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(); T.talon_probe_read(bufs[i % 3][:nbytes], sink); e1.record()
+            evs.append((e0, e1))
+        torch.cuda.synchronize()
+        ms = sorted(e0.elapsed_time(e1) for e0, e1 in evs[3:])
+        out[label] = {"us_median": ms[len(ms) // 2] * 1e3, "GBps": nbytes / (ms[len(ms) // 2] * 1e-3) / 1e9}
+    wgs, iters = 256 * 8, 20000
+    evs = []
+    for i in range(6):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(); fl = T.talon_probe_mfma(wgs, iters, sink); e1.record()
+        evs.append((e0, e1))
+    torch.cuda.synchronize()
+    ms = sorted(e0.elapsed_time(e1) for e0, e1 in evs[1:])
+    out["mfma_bf16_32x32x16"] = {"us_median": ms[len(ms) // 2] * 1e3, "TFLOPs": fl / (ms[len(ms) // 2] * 1e-3) / 1e12}
+    return out
 
 
 def layerwise(T, torch, np, cfg, slots, st, cand, ws, roots, steps, elem):

@@ -177,6 +177,18 @@ int talon_profile_scan_launches(int enable);
 int talon_profile_read(float* durations_us, int32_t capacity, int32_t* n_launches);
 
 /*
+ * Attainable-rate probes (no counterpart in the paper), for a second denominator beside the
+ * published peaks.  talon_probe_read streams `bytes` of the device buffer `buf` (16-byte
+ * aligned) through the vector units once and writes nothing; talon_probe_mfma runs, on
+ * `workgroups` workgroups of 4 wavefronts, `iters` rounds of 4 independent
+ * v_mfma_f32_32x32x16_bf16 on register operands and stores the FLOP count of the launch in
+ * *flops (host, optional).  `sink` is a 4-byte device word that is never actually written.
+ * The caller times the launches.  Errors: INVALID_ARG.
+ */
+int talon_probe_read(const void* buf, size_t bytes, void* sink, void* stream);
+int talon_probe_mfma(int32_t workgroups, int32_t iters, void* sink, double* flops, void* stream);
+
+/*
  * Tree attention mask (Fig. 5(b); App. B): bit j of row i is set iff node j is node i or
  * one of its ancestors, the root included.
  *   mask [B][N_pad][N_pad/64] uint64, bit j of row i = word j/64, bit j%64.

@@ -35,7 +35,7 @@ TALON_ROWS_BY_FRONTIER = 1
 EXPORTS = [
     "talon_last_error_string", "talon_tree_init", "talon_expand_workspace_bytes",
     "talon_expand_workspace_init", "talon_expand_layer", "talon_select_budget", "talon_expand_select_layer",
-    "talon_expand_tree", "talon_profile_scan_launches", "talon_profile_read",
+    "talon_expand_tree", "talon_profile_scan_launches", "talon_profile_read", "talon_probe_read", "talon_probe_mfma",
     "talon_build_tree_mask", "talon_tree_attention_workspace_bytes", "talon_tree_attention",
 ]
 
@@ -83,6 +83,8 @@ def load_library() -> ctypes.CDLL:
                                               P, c_size_t, P]
     lib.talon_profile_scan_launches.argtypes = [c_int]
     lib.talon_profile_read.argtypes = [POINTER(c_float), c_int32, POINTER(c_int32)]
+    lib.talon_probe_read.argtypes = [P, c_size_t, P, P]
+    lib.talon_probe_mfma.argtypes = [c_int32, c_int32, P, POINTER(c_double), P]
     lib.talon_build_tree_mask.argtypes = [POINTER(_CTreeState), P, P]
     lib.talon_tree_attention_workspace_bytes.restype = c_size_t
     lib.talon_tree_attention_workspace_bytes.argtypes = [c_int32] * 6
@@ -226,6 +228,17 @@ def talon_profile_read(capacity: int):
     n = c_int32(0)
     _check(load_library().talon_profile_read(buf, capacity, ctypes.byref(n)))
     return [float(buf[i]) for i in range(min(n.value, capacity))], n.value
+
+
+def talon_probe_read(buf: torch.Tensor, sink: torch.Tensor, stream=None):
+    _check(load_library().talon_probe_read(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), _stream(stream)))
+
+
+def talon_probe_mfma(workgroups: int, iters: int, sink: torch.Tensor, stream=None) -> float:
+    """Launches the MFMA probe; returns the FLOPs of the launch."""
+    fl = c_double(0.0)
+    _check(load_library().talon_probe_mfma(workgroups, iters, _ptr(sink), ctypes.byref(fl), _stream(stream)))
+    return fl.value
 
 
 def talon_build_tree_mask(st: TreeState, mask: torch.Tensor, stream=None):

@@ -364,6 +364,24 @@ int talon_profile_read(float* durations_us, int32_t capacity, int32_t* n_launche
   return TALON_OK;
 }
 
+int talon_probe_read(const void* buf, size_t bytes, void* sink, void* stream) {
+  if (!buf || !sink || bytes < 16 || (reinterpret_cast<uintptr_t>(buf) & 15u)) {
+    set_error("talon_probe_read: needs a 16-byte aligned device buffer of at least 16 bytes and a 4-byte device sink");
+    return TALON_ERR_INVALID_ARG;
+  }
+  return check_hip(launch_read_probe(buf, bytes, sink, static_cast<hipStream_t>(stream)), "read probe launch");
+}
+
+int talon_probe_mfma(int32_t workgroups, int32_t iters, void* sink, double* flops, void* stream) {
+  if (!sink || workgroups < 1 || workgroups > 65536 || iters < 1) {
+    set_error("talon_probe_mfma: workgroups in [1, 65536], iters >= 1 and a 4-byte device sink are required");
+    return TALON_ERR_INVALID_ARG;
+  }
+  // 4 wavefronts per workgroup, 4 MFMA 32x32x16 per iteration, 2*32*32*16 FLOP each
+  if (flops) *flops = static_cast<double>(workgroups) * 4.0 * iters * 4.0 * 32768.0;
+  return check_hip(launch_mfma_probe(workgroups, iters, sink, static_cast<hipStream_t>(stream)), "mfma probe launch");
+}
+
 int talon_build_tree_mask(const talon_tree_state* st, uint64_t* mask, void* stream) {
   int rc = check_state(st);
   if (rc) return rc;

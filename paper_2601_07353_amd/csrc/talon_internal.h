@@ -95,6 +95,8 @@ struct AttnArgs {
 // launchers (each checks nothing: arguments were validated by the ABI layer)
 hipError_t launch_tree_init(const talon_tree_state& st, const int32_t* root_token, hipStream_t s);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+hipError_t launch_read_probe(const void* buf, size_t bytes, void* sink, hipStream_t s);
+hipError_t launch_mfma_probe(int workgroups, int iters, void* sink, hipStream_t s);
 hipError_t launch_fused_init(const talon_tree_state& st, const ExpandArgs& a, hipStream_t s);
 hipError_t launch_expand_tree(const ExpandArgs& a, int dtype, int grid, hipStream_t s);
 int expand_tree_max_grid(int dtype);
