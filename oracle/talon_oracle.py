@@ -19,6 +19,12 @@ What each function follows:
   build_tree_mask      each tree token sees its root-to-node path (Fig. 5(b), App. B)
   tree_attention       one attention layer under that mask plus the whole prefix
                        (App. B "Tree Attention")
+  target_argmax        the target model's greedy token after each tree node (temperature 0)
+  greedy_accept        verification at temperature 0: the longest root path on which every
+                       drafted token is the target's own choice ("accepting the longest
+                       matched prefix", Sec. 2; App. B step (2), "selecting the optimal
+                       valid prefix"); the token after it comes from the target
+  compact_kv           the accepted tokens' keys and values join the prefix cache
 
 Readings taken where the paper is silent (each also listed in the design notes):
   * per-row candidate cap `cap`: the pool of a parent is its `cap` best tokens.
@@ -292,3 +298,44 @@ def tree_attention(q: np.ndarray, k_prefix: np.ndarray, v_prefix: np.ndarray,
                 out[i, h] = (e / z) @ vals
                 lse[i, h] = mx + math.log(z)
     return out, lse
+
+
+# --------------------------------------------------------------------------
+# verification outcome at temperature 0 (greedy): acceptance walk and cache update
+# --------------------------------------------------------------------------
+def target_argmax(row: np.ndarray) -> int:
+    """Greedy token of one target-logits row: the largest logit, lowest id among equals
+    (-0.0 equals +0.0)."""
+    x = np.asarray(row, dtype=np.float64) + 0.0
+    return int(np.argmax(x))   # numpy returns the first (lowest-id) maximum
+
+
+def greedy_accept(token: List[int], parent: List[int], target_token: List[int]):
+    """Longest accepted path of a draft tree at temperature 0.
+
+    token[i], parent[i]: the tree (node 0 is the root, the last verified token);
+    target_token[i]: the target's greedy token after node i.  Starting at the root, the
+    child whose drafted token equals the target's token at the current node is accepted and
+    becomes the current node; the walk stops where no child matches.  Returns
+    (path, bonus): the accepted node ids from the root on (the root is always on it), and the
+    target's token after the last accepted node (the token this step emits on top).
+    """
+    n = len(token)
+    path = [0]
+    cur = 0
+    while True:
+        want = target_token[cur]
+        nxt = [c for c in range(n) if parent[c] == cur and token[c] == want]
+        if not nxt:
+            break
+        cur = nxt[0]          # siblings carry distinct tokens: at most one can match
+        path.append(cur)
+    return path, int(target_token[cur])
+
+
+def compact_kv(cache: np.ndarray, tree: np.ndarray, path: List[int], prefix_len: int) -> int:
+    """Append the rows of `tree` [n][...] on the accepted path to `cache` [cap][...] at
+    positions prefix_len, prefix_len + 1, ... (in place); returns the new prefix length."""
+    for j, node in enumerate(path):
+        cache[prefix_len + j] = tree[node]
+    return prefix_len + len(path)

@@ -560,3 +560,97 @@ def test_logits_rows_are_pure_functions_of_their_key():
     assert not np.array_equal(a, logits_row(cfg, 5, 0, 4))
     assert not np.array_equal(a, logits_row(cfg, 6, 0, 3))
     assert a.dtype == np.float32 and a.shape == (1024,)
+
+
+# ---------------------------------------------------------------- greedy verification (T = 0)
+def test_target_argmax_matches_torch_and_tie_rule():
+    rng = np.random.default_rng(51)
+    for _ in range(20):
+        row = rng.normal(size=777)
+        assert O.target_argmax(row) == int(torch.argmax(torch.from_numpy(row)))
+    assert O.target_argmax(np.array([1.0, 3.0, 3.0, 2.0, 3.0])) == 1          # lowest id among equals
+    assert O.target_argmax(np.array([-1.0, -0.0, 0.0, -2.0])) == 1            # -0.0 ties with +0.0
+    assert O.target_argmax(np.array([-np.inf, -np.inf, -5.0])) == 2
+    # the greedy token is the first of the row's ranked candidates
+    row = rng.normal(size=500); row[100] = row[400] = row.max() + 1.0
+    assert O.target_argmax(row) == int(O.row_candidates(row, 1)[0]) == 100
+
+
+def _valid_nodes_by_definition(token, parent, target_token):
+    """Every node whose whole root path was drafted as the target would have chosen."""
+    def ok(i):
+        return i == 0 or (token[i] == target_token[parent[i]] and ok(parent[i]))
+    return [i for i in range(len(token)) if ok(i)]
+
+
+def random_tree(rng, n, vocab, fan=3):
+    token, parent = [int(rng.integers(vocab))], [-1]
+    while len(token) < n:
+        p = int(rng.integers(len(token)))
+        used = {token[c] for c in range(len(token)) if parent[c] == p}
+        if len(used) >= min(fan, vocab):
+            continue
+        t = int(rng.integers(vocab))
+        if t in used:
+            continue
+        token.append(t); parent.append(p)
+    return token, parent
+
+
+def test_greedy_accept_equals_the_set_definition_on_random_trees():
+    rng = np.random.default_rng(52)
+    lengths = []
+    for trial in range(300):
+        n = int(rng.integers(1, 30)); vocab = int(rng.integers(2, 5))
+        token, parent = random_tree(rng, n, vocab)
+        target = [int(rng.integers(vocab)) for _ in range(n)]
+        path, bonus = O.greedy_accept(token, parent, target)
+        valid = _valid_nodes_by_definition(token, parent, target)
+        # the valid nodes form one chain from the root, and the walk returns exactly it
+        assert sorted(path) == sorted(valid)
+        assert path[0] == 0 and all(parent[path[j + 1]] == path[j] for j in range(len(path) - 1))
+        # maximal: no child of the last accepted node carries the target's token; bonus is that token
+        last = path[-1]
+        assert bonus == target[last]
+        assert not any(parent[c] == last and token[c] == bonus for c in range(n))
+        lengths.append(len(path))
+    assert max(lengths) >= 4 and min(lengths) == 1      # the cases are not all trivial
+
+
+def test_greedy_accept_closed_forms():
+    # a chain drafted exactly as the target decodes: everything is accepted
+    n = 9
+    token = [50] + list(range(1, n)); parent = [-1] + list(range(n - 1))
+    target = [token[i + 1] for i in range(n - 1)] + [77]
+    assert O.greedy_accept(token, parent, target) == (list(range(n)), 77)
+    # one wrong draft token at depth d cuts the chain there
+    for d in range(1, n):
+        t2 = list(token); t2[d] = 999
+        path, bonus = O.greedy_accept(t2, parent, target)
+        assert path == list(range(d)) and bonus == target[d - 1]
+    # a star: the target's first token picks one leaf or none
+    token = [5, 10, 11, 12, 13]; parent = [-1, 0, 0, 0, 0]
+    assert O.greedy_accept(token, parent, [12, 1, 2, 3, 4]) == ([0, 3], 3)
+    assert O.greedy_accept(token, parent, [14, 1, 2, 3, 4]) == ([0], 14)
+    # a tree with only the root
+    assert O.greedy_accept([3], [-1], [8]) == ([0], 8)
+
+
+def test_greedy_accept_hand_worked_cases():
+    g = json.load(open(os.path.join(HERE, "golden", "accept_example.json")))
+    for case in g["cases"]:
+        path, bonus = O.greedy_accept(g["token"], g["parent"], case["target_token"])
+        assert path == case["path"] and bonus == case["bonus"], case["why"]
+
+
+def test_compact_kv_is_a_gather_appended_to_the_cache():
+    rng = np.random.default_rng(53)
+    L, cap, n = 7, 20, 10
+    cache = rng.normal(size=(cap, 2, 4)); tree = rng.normal(size=(n, 2, 4))
+    before = cache.copy()
+    path = [0, 2, 5, 9]
+    new_len = O.compact_kv(cache, tree, path, L)
+    assert new_len == L + 4
+    np.testing.assert_array_equal(cache[:L], before[:L])
+    np.testing.assert_array_equal(cache[L:new_len], tree[np.array(path)])
+    np.testing.assert_array_equal(cache[new_len:], before[new_len:])

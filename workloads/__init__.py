@@ -14,5 +14,7 @@ from .generators import (  # noqa: F401
     logits_pool,
     logits_row,
     storage_to_f64,
+    target_logits_pool,
+    target_logits_row,
     zipf_row,
 )

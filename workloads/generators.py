@@ -21,6 +21,7 @@ _TAG_KP = 0x22
 _TAG_VP = 0x23
 _TAG_KT = 0x24
 _TAG_VT = 0x25
+_TAG_TARGET = 0x31
 
 
 def _rng(seed: int, tag: int, b: int, i: int) -> np.random.Generator:
@@ -120,6 +121,29 @@ def logits_row(cfg: WorkloadConfig, seed: int, b: int, node: int) -> np.ndarray:
     else:
         raise ValueError(rec)
     return _store(x, cfg.logits_dtype)
+
+
+def target_logits_row(cfg: WorkloadConfig, seed: int, b: int, node: int, noise: float = 0.25) -> np.ndarray:
+    """Logits row the *target* model would emit at node `node` of sequence `b`: the draft's
+    stored row plus independent Gaussian noise of `noise` times the row's standard deviation,
+    so that the target mostly, but not always, agrees with the draft's best token (a stand-in
+    for a real drafter/target pair).  Stored in the config's logits type."""
+    draft = storage_to_f64(logits_row(cfg, seed, b, node)).astype(np.float32)
+    g = _rng(seed, _TAG_TARGET, b, node)
+    sd = np.float32(draft[np.isfinite(draft)].std()) if np.isfinite(draft).any() else np.float32(1.0)
+    x = draft + g.standard_normal(cfg.V, dtype=np.float32) * np.float32(noise) * sd
+    return _store(x, cfg.logits_dtype)
+
+
+def target_logits_pool(cfg: WorkloadConfig, seed, noise: float = 0.25) -> np.ndarray:
+    """Pool [B][N_pad][V] of target rows; `seed` is one seed or one per sequence."""
+    seeds = [seed] * cfg.B if np.isscalar(seed) else list(seed)
+    dt = np.float32 if cfg.logits_dtype == "f32" else np.uint16
+    pool = np.zeros((cfg.B, cfg.N_pad, cfg.V), dtype=dt)
+    for b in range(cfg.B):
+        for i in range(cfg.N):
+            pool[b, i] = target_logits_row(cfg, seeds[b], b, i, noise)
+    return pool
 
 
 def logits_pool(cfg: WorkloadConfig, seed: int, nodes=None) -> np.ndarray:
