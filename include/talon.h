@@ -177,6 +177,49 @@ int talon_profile_scan_launches(int enable);
 int talon_profile_read(float* durations_us, int32_t capacity, int32_t* n_launches);
 
 /*
+ * Verification outcome at temperature 0 (App. B "Token-Tree Verification", step (2): the
+ * longest valid prefix; Sec. 2: "accepting the longest matched prefix").  Three calls.
+ *
+ * talon_target_argmax: the target model's greedy token after every node of every tree.
+ *   logits: device, target logits, row i of sequence b at (b*seq_stride + i*row_stride)
+ *   elements (same layout rules as talon_expand_layer, rows by node).  Outputs, device:
+ *   target_token [B][N_pad] int32 (largest logit, lowest id among equals; rows >= n_nodes
+ *   untouched), target_prob [B][N_pad] float (softmax probability of that token; may be
+ *   NULL), scan_status [B] uint32 (TALON_STATUS_BAD_ROW if a row of the sequence held a NaN
+ *   or +inf).  One pass of the vocabulary scan with k = 1 over n_nodes rows per sequence.
+ *   `workspace`: talon_verify_workspace_bytes bytes of device memory, no initialisation
+ *   needed.  Errors as talon_expand_layer.
+ *
+ * talon_greedy_accept: starting at the root, the child whose drafted token equals the
+ *   target's token at the current node is accepted and becomes the current node, until no
+ *   child matches.  Outputs, device: path [B][N_pad] int32 (accepted node ids from the root
+ *   on, path[b][0] = 0, -1 beyond), accept_len [B] (accepted drafted tokens; the root is not
+ *   counted), bonus_token [B] (the target's token after the last accepted node).  A sequence
+ *   whose scan_status has BAD_ROW gets that bit in st->status; its outputs are then not
+ *   meaningful.
+ *
+ * talon_compact_kv: the keys and values of the accept_len[b] + 1 nodes on the path (tree
+ *   K/V [B][N_pad][Hkv][Dh] bf16) are copied to positions prefix_len[b] + j of the prefix
+ *   cache (strided as in talon_tree_attention), new_prefix_len[b] = prefix_len[b] +
+ *   accept_len[b] + 1.  Rows that would land at or beyond prefix_capacity are not written and
+ *   new_prefix_len is clamped to prefix_capacity.  The caller owns all buffers.
+ *   Errors: INVALID_ARG (NULL or misaligned pointers, Dh not a multiple of 8, strides).
+ */
+size_t talon_verify_workspace_bytes(int32_t B, int32_t N_pad, int32_t vocab, int dtype);
+int talon_target_argmax(const void* logits, int dtype, int64_t row_stride, int64_t seq_stride,
+                        const talon_tree_state* st, int32_t vocab, int32_t* target_token,
+                        float* target_prob, uint32_t* scan_status, void* workspace,
+                        size_t workspace_bytes, void* stream);
+int talon_greedy_accept(const talon_tree_state* st, const int32_t* target_token,
+                        const uint32_t* scan_status, int32_t* path, int32_t* accept_len,
+                        int32_t* bonus_token, void* stream);
+int talon_compact_kv(const void* k_tree, const void* v_tree, const int32_t* path,
+                     const int32_t* accept_len, const int32_t* prefix_len, int32_t* new_prefix_len,
+                     void* k_prefix, void* v_prefix, int32_t B, int32_t N_pad, int32_t Hkv,
+                     int32_t Dh, int32_t prefix_capacity, int64_t kv_stride_b, int64_t kv_stride_t,
+                     int64_t kv_stride_h, void* stream);
+
+/*
  * Attainable-rate probes (no counterpart in the paper), for a second denominator beside the
  * published peaks.  talon_probe_read streams `bytes` of the device buffer `buf` (16-byte
  * aligned) through the vector units once and writes nothing; talon_probe_mfma runs, on

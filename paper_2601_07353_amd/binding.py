@@ -35,7 +35,8 @@ TALON_ROWS_BY_FRONTIER = 1
 EXPORTS = [
     "talon_last_error_string", "talon_tree_init", "talon_expand_workspace_bytes",
     "talon_expand_workspace_init", "talon_expand_layer", "talon_select_budget", "talon_expand_select_layer",
-    "talon_expand_tree", "talon_profile_scan_launches", "talon_profile_read", "talon_probe_read", "talon_probe_mfma",
+    "talon_expand_tree", "talon_profile_scan_launches", "talon_profile_read", "talon_probe_read", "talon_probe_mfma", "talon_verify_workspace_bytes", "talon_target_argmax",
+    "talon_greedy_accept", "talon_compact_kv",
     "talon_build_tree_mask", "talon_tree_attention_workspace_bytes", "talon_tree_attention",
 ]
 
@@ -83,6 +84,12 @@ def load_library() -> ctypes.CDLL:
                                               P, c_size_t, P]
     lib.talon_profile_scan_launches.argtypes = [c_int]
     lib.talon_profile_read.argtypes = [POINTER(c_float), c_int32, POINTER(c_int32)]
+    lib.talon_verify_workspace_bytes.restype = c_size_t
+    lib.talon_verify_workspace_bytes.argtypes = [c_int32, c_int32, c_int32, c_int]
+    lib.talon_target_argmax.argtypes = [P, c_int, c_int64, c_int64, POINTER(_CTreeState), c_int32, P, P, P, P, c_size_t, P]
+    lib.talon_greedy_accept.argtypes = [POINTER(_CTreeState), P, P, P, P, P, P]
+    lib.talon_compact_kv.argtypes = [P, P, P, P, P, P, P, P, c_int32, c_int32, c_int32, c_int32, c_int32, c_int64,
+                                     c_int64, c_int64, P]
     lib.talon_probe_read.argtypes = [P, c_size_t, P, P]
     lib.talon_probe_mfma.argtypes = [c_int32, c_int32, P, POINTER(c_double), P]
     lib.talon_build_tree_mask.argtypes = [POINTER(_CTreeState), P, P]
@@ -269,3 +276,36 @@ def talon_tree_attention(q, k_prefix, v_prefix, k_tree, v_tree, mask, n_nodes, p
         _ptr(q), _ptr(k_prefix), _ptr(v_prefix), _ptr(k_tree), _ptr(v_tree), _ptr(mask), _ptr(n_nodes),
         _ptr(prefix_len), B, N_pad, Hq, Hkv, Dh, max_prefix_len, sb, st_, sh, c_float(scale), _ptr(out),
         _ptr(out_lse), _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def make_verify_workspace(B, N_pad, vocab, dtype) -> torch.Tensor:
+    nb = load_library().talon_verify_workspace_bytes(B, N_pad, vocab, dtype)
+    if nb == 0:
+        raise TalonError(TALON_ERR_INVALID_ARG, load_library().talon_last_error_string().decode())
+    return torch.empty(nb, dtype=torch.uint8, device="cuda")
+
+
+def talon_target_argmax(logits, st: TreeState, target_token, target_prob, scan_status, workspace, vocab=None,
+                        stream=None):
+    dt, row_stride, seq_stride, V = _logits_meta(logits)
+    _check(load_library().talon_target_argmax(
+        _ptr(logits), dt, row_stride, seq_stride, ctypes.byref(st.c), V if vocab is None else vocab,
+        _ptr(target_token), _ptr(target_prob), _ptr(scan_status), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def talon_greedy_accept(st: TreeState, target_token, scan_status, path, accept_len, bonus_token, stream=None):
+    _check(load_library().talon_greedy_accept(ctypes.byref(st.c), _ptr(target_token), _ptr(scan_status), _ptr(path),
+                                              _ptr(accept_len), _ptr(bonus_token), _stream(stream)))
+
+
+def talon_compact_kv(k_tree, v_tree, path, accept_len, prefix_len, new_prefix_len, k_prefix, v_prefix, stream=None):
+    """k_tree/v_tree [B][N_pad][Hkv][Dh] bf16 dense; k_prefix/v_prefix [B][capacity][Hkv][Dh] views sharing
+    strides, Dh contiguous."""
+    B, N_pad, Hkv, Dh = k_tree.shape
+    if k_prefix.stride() != v_prefix.stride() or k_prefix.stride(3) != 1:
+        raise TalonError(TALON_ERR_INVALID_ARG, "k_prefix and v_prefix must share strides, Dh contiguous")
+    _check(load_library().talon_compact_kv(
+        _ptr(k_tree), _ptr(v_tree), _ptr(path), _ptr(accept_len), _ptr(prefix_len), _ptr(new_prefix_len),
+        _ptr(k_prefix), _ptr(v_prefix), B, N_pad, Hkv, Dh, k_prefix.shape[1], k_prefix.stride(0), k_prefix.stride(1),
+        k_prefix.stride(2), _stream(stream)))

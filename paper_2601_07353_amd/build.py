@@ -13,7 +13,7 @@ LIB_DIR = os.path.join(PKG, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libtalon.so")
 OBJ_DIR = os.path.join(PKG, "_build")
 
-SOURCES = ["api.hip", "expand.hip", "select.hip", "attention.hip", "calibrate.hip"]
+SOURCES = ["api.hip", "expand.hip", "select.hip", "attention.hip", "accept.hip", "calibrate.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -47,7 +47,7 @@ def build(verbose: bool = False) -> str:
     def compile_one(i):
         return _run([hipcc, *FLAGS, "-c", os.path.join(CSRC, SOURCES[i]), "-o", objs[i]])
 
-    with ThreadPoolExecutor(max_workers=5) as ex:
+    with ThreadPoolExecutor(max_workers=6) as ex:
         for out in ex.map(compile_one, range(len(SOURCES))):
             if verbose and out.strip():
                 print(out)

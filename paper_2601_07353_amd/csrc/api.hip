@@ -171,6 +171,30 @@ int expand_grid(const talon_tree_state* st, int chunks, int layer, int k, int K_
   return static_cast<int>(items);
 }
 
+// Workspace of talon_target_argmax: the scan's workspace for k = 1, then the stand-in frontier
+// {begin, count, status}[B] and the scan outputs nobody asked for.
+struct VerifyLayout {
+  ExpandLayout scan;
+  size_t off_begin, off_count, off_status, off_logit, off_prob, off_edge, off_max, off_lse, total;
+};
+
+int verify_layout(int B, int N_pad, int vocab, int dtype, VerifyLayout* V) {
+  int rc = expand_layout(B, N_pad, vocab, 1, dtype, &V->scan);
+  if (rc) return rc;
+  const size_t rows = static_cast<size_t>(B) * N_pad;
+  size_t o = V->scan.total;
+  V->off_begin = o;  o += align_up(B * sizeof(int32_t), 256);
+  V->off_count = o;  o += align_up(B * sizeof(int32_t), 256);
+  V->off_status = o; o += align_up(B * sizeof(uint32_t), 256);
+  V->off_logit = o;  o += align_up(rows * sizeof(float), 256);
+  V->off_prob = o;   o += align_up(rows * sizeof(float), 256);
+  V->off_edge = o;   o += align_up(rows * sizeof(double), 256);
+  V->off_max = o;    o += align_up(rows * sizeof(float), 256);
+  V->off_lse = o;    o += align_up(rows * sizeof(double), 256);
+  V->total = o;
+  return TALON_OK;
+}
+
 }  // namespace
 }  // namespace talon
 
@@ -362,6 +386,85 @@ int talon_profile_read(float* durations_us, int32_t capacity, int32_t* n_launche
   }
   g_profile.used = 0;
   return TALON_OK;
+}
+
+size_t talon_verify_workspace_bytes(int32_t B, int32_t N_pad, int32_t vocab, int dtype) {
+  VerifyLayout V;
+  if (verify_layout(B, N_pad, vocab, dtype, &V)) return 0;
+  return V.total;
+}
+
+int talon_target_argmax(const void* logits, int dtype, int64_t row_stride, int64_t seq_stride,
+                        const talon_tree_state* st, int32_t vocab, int32_t* target_token, float* target_prob,
+                        uint32_t* scan_status, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_state(st);
+  if (rc) return rc;
+  VerifyLayout V;
+  rc = verify_layout(st->B, st->N_pad, vocab, dtype, &V);
+  if (rc) return rc;
+  if (!scan_status) { set_error("scan_status is NULL"); return TALON_ERR_INVALID_ARG; }
+  char* w = static_cast<char*>(workspace);
+  ExpandLayout L;
+  // the scan's own checks (pointers, alignment, strides), with the unused outputs in the workspace
+  float* prob = target_prob ? target_prob : (w ? reinterpret_cast<float*>(w + V.off_prob) : nullptr);
+  rc = check_expand_args(logits, dtype, row_stride, seq_stride, TALON_ROWS_BY_NODE, st, vocab, 1, target_token,
+                         w ? w + V.off_logit : nullptr, prob, w ? w + V.off_edge : nullptr, w ? w + V.off_max : nullptr,
+                         w ? w + V.off_lse : nullptr, workspace, workspace_bytes, &L);
+  if (rc) return rc;
+  if (workspace_bytes < V.total) {
+    set_error("workspace of %zu bytes is smaller than the %zu needed", workspace_bytes, V.total);
+    return TALON_ERR_WORKSPACE;
+  }
+  ExpandArgs a = make_expand_args(logits, row_stride, seq_stride, TALON_ROWS_BY_NODE, st, vocab, 1, target_token,
+                                  reinterpret_cast<float*>(w + V.off_logit), prob,
+                                  reinterpret_cast<double*>(w + V.off_edge), reinterpret_cast<float*>(w + V.off_max),
+                                  reinterpret_cast<double*>(w + V.off_lse), workspace, L);
+  int32_t* begin = reinterpret_cast<int32_t*>(w + V.off_begin);
+  int32_t* count = reinterpret_cast<int32_t*>(w + V.off_count);
+  a.frontier_begin = begin; a.frontier_count = count; a.status = scan_status;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  rc = check_hip(launch_all_nodes_frontier(*st, begin, count, scan_status, a.ticket, s), "frontier launch");
+  if (rc) return rc;
+  // every node of every tree is a row: N rows per sequence at most
+  long long items = static_cast<long long>(st->B) * st->N * L.chunks;
+  const int grid = static_cast<int>(items > 1024 ? 1024 : (items < 1 ? 1 : items));
+  return check_hip(launch_expand(a, dtype, grid, false, s), "target scan launch");
+}
+
+int talon_greedy_accept(const talon_tree_state* st, const int32_t* target_token, const uint32_t* scan_status,
+                        int32_t* path, int32_t* accept_len, int32_t* bonus_token, void* stream) {
+  int rc = check_state(st);
+  if (rc) return rc;
+  if (!target_token || !scan_status || !path || !accept_len || !bonus_token) {
+    set_error("talon_greedy_accept: NULL pointer argument");
+    return TALON_ERR_INVALID_ARG;
+  }
+  return check_hip(launch_accept(*st, target_token, scan_status, path, accept_len, bonus_token,
+                                 static_cast<hipStream_t>(stream)), "accept launch");
+}
+
+int talon_compact_kv(const void* k_tree, const void* v_tree, const int32_t* path, const int32_t* accept_len,
+                     const int32_t* prefix_len, int32_t* new_prefix_len, void* k_prefix, void* v_prefix, int32_t B,
+                     int32_t N_pad, int32_t Hkv, int32_t Dh, int32_t prefix_capacity, int64_t kv_stride_b,
+                     int64_t kv_stride_t, int64_t kv_stride_h, void* stream) {
+  const void* ptrs[] = {k_tree, v_tree, path, accept_len, prefix_len, new_prefix_len, k_prefix, v_prefix};
+  for (const void* p : ptrs)
+    if (!p) { set_error("talon_compact_kv: NULL pointer argument"); return TALON_ERR_INVALID_ARG; }
+  if (!aligned16(k_tree) || !aligned16(v_tree) || !aligned16(k_prefix) || !aligned16(v_prefix)) {
+    set_error("talon_compact_kv: K/V pointers must be 16-byte aligned");
+    return TALON_ERR_INVALID_ARG;
+  }
+  if (B < 1 || B > TALON_B_MAX || N_pad < 64 || N_pad > TALON_N_MAX || N_pad % 64) { set_error("bad B=%d or N_pad=%d", B, N_pad); return TALON_ERR_INVALID_ARG; }
+  if (Hkv < 1 || Dh < 8 || Dh % 8) { set_error("Hkv=%d, Dh=%d: Dh must be a positive multiple of 8", Hkv, Dh); return TALON_ERR_INVALID_ARG; }
+  if (prefix_capacity < 1) { set_error("prefix_capacity=%d must be >= 1", prefix_capacity); return TALON_ERR_INVALID_ARG; }
+  if (kv_stride_t % 8 || kv_stride_h % 8 || kv_stride_b % 8 || kv_stride_h < Dh) {
+    set_error("talon_compact_kv: KV strides must be multiples of 8 elements with a contiguous Dh run");
+    return TALON_ERR_INVALID_ARG;
+  }
+  return check_hip(launch_compact_kv(static_cast<const uint16_t*>(k_tree), static_cast<const uint16_t*>(v_tree), path,
+                                     accept_len, prefix_len, new_prefix_len, static_cast<uint16_t*>(k_prefix),
+                                     static_cast<uint16_t*>(v_prefix), B, N_pad, Hkv, Dh, prefix_capacity, kv_stride_b,
+                                     kv_stride_t, kv_stride_h, static_cast<hipStream_t>(stream)), "compact launch");
 }
 
 int talon_probe_read(const void* buf, size_t bytes, void* sink, void* stream) {

@@ -47,6 +47,12 @@ __device__ __forceinline__ int wave_sum_i32(int v) {
   return v;
 }
 
+__device__ __forceinline__ int combine_max_i32(int a, int b) { return a > b ? a : b; }
+__device__ __forceinline__ int wave_max_i32(int v) {
+  TALON_WAVE_ALLREDUCE_32(v, combine_max_i32);
+  return v;
+}
+
 // 64-bit all-reduces move the two halves separately.
 #define TALON_WAVE_ALLREDUCE_64(T, x, COMBINE)                                               \
   do {                                                                                       \

@@ -95,6 +95,14 @@ struct AttnArgs {
 // launchers (each checks nothing: arguments were validated by the ABI layer)
 hipError_t launch_tree_init(const talon_tree_state& st, const int32_t* root_token, hipStream_t s);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+hipError_t launch_all_nodes_frontier(const talon_tree_state& st, int32_t* begin, int32_t* count, uint32_t* status,
+                                     int32_t* ticket, hipStream_t s);
+hipError_t launch_accept(const talon_tree_state& st, const int32_t* target_token, const uint32_t* scan_status,
+                         int32_t* path, int32_t* accept_len, int32_t* bonus_token, hipStream_t s);
+hipError_t launch_compact_kv(const uint16_t* k_tree, const uint16_t* v_tree, const int32_t* path, const int32_t* accept_len,
+                             const int32_t* prefix_len, int32_t* new_prefix_len, uint16_t* k_prefix, uint16_t* v_prefix,
+                             int B, int N_pad, int Hkv, int Dh, int capacity, int64_t sb, int64_t st_, int64_t sh,
+                             hipStream_t s);
 hipError_t launch_read_probe(const void* buf, size_t bytes, void* sink, hipStream_t s);
 hipError_t launch_mfma_probe(int workgroups, int iters, void* sink, hipStream_t s);
 hipError_t launch_fused_init(const talon_tree_state& st, const ExpandArgs& a, hipStream_t s);

@@ -243,3 +243,70 @@ def compare_step(cfg: WorkloadConfig, gpu: dict, ref: dict, check_rows=True):
     if "attn_out" in gpu and ref["attn_out"]:
         return compare_attention(cfg, gpu, ref)
     return None
+
+
+# --------------------------------------------------------------------------- greedy verification
+def run_gpu_verify(cfg: WorkloadConfig, st, target_pool: np.ndarray, attn, capacity=None):
+    """Target argmax over every tree node, acceptance walk, cache compaction, through the C ABI.
+    `st`: the device tree state after expansion; `attn`: per-sequence attention inputs (their
+    prefix and tree K/V are the cache and the tree's keys/values)."""
+    import torch
+    import paper_2601_07353_amd as T
+    dev = to_device_logits(target_pool)
+    dt = T.TALON_DTYPE_F32 if cfg.logits_dtype == "f32" else T.TALON_DTYPE_BF16
+    ws = T.make_verify_workspace(cfg.B, st.N_pad, cfg.V, dt)
+    tgt = torch.full((cfg.B, st.N_pad), -7, dtype=torch.int32, device="cuda")
+    prob = torch.zeros(cfg.B, st.N_pad, dtype=torch.float32, device="cuda")
+    sstat = torch.zeros(cfg.B, dtype=torch.int32, device="cuda")
+    path = torch.full((cfg.B, st.N_pad), -9, dtype=torch.int32, device="cuda")
+    alen = torch.full((cfg.B,), -9, dtype=torch.int32, device="cuda")
+    bonus = torch.full((cfg.B,), -9, dtype=torch.int32, device="cuda")
+    T.talon_target_argmax(dev, st, tgt, prob, sstat, ws)
+    T.talon_greedy_accept(st, tgt, sstat, path, alen, bonus)
+    capacity = cfg.L + st.N_pad if capacity is None else capacity
+    kp = np.zeros((cfg.B, capacity, cfg.Hkv, cfg.Dh), dtype=np.uint16)
+    vp = np.zeros_like(kp)
+    keep = min(cfg.L, capacity)
+    for b in range(cfg.B):
+        kp[b, :keep] = attn[b]["k_prefix"][:keep]
+        vp[b, :keep] = attn[b]["v_prefix"][:keep]
+    kp_d, vp_d = bf16_to_device(kp), bf16_to_device(vp)
+    kt_d = bf16_to_device(np.stack([x["k_tree"] for x in attn]))
+    vt_d = bf16_to_device(np.stack([x["v_tree"] for x in attn]))
+    plen = torch.full((cfg.B,), keep, dtype=torch.int32, device="cuda")
+    new_plen = torch.full((cfg.B,), -9, dtype=torch.int32, device="cuda")
+    T.talon_compact_kv(kt_d, vt_d, path, alen, plen, new_plen, kp_d, vp_d)
+    torch.cuda.synchronize()
+    return {"target_token": tgt.cpu().numpy(), "target_prob": prob.cpu().numpy(), "scan_status": sstat.cpu().numpy(),
+            "path": path.cpu().numpy(), "accept_len": alen.cpu().numpy(), "bonus": bonus.cpu().numpy(),
+            "new_prefix_len": new_plen.cpu().numpy(), "prefix_len": keep,
+            "k_cache": kp_d.view(torch.int16).cpu().numpy().view(np.uint16),
+            "v_cache": vp_d.view(torch.int16).cpu().numpy().view(np.uint16),
+            "k_cache_before": kp, "v_cache_before": vp}
+
+
+def compare_verify(cfg: WorkloadConfig, gpu: dict, b: int, token, parent, target_rows_f64, attn_b):
+    """One sequence of run_gpu_verify against the oracle's greedy verification."""
+    from oracle import talon_oracle as O
+    n = len(token)
+    want_tok = [O.target_argmax(target_rows_f64[i]) for i in range(n)]
+    np.testing.assert_array_equal(gpu["target_token"][b, :n], np.asarray(want_tok, dtype=np.int32))
+    assert np.all(gpu["target_token"][b, n:] == -7)                      # rows beyond the tree untouched
+    for i in range(n):
+        _, lse = O.softmax_stats(target_rows_f64[i])
+        want_p = math.exp(target_rows_f64[i][want_tok[i]] - lse)
+        assert abs(float(gpu["target_prob"][b, i]) - want_p) <= PROB_RTOL * want_p + 1e-30, (b, i)
+    path, bonus = O.greedy_accept(list(token), list(parent), want_tok)
+    assert int(gpu["accept_len"][b]) == len(path) - 1
+    np.testing.assert_array_equal(gpu["path"][b, :len(path)], np.asarray(path, dtype=np.int32))
+    assert np.all(gpu["path"][b, len(path):] == -1)
+    assert int(gpu["bonus"][b]) == bonus
+    L = gpu["prefix_len"]
+    cap = gpu["k_cache"].shape[1]
+    for name, tree in (("k_cache", attn_b["k_tree"]), ("v_cache", attn_b["v_tree"])):
+        want = gpu[name + "_before"][b].copy()
+        fit = [p for j, p in enumerate(path) if L + j < cap]
+        new_len = O.compact_kv(want, tree, fit, L)
+        np.testing.assert_array_equal(gpu[name][b], want)                 # bit-exact, untouched elsewhere
+    assert int(gpu["new_prefix_len"][b]) == new_len == min(L + len(path), cap)
+    return len(path) - 1
