@@ -43,6 +43,9 @@ def parse_args():
     ap.add_argument("--attainable", action="store_true",
                     help="only run the library's two probes: a streaming read of 1 GiB and 512 MiB buffers (cold) "
                          "and a register-resident bf16 MFMA loop; prints the rates they reach")
+    ap.add_argument("--accept", action="store_true",
+                    help="also time the greedy verification outcome that follows a step (target argmax over every "
+                         "tree node, acceptance walk, accepted-path KV compaction) on synthetic target logits")
     ap.add_argument("--layerwise", action="store_true",
                     help="also time the expansion layer by layer (one fused scan+selection launch per layer, "
                          "talon_expand_select_layer) and report rows, duration and read bandwidth of each layer")
@@ -231,12 +234,63 @@ def main():
         "kernels": kernels,
     }
 
+    if args.accept:
+        result["accept"] = accept_outcome(T, torch, np, cfg, slots, st, args.steps, elem)
+
     if args.layerwise:
         result["layers"] = layerwise(T, torch, np, cfg, slots, st, cand, ws_expand, roots, args.steps, elem)
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, args.cpu_seconds, H)
     print(json.dumps(result))
+
+
+def accept_outcome(T, torch, np, cfg, slots, st, steps, elem):
+    """The calls that follow a step at temperature 0, timed as one HIP graph per replay on the
+    tree the last step left in `st`: talon_target_argmax (one vocabulary scan with k = 1 over
+    every tree node: n * V * sizeof(dtype) bytes per sequence, HBM-bound), talon_greedy_accept,
+    talon_compact_kv.  Target logits: random rows of the draft pools of other slots (any row
+    serves: the scan's cost does not depend on the values)."""
+    dt = T.TALON_DTYPE_F32 if cfg.logits_dtype == "f32" else T.TALON_DTYPE_BF16
+    ws = T.make_verify_workspace(cfg.B, st.N_pad, cfg.V, dt)
+    dev = "cuda"
+    tgt = torch.zeros(cfg.B, st.N_pad, dtype=torch.int32, device=dev)
+    prob = torch.zeros(cfg.B, st.N_pad, dtype=torch.float32, device=dev)
+    sstat = torch.zeros(cfg.B, dtype=torch.int32, device=dev)
+    path = torch.zeros(cfg.B, st.N_pad, dtype=torch.int32, device=dev)
+    alen = torch.zeros(cfg.B, dtype=torch.int32, device=dev)
+    bonus = torch.zeros(cfg.B, dtype=torch.int32, device=dev)
+    cap = cfg.L + st.N_pad
+    kp = torch.zeros(cfg.B, cap, cfg.Hkv, cfg.Dh, dtype=torch.bfloat16, device=dev)
+    vp = torch.zeros_like(kp)
+    plen = torch.full((cfg.B,), cfg.L, dtype=torch.int32, device=dev)
+    new_plen = torch.zeros(cfg.B, dtype=torch.int32, device=dev)
+
+    def outcome(s):
+        T.talon_target_argmax(s.logits, st, tgt, prob, sstat, ws)
+        T.talon_greedy_accept(st, tgt, sstat, path, alen, bonus)
+        T.talon_compact_kv(s.kt, s.vt, path, alen, plen, new_plen, kp, vp)
+
+    graphs = []
+    for s in slots:
+        outcome(s)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            outcome(s)
+        graphs.append(g)
+    for g in graphs:
+        g.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        graphs[i % len(graphs)].replay()
+    torch.cuda.synchronize()
+    us = (time.perf_counter() - t0) * 1e6 / steps
+    rows = float(st.n_nodes.sum().item())
+    by = rows * cfg.V * elem
+    return {"us_per_call": us, "target_rows": rows, "bytes": by, "GBps": by / (us * 1e-6) / 1e9,
+            "accepted_mean": float(alen.float().mean().item())}
 
 
 def attainable(T, torch):

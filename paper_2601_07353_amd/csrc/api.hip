@@ -117,8 +117,8 @@ int expand_target_items() {
   static int v = 0;
   if (v == 0) {
     const char* e = getenv("TALON_EXPAND_TARGET_ITEMS");
-    v = e ? atoi(e) : 2048;
-    if (v < 1) v = 2048;
+    v = e ? atoi(e) : 512;
+    if (v < 1) v = 512;
   }
   return v;
 }
