@@ -119,16 +119,14 @@ def main():
     nb = T.talon_tree_attention_workspace_bytes(cfg.B, st.N_pad, cfg.Hq, cfg.Hkv, cfg.Dh, cfg.L)
     ws_attn = torch.empty(max(nb, 256), dtype=torch.uint8, device=dev)
 
-    def expand(s):
-        T.talon_tree_init(st, roots)
-        T.talon_expand_tree(s.logits, st, cfg.K, cfg.mu, cfg.K, 1, cfg.Dmax, cand, ws_expand)
+    def expand(s):   # tree init, the whole loop of Alg. 2 and the ancestor mask: two launches
+        T.talon_build_tree(roots, s.logits, st, cfg.K, cfg.mu, cfg.K, 1, cfg.Dmax, cand, ws_expand, mask=mask)
 
     def attention(s):
         T.talon_tree_attention(s.q, s.kp, s.vp, s.kt, s.vt, mask, st.n_nodes, plen, cfg.L, out, None, ws_attn)
 
     def step(s):
         expand(s)
-        T.talon_build_tree_mask(st, mask)
         attention(s)
 
     # ---- warmup (also records the per-slot work: rows scanned, attention FLOPs)
@@ -174,7 +172,7 @@ def main():
 
     # ---- kernel timing region: the same K steps launched eagerly, with HIP events (on the
     # launch stream) around the expansion launch (one per step: the kernel walks all layers;
-    # recorded by the library's measurement hook inside talon_expand_tree) and around the
+    # recorded by the library's measurement hook inside talon_build_tree) and around the
     # tree-attention call.
     layers = 1
     ev_attn = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
@@ -182,7 +180,6 @@ def main():
     for i in range(args.steps):
         s = slots[i % n_slots]
         expand(s)
-        T.talon_build_tree_mask(st, mask)
         e0, e1 = ev_attn[i]
         e0.record(); attention(s); e1.record()
     torch.cuda.synchronize()

@@ -166,6 +166,20 @@ int talon_expand_tree(const void* logits, int dtype, int64_t row_stride, int64_t
                       void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Alg. 2 from its first line to its last, and the tree's attention mask, in two launches:
+ * T = {x_t} as talon_tree_init sets it (root_token: device, [B]), the whole loop as
+ * talon_expand_tree runs it, and, if `mask` is not NULL, the ancestor mask of
+ * talon_build_tree_mask written by the same launch once every sequence is complete.
+ * Same results as the three calls in a row; arguments and errors as theirs.
+ */
+int talon_build_tree(const int32_t* root_token, const void* logits, int dtype, int64_t row_stride,
+                     int64_t seq_stride, int row_mode, const talon_tree_state* st, int32_t vocab,
+                     int32_t k, float mu, int32_t K_init, int32_t init_layers, int32_t max_depth,
+                     int32_t* cand_token, float* cand_logit, float* cand_prob,
+                     double* cand_edge_logp, float* row_max, double* row_lse, uint64_t* mask,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Measurement hook (no counterpart in the paper).  While enabled, talon_expand_tree and
  * talon_expand_select_layer record a HIP event on the launch stream before and after every
  * fused scan launch; talon_profile_read waits for them, writes the first `capacity`

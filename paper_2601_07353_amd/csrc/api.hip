@@ -142,6 +142,7 @@ ExpandArgs make_expand_args(const void* logits, int64_t row_stride, int64_t seq_
   a.launch_idx = 0;
   a.layers = 0;
   a.spin_ticks = 0;
+  a.tree_mask = nullptr;
   memset(&a.sel, 0, sizeof(a.sel));
   a.part_max = reinterpret_cast<float*>(w + L.off_max);
   a.part_sum = reinterpret_cast<double*>(w + L.off_sum);
@@ -284,7 +285,7 @@ unsigned long long spin_limit_ticks() {
   return static_cast<unsigned long long>(us < 0 ? 0 : us) * 100ull;
 }
 
-int run_fused_layers(bool single_launch, const void* logits, int dtype, int64_t row_stride, int64_t seq_stride, int row_mode,
+int run_fused_layers(bool single_launch, const int32_t* root_token, uint64_t* mask, const void* logits, int dtype, int64_t row_stride, int64_t seq_stride, int row_mode,
                      int first_layer, int layers, const talon_tree_state* st, int32_t vocab, int32_t k, float mu,
                      int32_t K_init, int32_t init_layers, int32_t max_depth, int32_t* cand_token, float* cand_logit,
                      float* cand_prob, double* cand_edge_logp, float* row_max, double* row_lse, void* workspace,
@@ -302,8 +303,12 @@ int run_fused_layers(bool single_launch, const void* logits, int dtype, int64_t 
   sa.log_mu = log(static_cast<double>(mu)); sa.K_init = K_init; sa.init_layers = init_layers; sa.max_depth = max_depth;
   ea.sel = sa;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (layers <= 0) return TALON_OK;
-  rc = check_hip(launch_fused_init(*st, ea, s), "fused init launch");
+  if (layers <= 0) {   // N = 1: the tree is its root
+    if (root_token && (rc = check_hip(launch_tree_init(*st, root_token, s), "tree_init launch"))) return rc;
+    if (mask) return check_hip(launch_mask(*st, mask, s), "mask launch");
+    return TALON_OK;
+  }
+  rc = check_hip(launch_fused_init(*st, root_token, ea, s), "fused init launch");
   if (rc) return rc;
   if (!single_launch) {
     for (int d = 0; d < layers; ++d) {
@@ -328,6 +333,7 @@ int run_fused_layers(bool single_launch, const void* logits, int dtype, int64_t 
   grid = grid < resident ? grid : resident;
   ea.layers = layers;
   ea.spin_ticks = spin_limit_ticks();
+  ea.tree_mask = mask;
   if (g_profile.enabled && (rc = check_hip(profile_record(s), "profile event"))) return rc;
   rc = check_hip(launch_expand_tree(ea, dtype, grid, s), "expand tree launch");
   if (rc) return rc;
@@ -342,7 +348,7 @@ int talon_expand_select_layer(const void* logits, int dtype, int64_t row_stride,
                               int32_t K_init, int32_t init_layers, int32_t max_depth, int32_t* cand_token,
                               float* cand_logit, float* cand_prob, double* cand_edge_logp, float* row_max,
                               double* row_lse, void* workspace, size_t workspace_bytes, void* stream) {
-  return run_fused_layers(false, logits, dtype, row_stride, seq_stride, row_mode, layer, 1, st, vocab, k, mu, K_init,
+  return run_fused_layers(false, nullptr, nullptr, logits, dtype, row_stride, seq_stride, row_mode, layer, 1, st, vocab, k, mu, K_init,
                           init_layers, max_depth, cand_token, cand_logit, cand_prob, cand_edge_logp, row_max,
                           row_lse, workspace, workspace_bytes, stream);
 }
@@ -357,9 +363,23 @@ int talon_expand_tree(const void* logits, int dtype, int64_t row_stride, int64_t
   // and the grid moves on to the next layer when every selection of a layer is done.
   int layers = 0;
   if (st && max_depth > 0) layers = max_depth < st->N - 1 ? max_depth : (st->N > 1 ? st->N - 1 : 0);
-  return run_fused_layers(true, logits, dtype, row_stride, seq_stride, row_mode, 0, layers, st, vocab, k, mu, K_init,
+  return run_fused_layers(true, nullptr, nullptr, logits, dtype, row_stride, seq_stride, row_mode, 0, layers, st, vocab, k, mu, K_init,
                           init_layers, max_depth, cand_token, cand_logit, cand_prob, cand_edge_logp, row_max,
                           row_lse, workspace, workspace_bytes, stream);
+}
+
+int talon_build_tree(const int32_t* root_token, const void* logits, int dtype, int64_t row_stride, int64_t seq_stride,
+                     int row_mode, const talon_tree_state* st, int32_t vocab, int32_t k, float mu, int32_t K_init,
+                     int32_t init_layers, int32_t max_depth, int32_t* cand_token, float* cand_logit, float* cand_prob,
+                     double* cand_edge_logp, float* row_max, double* row_lse, uint64_t* mask, void* workspace,
+                     size_t workspace_bytes, void* stream) {
+  if (!root_token) { set_error("root_token is NULL"); return TALON_ERR_INVALID_ARG; }
+  if (mask && (reinterpret_cast<uintptr_t>(mask) & 7u)) { set_error("mask is not 8-byte aligned"); return TALON_ERR_INVALID_ARG; }
+  int layers = 0;
+  if (st && max_depth > 0) layers = max_depth < st->N - 1 ? max_depth : (st->N > 1 ? st->N - 1 : 0);
+  return run_fused_layers(true, root_token, mask, logits, dtype, row_stride, seq_stride, row_mode, 0, layers, st, vocab,
+                          k, mu, K_init, init_layers, max_depth, cand_token, cand_logit, cand_prob, cand_edge_logp,
+                          row_max, row_lse, workspace, workspace_bytes, stream);
 }
 
 int talon_profile_scan_launches(int enable) {

@@ -714,7 +714,8 @@ __global__ __launch_bounds__(kThreads, 3) void expand_tree_kernel(ExpandArgs a) 
   __shared__ int s_go;
   for (int d = 0; d < a.layers; ++d) {
     const int rows = expand_body<EPL, kModeTree>(a, d);
-    if (rows == 0 || d + 1 == a.layers) return;   // uniform over the grid: every workgroup reads the same descriptors
+    if (rows == 0) break;   // uniform over the grid: every workgroup reads the same descriptors
+    if (d + 1 == a.layers && !a.tree_mask) return;
     if (threadIdx.x == 0) {
       const unsigned long long t0 = wall_clock64();
       int go = 1;
@@ -730,6 +731,38 @@ __global__ __launch_bounds__(kThreads, 3) void expand_tree_kernel(ExpandArgs a) 
       return;
     }
     __syncthreads();   // s_go is rewritten in the next round
+  }
+  // ---- ancestor masks (Fig. 5(b), App. B): every selection of every layer is published by
+  // now.  Bit j of row i is set iff j is i or an ancestor of i; one thread per node walks its
+  // parent chain in LDS.
+  if (!a.tree_mask) return;
+  __shared__ int s_par[TALON_N_MAX];
+  const talon_tree_state& st = a.sel.st;
+  const int words = st.N_pad / 64;
+  for (int b = blockIdx.x; b < a.B; b += gridDim.x) {
+    const int tid = threadIdx.x;
+    const int n = load_agent(st.n_nodes + b);
+    const size_t base = static_cast<size_t>(b) * st.N_pad;
+    __syncthreads();
+    if (tid < st.N_pad) s_par[tid] = tid < n ? load_agent(st.parent + base + tid) : -1;
+    __syncthreads();
+    if (tid < st.N_pad) {
+      uint64_t w[4] = {0, 0, 0, 0};
+      if (tid < n) {
+        int j = tid;
+        for (int step = 0; step < TALON_N_MAX && j >= 0; ++step) {
+          const uint64_t bit = 1ull << (j & 63);
+          const int q = j >> 6;
+#pragma unroll
+          for (int u = 0; u < 4; ++u) w[u] |= q == u ? bit : 0ull;
+          j = s_par[j];
+        }
+      }
+      uint64_t* row = a.tree_mask + (base + tid) * words;
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (u < words) row[u] = w[u];
+    }
   }
 }
 
@@ -761,22 +794,39 @@ int expand_chunk_elems(int dtype) { return dtype == TALON_DTYPE_F32 ? kChunkByte
 
 // Start of a fused call: frontier descriptors of its first layer from the public tree state,
 // zero layer counters, and zero tickets (a launch that gave up may have left some taken).
-__global__ void fused_init_kernel(talon_tree_state st, int32_t* desc, uint32_t* layer_done, int32_t* ticket,
-                                  int32_t* seq_ticket) {
+__global__ void fused_init_kernel(talon_tree_state st, const int32_t* root_token, int32_t* desc, uint32_t* layer_done,
+                                  int32_t* ticket, int32_t* seq_ticket) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < st.B * st.N_pad) ticket[i] = 0;
   if (i < st.N_pad) layer_done[i] = 0u;
   if (i >= st.B) return;
   seq_ticket[i] = 0;
+  if (root_token) {   // start from T = {x_t} (Alg. 2 line 1), as talon_tree_init does
+    const size_t o = static_cast<size_t>(i) * st.N_pad;
+    st.token[o] = root_token[i];
+    st.parent[o] = -1;
+    st.depth[o] = 0;
+    st.prob[o] = 1.f;
+    st.logp[o] = 0.0;
+    st.n_nodes[i] = 1;
+    st.frontier_begin[i] = 0;
+    st.frontier_count[i] = 1;
+    st.depth_cur[i] = 0;
+    const uint32_t s0 = st.N <= 1 ? TALON_STATUS_DONE_BUDGET : 0u;
+    st.status[i] = s0;
+    desc[2 * i] = 0;
+    desc[2 * i + 1] = s0 ? 0 : 1;
+    return;
+  }
   desc[2 * i] = st.frontier_begin[i];
   desc[2 * i + 1] = (st.status[i] & kDoneMask) ? 0 : st.frontier_count[i];
 }
 
-hipError_t launch_fused_init(const talon_tree_state& st, const ExpandArgs& a, hipStream_t s) {
+hipError_t launch_fused_init(const talon_tree_state& st, const int32_t* root_token, const ExpandArgs& a, hipStream_t s) {
   static_assert(TALON_B_MAX <= 256 && TALON_N_MAX <= 256, "the first workgroup covers the per-sequence and per-layer arrays");
   const int n = st.B * st.N_pad;
-  hipLaunchKernelGGL(fused_init_kernel, dim3((n + 255) / 256), dim3(256), 0, s, st, a.desc, a.layer_done, a.ticket,
-                     a.seq_ticket);
+  hipLaunchKernelGGL(fused_init_kernel, dim3((n + 255) / 256), dim3(256), 0, s, st, root_token, a.desc, a.layer_done,
+                     a.ticket, a.seq_ticket);
   return hipGetLastError();
 }
 

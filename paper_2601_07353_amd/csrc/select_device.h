@@ -214,7 +214,7 @@ __device__ __forceinline__ void select_sequence(const SelectArgs& a, int b, int 
       const size_t ci = (base + fb + p) * k + (c - p * k);
       const size_t o = base + n + pos;
       st.token[o] = ld<AGENT, int32_t>(a.cand_token + ci);
-      st.parent[o] = fb + p;
+      st_<AGENT, int32_t>(st.parent + o, fb + p);   // read again by the in-launch mask build
       st.depth[o] = d + 1;
       st.prob[o] = ld<AGENT, float>(a.cand_prob + ci);
       st_<AGENT, double>(st.logp + o, ld<AGENT, double>(st.logp + base + fb + p) + ld<AGENT, double>(a.cand_edge_logp + ci));

@@ -117,9 +117,10 @@ def bf16_to_device(bits: np.ndarray):
 
 
 def run_gpu_expand(cfg: WorkloadConfig, pool_dev, init_layers=1, mu=None, K_init=None, layerwise=False):
-    """Whole expansion loop on the GPU.  layerwise=True (or "split") drives the two per-layer
-    entry points from the host, layerwise="fused" the one-launch-per-layer entry point, instead
-    of the single talon_expand_tree call."""
+    """Whole expansion loop on the GPU.  Default: talon_build_tree (init, loop and mask in two
+    launches; the mask is returned).  layerwise="tree": talon_tree_init + talon_expand_tree;
+    "fused": one talon_expand_select_layer per layer; True / "split": talon_expand_layer +
+    talon_select_budget per layer.  Those three return no mask."""
     import torch
     import paper_2601_07353_amd as T
     st = T.TreeState(cfg.B, cfg.N)
@@ -129,19 +130,25 @@ def run_gpu_expand(cfg: WorkloadConfig, pool_dev, init_layers=1, mu=None, K_init
     roots = torch.from_numpy(root_tokens(cfg)).cuda()
     mu = cfg.mu if mu is None else mu
     K_init = cfg.K if K_init is None else K_init
-    T.talon_tree_init(st, roots)
+    mask = None
     if layerwise == "fused":
+        T.talon_tree_init(st, roots)
         for d in range(cfg.Dmax):
             T.talon_expand_select_layer(pool_dev, st, cfg.K, mu, K_init, init_layers, cfg.Dmax, cand, ws,
                                         layer=d if d % 2 == 0 else -1)
+    elif layerwise == "tree":
+        T.talon_tree_init(st, roots)
+        T.talon_expand_tree(pool_dev, st, cfg.K, mu, K_init, init_layers, cfg.Dmax, cand, ws)
     elif layerwise:
+        T.talon_tree_init(st, roots)
         for d in range(cfg.Dmax):
             T.talon_expand_layer(pool_dev, st, cfg.K, cand, ws, layer=d if d % 2 == 0 else -1)
             T.talon_select_budget(st, cfg.K, cand, mu, K_init, init_layers, cfg.Dmax)
     else:
-        T.talon_expand_tree(pool_dev, st, cfg.K, mu, K_init, init_layers, cfg.Dmax, cand, ws)
+        mask = torch.full((cfg.B, st.N_pad, st.N_pad // 64), -1, dtype=torch.int64, device="cuda")
+        T.talon_build_tree(roots, pool_dev, st, cfg.K, mu, K_init, init_layers, cfg.Dmax, cand, ws, mask=mask)
     torch.cuda.synchronize()
-    return st, cand, ws
+    return st, cand, ws, mask
 
 
 def run_gpu_step(cfg: WorkloadConfig, seeds=None, pool=None, attn=None, with_attention=True, init_layers=1,
@@ -151,9 +158,10 @@ def run_gpu_step(cfg: WorkloadConfig, seeds=None, pool=None, attn=None, with_att
     seeds = seeds_for(cfg, seeds)
     pool = build_pool(cfg, seeds) if pool is None else pool
     pool_dev = to_device_logits(pool)
-    st, cand, _ = run_gpu_expand(cfg, pool_dev, init_layers, mu, K_init, layerwise)
-    mask = torch.zeros(cfg.B, st.N_pad, st.N_pad // 64, dtype=torch.int64, device="cuda")
-    T.talon_build_tree_mask(st, mask)
+    st, cand, _, mask = run_gpu_expand(cfg, pool_dev, init_layers, mu, K_init, layerwise)
+    if mask is None:
+        mask = torch.zeros(cfg.B, st.N_pad, st.N_pad // 64, dtype=torch.int64, device="cuda")
+        T.talon_build_tree_mask(st, mask)
     res = {
         "token": st.token.cpu().numpy(), "parent": st.parent.cpu().numpy(), "depth": st.depth.cpu().numpy(),
         "prob": st.prob.cpu().numpy(), "logp": st.logp.cpu().numpy(), "n_nodes": st.n_nodes.cpu().numpy(),

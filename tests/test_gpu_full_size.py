@@ -1,5 +1,5 @@
 """GPU parity at the full sizes of the benchmark configurations, in the launch configuration
-bench.py times (one talon_expand_tree call, mask, one talon_tree_attention call).
+bench.py times (one talon_build_tree call: init, loop and mask; one talon_tree_attention call).
 
 Where the oracle cannot finish the whole configuration in seconds, it checks a stated sample
 (some sequences in full for the expansion, sampled (node, head) pairs for attention) and the

@@ -39,7 +39,7 @@ def test_c1_tiny_step():
     assert ref["trees"][0].n == 16
 
 
-@pytest.mark.parametrize("mode", ["split", "fused"])
+@pytest.mark.parametrize("mode", ["split", "fused", "tree"])
 def test_c1_layerwise_entry_points_match_single_call(mode):
     cfg = CONFIGS["c1"]
     seeds = admissible_seeds(cfg)
@@ -76,7 +76,7 @@ def test_tree_launch_gives_up_cleanly_when_the_wait_is_cut_short(monkeypatch):
         np.testing.assert_array_equal(again[key], ref[key])
 
 
-@pytest.mark.parametrize("mode", ["split", "fused"])
+@pytest.mark.parametrize("mode", ["split", "fused", "tree"])
 def test_layerwise_entry_points_against_oracle(mode):
     """The per-layer entry points (scan and selection as two launches, or as one) on a batch
     of three sequences with different logit recipes, several chunks per row."""

@@ -19,7 +19,7 @@ def verify_case(cfg, seqs=None, capacity=None, noise=0.25):
     seeds = admissible_seeds(cfg)
     print("case", cfg.name, "seeds", seeds, flush=True)
     pool = H.build_pool(cfg, seeds)
-    st, _, _ = H.run_gpu_expand(cfg, H.to_device_logits(pool))
+    st, _, _, _ = H.run_gpu_expand(cfg, H.to_device_logits(pool))
     n = st.n_nodes.cpu().numpy()
     token, parent = st.token.cpu().numpy(), st.parent.cpu().numpy()
     seqs = range(cfg.B) if seqs is None else seqs
