@@ -460,17 +460,19 @@ __global__ __launch_bounds__(kThreads) void tree_attention_combine_kernel(AttnAr
   int ns = (T + a.tiles_per_split - 1) / a.tiles_per_split;  // splits that held at least one tile
   ns = ns < a.splits ? ns : a.splits;
   const size_t base = static_cast<size_t>(bg) * a.splits * a.rows_pad + rho;
+  // branch-free, so that the loads of all splits are in flight together
   float M = kNegInfF;
   for (int s = 0; s < ns; ++s) M = fmaxf(M, a.part_m[base + static_cast<size_t>(s) * a.rows_pad]);
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   float den = 0.f;
+#pragma unroll 4
   for (int s = 0; s < ns; ++s) {
     const size_t pr = base + static_cast<size_t>(s) * a.rows_pad;
     const float ms = a.part_m[pr];
-    if (ms == kNegInfF) continue;
-    const float w = __builtin_amdgcn_exp2f(ms - M);
-    den += w * a.part_l[pr];
+    const float ls = a.part_l[pr];
     const float4 v = *reinterpret_cast<const float4*>(a.part_o + pr * DH + 4 * c);
+    const float w = ms == kNegInfF ? 0.f : __builtin_amdgcn_exp2f(ms - M);   // an empty split stores zeros
+    den += w * ls;
     acc.x += w * v.x; acc.y += w * v.y; acc.z += w * v.z; acc.w += w * v.w;
   }
   const float inv = 1.f / den;
