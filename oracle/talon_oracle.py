@@ -25,6 +25,9 @@ What each function follows:
                        matched prefix", Sec. 2; App. B step (2), "selecting the optimal
                        valid prefix"); the token after it comes from the target
   compact_kv           the accepted tokens' keys and values join the prefix cache
+  build_static_tree    the static baseline the paper compares with (Alg. 1): every layer keeps
+                       the K best of the K x K pool, D + 1 layers, then the N best nodes overall
+  prune_top_n          Alg. 1's last step, "final pruning to budget N"
 
 Readings taken where the paper is silent (each also listed in the design notes):
   * per-row candidate cap `cap`: the pool of a parent is its `cap` best tokens.
@@ -339,3 +342,52 @@ def compact_kv(cache: np.ndarray, tree: np.ndarray, path: List[int], prefix_len:
     for j, node in enumerate(path):
         cache[prefix_len + j] = tree[node]
     return prefix_len + len(path)
+
+
+# --------------------------------------------------------------------------
+# Alg. 1: the static (EAGLE-style) tree, as a second workload for the same kernels
+# --------------------------------------------------------------------------
+@dataclass
+class PrunedTree:
+    token: List[int]
+    parent: List[int]          # re-indexed
+    depth: List[int]
+    prob: List[float]
+    logp: List[float]
+    kept: List[int]            # ids the nodes had before pruning, ascending
+    margin: float              # smallest gap between a kept and a dropped node of different parents
+
+    @property
+    def n(self) -> int:
+        return len(self.token)
+
+
+def prune_top_n(tree: Tree, N: int) -> PrunedTree:
+    """T <- Top-N(T by p(u)) (Alg. 1, last step).  Order: (path confidence descending, node
+    id ascending); a node's confidence never exceeds its parent's and the parent has the
+    smaller id, so the kept set is closed under "parent of".  Kept nodes keep their relative
+    order and are renumbered 0..N-1."""
+    n = tree.n
+    order = sorted(range(n), key=lambda i: (-tree.logp[i], i))
+    kept = sorted(order[:N])
+    dropped = order[N:]
+    margin = math.inf
+    for i in kept:
+        for j in dropped:
+            if tree.parent[i] != tree.parent[j]:
+                margin = min(margin, abs(tree.logp[i] - tree.logp[j]))
+    new_id = {old: new for new, old in enumerate(kept)}
+    return PrunedTree(token=[tree.token[i] for i in kept],
+                      parent=[-1 if tree.parent[i] < 0 else new_id[tree.parent[i]] for i in kept],
+                      depth=[tree.depth[i] for i in kept], prob=[tree.prob[i] for i in kept],
+                      logp=[tree.logp[i] for i in kept], kept=kept, margin=margin)
+
+
+def build_static_tree(row_of: Callable[[int], np.ndarray], root_token: int, D: int, K: int, N: int):
+    """Alg. 1: for d = 0..D every parent proposes its K best tokens, the K best of the pool (by
+    path confidence) become the next parents and join the tree; at the end the N best nodes
+    of the tree are kept.  Returns (the tree before pruning, the pruned tree).  row_of(i) is
+    the draft row of node i in the numbering before pruning."""
+    full = build_tree(row_of, root_token, N=1 + K * (D + 1), K=K, mu=1.0, cap=K, Dmax=D + 1,
+                      init_layers=D + 1)
+    return full, prune_top_n(full, N)

@@ -654,3 +654,114 @@ def test_compact_kv_is_a_gather_appended_to_the_cache():
     np.testing.assert_array_equal(cache[:L], before[:L])
     np.testing.assert_array_equal(cache[L:new_len], tree[np.array(path)])
     np.testing.assert_array_equal(cache[new_len:], before[new_len:])
+
+
+# ---------------------------------------------------------------- Alg. 1, the static tree
+def alg1_literal(rows_prob_of_path, D, K, N):
+    """Alg. 1 written out on paths (tuples of tokens) in the probability domain, independent of
+    the oracle's layer functions.  rows_prob_of_path(path) -> probability row after that path."""
+    tree = [((), 1.0)]                       # (path, p); the root is the empty path
+    parents = [((), 1.0)]
+    for d in range(D + 1):
+        pool = []
+        for pi, (path, p) in enumerate(parents):
+            row = rows_prob_of_path(path)
+            best = sorted(range(len(row)), key=lambda w: (-row[w], w))[:K]
+            pool += [(p * row[w], pi, r, path + (w,)) for r, w in enumerate(best)]
+        chosen = sorted(pool, key=lambda c: (-c[0], c[1], c[2]))[:K]
+        chosen = sorted(chosen, key=lambda c: (c[1], c[2]))          # node order: (parent, rank)
+        parents = [(c[3], c[0]) for c in chosen]
+        tree += parents
+    order = sorted(range(len(tree)), key=lambda i: (-tree[i][1], i))[:N]
+    return [tree[i] for i in sorted(order)]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_static_tree_vs_literal_alg1(seed):
+    rng = np.random.default_rng(600 + seed)
+    V, K, D = 5, int(rng.integers(2, 4)), int(rng.integers(1, 4))
+    N = int(rng.integers(2, 1 + K * (D + 1) + 1))
+    table = {}
+
+    def prob_row(path):
+        if path not in table:
+            p = rng.dirichlet(np.ones(V) * 0.7)
+            table[path] = p
+        return table[path]
+
+    want = alg1_literal(prob_row, D, K, N)
+    # the oracle is driven by node ids: keep the path of every node as it is created, layer by
+    # layer through the oracle's own layer functions
+    paths = {0: ()}
+
+    def row_of_lazy(i):
+        return np.log(prob_row(paths[i]))
+
+    t = O.Tree(token=[0], parent=[-1], depth=[0], prob=[1.0], logp=[0.0])
+    frontier = [0]
+    t.layers.append(range(0, 1))
+    for d in range(D + 1):
+        pool = O.expand_layer(frontier, t.logp, row_of_lazy, K)
+        sel = O.select_budget(pool, d, 10 ** 6, K, 1.0, D + 1)
+        by_node = {r.node: r for r in pool}
+        begin = t.n
+        for (v, j) in sel.kept:
+            r = by_node[v]
+            paths[t.n] = paths[v] + (int(r.token[j]),)
+            t.token.append(int(r.token[j])); t.parent.append(v); t.depth.append(t.depth[v] + 1)
+            t.prob.append(float(r.prob[j])); t.logp.append(float(r.score[j]))
+        frontier = list(range(begin, t.n))
+    pruned = O.prune_top_n(t, N)
+    got = [(paths[i], math.exp(t.logp[i])) for i in pruned.kept]
+    assert [g[0] for g in got] == [w[0] for w in want]
+    np.testing.assert_allclose([g[1] for g in got], [w[1] for w in want], rtol=1e-12)
+    # and the one-call form builds the same tree (same layer functions, same arguments)
+    full, pruned2 = O.build_static_tree(lambda i: np.log(prob_row(paths[i])), 0, D, K, N)
+    assert full.token == t.token and full.parent == t.parent
+    assert pruned2.kept == pruned.kept and pruned2.parent == pruned.parent
+
+
+def test_prune_top_n_properties_and_closed_forms():
+    rng = np.random.default_rng(61)
+    for _ in range(100):
+        n = int(rng.integers(1, 40))
+        token, parent = random_tree(rng, n, 50, fan=4)
+        logp = [0.0] * n
+        for i in range(1, n):
+            logp[i] = logp[parent[i]] - float(rng.exponential(1.0))
+        depth = [0] * n
+        for i in range(1, n):
+            depth[i] = depth[parent[i]] + 1
+        t = O.Tree(token=token, parent=parent, depth=depth, prob=[1.0] * n, logp=logp)
+        N = int(rng.integers(1, n + 1))
+        p = O.prune_top_n(t, N)
+        assert p.n == N and p.kept == sorted(p.kept) and p.kept[0] == 0
+        kept = set(p.kept)
+        assert all(parent[i] in kept for i in p.kept if i > 0)                 # closed under "parent of"
+        worst_kept = min(logp[i] for i in p.kept)
+        assert all(logp[j] <= worst_kept for j in range(n) if j not in kept)   # nothing better was dropped
+        for new, old in enumerate(p.kept):                                       # renumbering is consistent
+            assert p.token[new] == token[old] and p.depth[new] == depth[old]
+            assert (p.parent[new] == -1) if old == 0 else (p.kept[p.parent[new]] == parent[old])
+    # a chain keeps its first N nodes; equal confidences keep the lower ids
+    chain = O.Tree(token=list(range(6)), parent=[-1, 0, 1, 2, 3, 4], depth=list(range(6)), prob=[1.0] * 6,
+                   logp=[0.0, -1.0, -2.0, -3.0, -4.0, -5.0])
+    assert O.prune_top_n(chain, 4).kept == [0, 1, 2, 3]
+    star = O.Tree(token=[9, 1, 2, 3, 4], parent=[-1, 0, 0, 0, 0], depth=[0, 1, 1, 1, 1], prob=[1.0] * 5,
+                  logp=[0.0, -1.0, -1.0, -1.0, -1.0])
+    assert O.prune_top_n(star, 3).kept == [0, 1, 2]
+
+
+def test_static_tree_shape():
+    # every layer of Alg. 1 adds exactly K nodes (the pool has K*K >= K candidates)
+    rng = np.random.default_rng(62)
+    rows = {}
+
+    def row_of(i):
+        if i not in rows:
+            rows[i] = rng.normal(size=64) * 2.0
+        return rows[i]
+
+    full, pruned = O.build_static_tree(row_of, 3, D=4, K=3, N=10)
+    assert full.n == 1 + 3 * 5 and [len(r) for r in full.layers] == [1, 3, 3, 3, 3, 3]
+    assert pruned.n == 10
