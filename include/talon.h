@@ -191,6 +191,18 @@ int talon_profile_scan_launches(int enable);
 int talon_profile_read(float* durations_us, int32_t capacity, int32_t* n_launches);
 
 /*
+ * Static tree construction (Alg. 1, the baseline the paper compares with) on the same
+ * kernels: call talon_build_tree with init_layers = max_depth = D + 1, K_init = K and a tree
+ * state of N = 1 + K*(D+1) nodes (every layer keeps the K best of the K x K pool), then
+ * talon_prune_tree, Alg. 1's "final pruning to budget N": the n_keep nodes of highest path
+ * confidence are kept (ties: lower node id), compacted in place in their old order, parents
+ * re-indexed; n_nodes is updated, the frontier is emptied and DONE_BUDGET is set.
+ * kept_ids [B][N_pad] (device) receives the old id of every kept node, -1 beyond.  The mask
+ * and attention calls then work on the pruned tree.  Errors: INVALID_ARG.
+ */
+int talon_prune_tree(const talon_tree_state* st, int32_t n_keep, int32_t* kept_ids, void* stream);
+
+/*
  * Verification outcome at temperature 0 (App. B "Token-Tree Verification", step (2): the
  * longest valid prefix; Sec. 2: "accepting the longest matched prefix").  Three calls.
  *

@@ -36,7 +36,7 @@ EXPORTS = [
     "talon_last_error_string", "talon_tree_init", "talon_expand_workspace_bytes",
     "talon_expand_workspace_init", "talon_expand_layer", "talon_select_budget", "talon_expand_select_layer",
     "talon_expand_tree", "talon_build_tree", "talon_profile_scan_launches", "talon_profile_read", "talon_probe_read", "talon_probe_mfma", "talon_verify_workspace_bytes", "talon_target_argmax",
-    "talon_greedy_accept", "talon_compact_kv",
+    "talon_greedy_accept", "talon_compact_kv", "talon_prune_tree",
     "talon_build_tree_mask", "talon_tree_attention_workspace_bytes", "talon_tree_attention",
 ]
 
@@ -92,6 +92,7 @@ def load_library() -> ctypes.CDLL:
     lib.talon_greedy_accept.argtypes = [POINTER(_CTreeState), P, P, P, P, P, P]
     lib.talon_compact_kv.argtypes = [P, P, P, P, P, P, P, P, c_int32, c_int32, c_int32, c_int32, c_int32, c_int64,
                                      c_int64, c_int64, P]
+    lib.talon_prune_tree.argtypes = [POINTER(_CTreeState), c_int32, P, P]
     lib.talon_probe_read.argtypes = [P, c_size_t, P, P]
     lib.talon_probe_mfma.argtypes = [c_int32, c_int32, P, POINTER(c_double), P]
     lib.talon_build_tree_mask.argtypes = [POINTER(_CTreeState), P, P]
@@ -321,3 +322,7 @@ def talon_compact_kv(k_tree, v_tree, path, accept_len, prefix_len, new_prefix_le
         _ptr(k_tree), _ptr(v_tree), _ptr(path), _ptr(accept_len), _ptr(prefix_len), _ptr(new_prefix_len),
         _ptr(k_prefix), _ptr(v_prefix), B, N_pad, Hkv, Dh, k_prefix.shape[1], k_prefix.stride(0), k_prefix.stride(1),
         k_prefix.stride(2), _stream(stream)))
+
+
+def talon_prune_tree(st: TreeState, n_keep: int, kept_ids, stream=None):
+    _check(load_library().talon_prune_tree(ctypes.byref(st.c), n_keep, _ptr(kept_ids), _stream(stream)))

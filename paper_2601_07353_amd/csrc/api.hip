@@ -408,6 +408,14 @@ int talon_profile_read(float* durations_us, int32_t capacity, int32_t* n_launche
   return TALON_OK;
 }
 
+int talon_prune_tree(const talon_tree_state* st, int32_t n_keep, int32_t* kept_ids, void* stream) {
+  int rc = check_state(st);
+  if (rc) return rc;
+  if (n_keep < 1 || n_keep > st->N_pad) { set_error("n_keep=%d outside [1, N_pad=%d]", n_keep, st->N_pad); return TALON_ERR_INVALID_ARG; }
+  if (!kept_ids) { set_error("kept_ids is NULL"); return TALON_ERR_INVALID_ARG; }
+  return check_hip(launch_prune(*st, n_keep, kept_ids, static_cast<hipStream_t>(stream)), "prune launch");
+}
+
 size_t talon_verify_workspace_bytes(int32_t B, int32_t N_pad, int32_t vocab, int dtype) {
   VerifyLayout V;
   if (verify_layout(B, N_pad, vocab, dtype, &V)) return 0;

@@ -58,7 +58,73 @@ __global__ __launch_bounds__(kThreads) void mask_kernel(talon_tree_state st, uin
   if (words > 3) row[3] = w3;
 }
 
+// Alg. 1, last step: T <- Top-N(T by p(u)).  One workgroup per sequence, one thread per node.
+// Order: (path confidence descending, node id ascending): a key of 64 bits, the order-preserving
+// image of the fp64 log confidence with its low 8 bits replaced by 255 - id.  (Dropping 8 of
+// the 52 mantissa bits only matters for confidences closer than 2^-44 relative, far below
+// what decides anything here.)  A node's confidence never exceeds its parent's and the parent
+// has the smaller id, so the kept set is closed under "parent of".  Kept nodes keep their
+// order; arrays are compacted in place.
+__global__ __launch_bounds__(kThreads) void prune_kernel(talon_tree_state st, int n_keep, int32_t* kept_ids) {
+  static_assert(TALON_N_MAX <= kThreads && TALON_N_MAX <= 256, "one thread per node, 8-bit ids");
+  __shared__ __attribute__((aligned(16))) unsigned long long s_key[TALON_N_MAX];
+  __shared__ int s_new[TALON_N_MAX];
+  __shared__ int s_red[8];
+  const int b = blockIdx.x;
+  const int i = threadIdx.x;
+  const int n = st.n_nodes[b];
+  const size_t base = static_cast<size_t>(b) * st.N_pad;
+  int token = 0, parent = -1, depth = 0;
+  float prob = 0.f;
+  double logp = 0.0;
+  unsigned long long key = 0ull;
+  if (i < n) {
+    token = st.token[base + i]; parent = st.parent[base + i]; depth = st.depth[base + i];
+    prob = st.prob[base + i]; logp = st.logp[base + i];
+    key = (sortable_u64(logp) & ~0xFFull) | static_cast<unsigned long long>(255 - i);
+    if ((key >> 8) == 0ull) key |= 0x100ull;   // never the "no node" key
+  }
+  s_key[i] = key;
+  __syncthreads();
+  int rank = 0;
+  if (i < n) {
+    const ulonglong2* kp = reinterpret_cast<const ulonglong2*>(s_key);
+    for (int j = 0; j < TALON_N_MAX / 2; j += 8) {
+      ulonglong2 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = kp[j + u];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) rank += ((v[u].x > key) ? 1 : 0) + ((v[u].y > key) ? 1 : 0);
+    }
+  }
+  const bool keep = i < n && rank < n_keep;
+  int total;
+  const int pos = block_exclusive_scan_i32(keep ? 1 : 0, s_red, &total);
+  s_new[i] = keep ? pos : -1;
+  __syncthreads();   // every thread has read its node; the new ids are known
+  if (keep) {
+    st.token[base + pos] = token;
+    st.parent[base + pos] = parent < 0 ? -1 : s_new[parent];
+    st.depth[base + pos] = depth;
+    st.prob[base + pos] = prob;
+    st.logp[base + pos] = logp;
+    kept_ids[base + pos] = i;
+  }
+  if (i < st.N_pad && i >= total) kept_ids[base + i] = -1;
+  if (i == 0) {
+    st.n_nodes[b] = total;
+    st.frontier_begin[b] = total;
+    st.frontier_count[b] = 0;
+    st.status[b] = st.status[b] | TALON_STATUS_DONE_BUDGET;
+  }
+}
+
 }  // namespace
+
+hipError_t launch_prune(const talon_tree_state& st, int n_keep, int32_t* kept_ids, hipStream_t s) {
+  hipLaunchKernelGGL(prune_kernel, dim3(st.B), dim3(kThreads), 0, s, st, n_keep, kept_ids);
+  return hipGetLastError();
+}
 
 hipError_t launch_select(const SelectArgs& a, hipStream_t s) {
   hipLaunchKernelGGL(select_kernel, dim3(a.st.B), dim3(kThreads), 0, s, a);

@@ -96,6 +96,7 @@ struct AttnArgs {
 // launchers (each checks nothing: arguments were validated by the ABI layer)
 hipError_t launch_tree_init(const talon_tree_state& st, const int32_t* root_token, hipStream_t s);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+hipError_t launch_prune(const talon_tree_state& st, int n_keep, int32_t* kept_ids, hipStream_t s);
 hipError_t launch_all_nodes_frontier(const talon_tree_state& st, int32_t* begin, int32_t* count, uint32_t* status,
                                      int32_t* ticket, hipStream_t s);
 hipError_t launch_accept(const talon_tree_state& st, const int32_t* target_token, const uint32_t* scan_status,
