@@ -46,6 +46,10 @@ def parse_args():
     ap.add_argument("--accept", action="store_true",
                     help="also time the greedy verification outcome that follows a step (target argmax over every "
                          "tree node, acceptance walk, accepted-path KV compaction) on synthetic target logits")
+    ap.add_argument("--zipf-grid", action="store_true",
+                    help="only run the paper's tree-construction micro-benchmark shape (App. E.6): latency of one "
+                         "layer expansion over K parents with Zipf rows, exponent x vocabulary grid, 20 warm-ups and "
+                         "100 timed runs, for the adaptive gate (Alg. 2) and the static top-K of the pool (Alg. 1)")
     ap.add_argument("--layerwise", action="store_true",
                     help="also time the expansion layer by layer (one fused scan+selection launch per layer, "
                          "talon_expand_select_layer) and report rows, duration and read bandwidth of each layer")
@@ -100,6 +104,9 @@ def main():
 
     if args.attainable:
         print(json.dumps({"attainable": attainable(T, torch)}))
+        return
+    if args.zipf_grid:
+        print(json.dumps({"zipf_grid": zipf_grid(T, torch, np, H)}))
         return
 
     elem = cfg.elem_bytes
@@ -288,6 +295,50 @@ def accept_outcome(T, torch, np, cfg, slots, st, steps, elem):
     by = rows * cfg.V * elem
     return {"us_per_call": us, "target_rows": rows, "bytes": by, "GBps": by / (us * 1e-6) / 1e9,
             "accepted_mean": float(alen.float().mean().item())}
+
+
+def zipf_grid(T, torch, np, H, K=10, N=60, warm=20, runs=100):
+    """Single-layer expansion latency on Zipf rows (the shape of the paper's App. E.6
+    micro-benchmark): a tree of root + K children; the timed call expands those K parents by one
+    layer (vocabulary scan of K rows + selection, one fused launch), once with the confidence
+    gate of Alg. 2 and once with Alg. 1's top-K of the K x K pool.  HIP events around the
+    launch (the library's hook); a long streaming-read launch is queued first so that the host
+    is ahead of the device and the bracket holds device time only."""
+    from workloads import WorkloadConfig, logits_row
+    out = []
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ballast = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").random_(0, 255)
+    for V in (32000, 128256, 151936):
+        for alpha in (0.7, 1.35, 5.0):
+            cfg = WorkloadConfig(name="zipf", B=1, V=V, logits_dtype="bf16", K=K, N=N, Dmax=12, mu=0.03, Hq=8, Hkv=8,
+                                 Dh=128, L=64, recipe=("zipf", alpha, 0.0))
+            pool = np.zeros((1, cfg.N_pad, V), dtype=np.uint16)
+            for i in range(K + 1):
+                pool[0, i] = logits_row(cfg, cfg.seed, 0, i)
+            dev = H.to_device_logits(pool)
+            st = T.TreeState(1, N)
+            cand = T.Candidates(1, st.N_pad, K)
+            ws = T.make_expand_workspace(1, st.N_pad, V, K, T.TALON_DTYPE_BF16)
+            roots = torch.from_numpy(H.root_tokens(cfg)).cuda()
+            res = {"V": V, "alpha": alpha, "parents": K}
+            for label, init_layers in (("adaptive_gate_us", 1), ("static_topk_us", 2)):
+                us = []
+                for it in range(warm + runs):
+                    T.talon_probe_read(ballast, sink)
+                    T.talon_tree_init(st, roots)
+                    T.talon_expand_select_layer(dev, st, K, cfg.mu, K, init_layers, 12, cand, ws, layer=0)
+                    T.talon_profile_scan_launches(True)
+                    T.talon_expand_select_layer(dev, st, K, cfg.mu, K, init_layers, 12, cand, ws, layer=1)
+                    torch.cuda.synchronize()
+                    d, n_rec = T.talon_profile_read(1)
+                    T.talon_profile_scan_launches(False)
+                    assert n_rec == 1
+                    if it >= warm:
+                        us.append(d[0])
+                res[label] = float(np.mean(us))
+                res[label.replace("_us", "_new_nodes")] = int(st.n_nodes[0].item()) - 1 - K
+            out.append(res)
+    return out
 
 
 def attainable(T, torch):
