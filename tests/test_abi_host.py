@@ -121,6 +121,52 @@ def test_fused_calls_reject_bad_arguments(lib, fn):
     assert fused_call(lib, fn, fake_state(B=0)) == T.TALON_ERR_INVALID_ARG
 
 
+def test_build_tree_rejects_bad_arguments(lib):
+    st = fake_state()
+
+    def call(root=P, mask=P, k=4, mu=0.03, ws_bytes=1 << 30):
+        return lib.talon_build_tree(root, P, 1, 1024, 1024 * 64, 0, ctypes.byref(st), 1024, k, ctypes.c_float(mu), 4, 1,
+                                    8, P, P, P, P, P, P, mask, P, ws_bytes, None)
+
+    assert call(root=0) == T.TALON_ERR_INVALID_ARG and "root_token" in err(lib)
+    assert call(mask=P + 4) == T.TALON_ERR_INVALID_ARG
+    assert call(k=0) == T.TALON_ERR_INVALID_ARG
+    assert call(mu=0.0) == T.TALON_ERR_INVALID_ARG
+    assert call(ws_bytes=64) == T.TALON_ERR_WORKSPACE
+
+
+def test_verification_and_prune_calls_reject_bad_arguments(lib):
+    st = fake_state()
+    assert lib.talon_verify_workspace_bytes(1, 64, 128256, 1) > lib.talon_expand_workspace_bytes(1, 64, 128256, 1, 1)
+    assert lib.talon_verify_workspace_bytes(1, 60, 128256, 1) == 0
+    ta = lambda **kw: lib.talon_target_argmax(kw.get("logits", P), kw.get("dtype", 1), kw.get("row_stride", 1024),
+                                              1024 * 64, ctypes.byref(st), kw.get("vocab", 1024), kw.get("tok", P), None,
+                                              kw.get("sstat", P), kw.get("ws", P), kw.get("ws_bytes", 1 << 30), None)
+    assert ta(logits=0) == T.TALON_ERR_INVALID_ARG
+    assert ta(tok=0) == T.TALON_ERR_INVALID_ARG
+    assert ta(sstat=0) == T.TALON_ERR_INVALID_ARG
+    assert ta(dtype=9) == T.TALON_ERR_UNSUPPORTED
+    assert ta(row_stride=1000) == T.TALON_ERR_INVALID_ARG
+    assert ta(ws=0) == T.TALON_ERR_INVALID_ARG
+    assert ta(ws_bytes=1024) == T.TALON_ERR_WORKSPACE
+    assert lib.talon_greedy_accept(ctypes.byref(st), P, P, None, P, P, None) == T.TALON_ERR_INVALID_ARG
+    assert lib.talon_greedy_accept(None, P, P, P, P, P, None) == T.TALON_ERR_INVALID_ARG
+    ck = lambda **kw: lib.talon_compact_kv(kw.get("kt", P), P, P, P, P, P, P, P, kw.get("B", 1), kw.get("N_pad", 64), 8,
+                                           kw.get("Dh", 128), kw.get("cap", 4096), 4096 * 1024, kw.get("st_", 1024), 128,
+                                           None)
+    assert ck(kt=0) == T.TALON_ERR_INVALID_ARG
+    assert ck(kt=P + 2) == T.TALON_ERR_INVALID_ARG
+    assert ck(Dh=100) == T.TALON_ERR_INVALID_ARG
+    assert ck(cap=0) == T.TALON_ERR_INVALID_ARG
+    assert ck(st_=1001) == T.TALON_ERR_INVALID_ARG
+    assert ck(N_pad=48) == T.TALON_ERR_INVALID_ARG
+    assert lib.talon_prune_tree(ctypes.byref(st), 0, P, None) == T.TALON_ERR_INVALID_ARG
+    assert lib.talon_prune_tree(ctypes.byref(st), 65, P, None) == T.TALON_ERR_INVALID_ARG
+    assert lib.talon_prune_tree(ctypes.byref(st), 8, None, None) == T.TALON_ERR_INVALID_ARG
+    assert lib.talon_probe_read(None, 1 << 20, P, None) == T.TALON_ERR_INVALID_ARG
+    assert lib.talon_probe_mfma(0, 10, P, None, None) == T.TALON_ERR_INVALID_ARG
+
+
 def test_profile_hook_host_side(lib):
     n = ctypes.c_int32(-1)
     assert lib.talon_profile_read(None, 0, None) == T.TALON_ERR_INVALID_ARG
