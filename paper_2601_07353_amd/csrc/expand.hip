@@ -54,13 +54,26 @@ constexpr int kSubKeys = kSubBatch * 8 + TALON_K_MAX + 16;  // keys ranked per r
 #ifdef TALON_PHASE_TIMING
 __device__ unsigned long long g_phase[16];
 #define PHASE(i) do { if (threadIdx.x == 0 && blockIdx.x == 0) g_phase[i] = wall_clock64(); } while (0)
-#define PHASE_MAX(i) do { if (threadIdx.x == 0) atomicMax(&g_phase[i], wall_clock64()); } while (0)
 __device__ unsigned long long g_wg[1024][16];   // per-workgroup time stamps of its first item
+#ifdef TALON_TIMELINE_ONLY   // only the per-layer marks of the single-launch kernel: nothing that perturbs it
+#define PHASE_MAX(i) do { } while (0)
+#define WG_MARK(i) do { } while (0)
+#define WG_MARK2(i) do { } while (0)
+#else
+#define PHASE_MAX(i) do { if (threadIdx.x == 0) atomicMax(&g_phase[i], wall_clock64()); } while (0)
 #define WG_MARK(i) do { if (threadIdx.x == 0 && item == blockIdx.x && blockIdx.x < 1024) g_wg[blockIdx.x][i] = wall_clock64(); } while (0)
 #define WG_MARK2(i) do { if (threadIdx.x == 0 && blockIdx.x < 1024) g_wg[blockIdx.x][i] = wall_clock64(); } while (0)
+#endif
+__device__ unsigned long long g_tl[32][4];      // single-launch kernel: per-layer time stamps of workgroup 0
+#define TL_MARK(d, i) do { if (threadIdx.x == 0 && blockIdx.x == 0 && (d) < 32) g_tl[d][i] = wall_clock64(); } while (0)
+#ifdef TALON_TIMELINE_ONLY
+#define WG_MARK_LOADED(i) do { } while (0)
+#else
 #define WG_MARK_LOADED(i) do { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); WG_MARK(i); } while (0)
+#endif
 #else
 #define WG_MARK(i) do { } while (0)
+#define TL_MARK(d, i) do { } while (0)
 #define WG_MARK2(i) do { } while (0)
 #define WG_MARK_LOADED(i) do { } while (0)
 #define PHASE(i) do { } while (0)
@@ -713,7 +726,9 @@ template <int EPL>
 __global__ __launch_bounds__(kThreads, 3) void expand_tree_kernel(ExpandArgs a) {
   __shared__ int s_go;
   for (int d = 0; d < a.layers; ++d) {
+    TL_MARK(d, 0);
     const int rows = expand_body<EPL, kModeTree>(a, d);
+    TL_MARK(d, 1);
     if (rows == 0) break;   // uniform over the grid: every workgroup reads the same descriptors
     if (d + 1 == a.layers && !a.tree_mask) return;
     if (threadIdx.x == 0) {
@@ -731,7 +746,9 @@ __global__ __launch_bounds__(kThreads, 3) void expand_tree_kernel(ExpandArgs a) 
       return;
     }
     __syncthreads();   // s_go is rewritten in the next round
+    TL_MARK(d, 2);
   }
+  TL_MARK(31, 0);
   // ---- ancestor masks (Fig. 5(b), App. B): every selection of every layer is published by
   // now.  Bit j of row i is set iff j is i or an ancestor of i; one thread per node walks its
   // parent chain in LDS.
@@ -764,6 +781,7 @@ __global__ __launch_bounds__(kThreads, 3) void expand_tree_kernel(ExpandArgs a) 
         if (u < words) row[u] = w[u];
     }
   }
+  TL_MARK(31, 1);
 }
 
 __global__ __launch_bounds__(kThreads) void fill_zero_kernel(uint32_t* p, size_t n) {
@@ -865,6 +883,9 @@ extern "C" int talon_debug_read_phases(unsigned long long* host16) {
 }
 extern "C" int talon_debug_read_wg(unsigned long long* host) {
   return static_cast<int>(hipMemcpyFromSymbol(host, HIP_SYMBOL(g_wg), sizeof(unsigned long long) * 1024 * 16));
+}
+extern "C" int talon_debug_read_timeline(unsigned long long* host) {
+  return static_cast<int>(hipMemcpyFromSymbol(host, HIP_SYMBOL(g_tl), sizeof(unsigned long long) * 32 * 4));
 }
 extern "C" int talon_debug_clear_phases() {
   unsigned long long z[16] = {0};
