@@ -42,6 +42,19 @@ constexpr float kNegInfF = -__builtin_huge_valf();
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
+// 16 bytes per lane from global memory straight into LDS: lane l of the wavefront lands at
+// lds_base + 16*l (lds_base wave-uniform).  Written as inline assembly on purpose: for the
+// builtin of the same instruction the compiler waits for ALL outstanding loads before the
+// next LDS read of any address, which exposes the whole memory latency inside every step;
+// here the only waits are the explicit ones of tile_landed().  (Loads complete in order, so
+// a compiler-inserted wait for one of its own loads can only wait longer, never less.)
+__device__ __forceinline__ void global_to_lds_16(const uint16_t* src, const uint16_t* lds_base) {
+  const uint32_t lds_addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+      (__attribute__((address_space(3))) void*)(lds_base)));
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :: "v"(src), "s"(lds_addr) : "memory", "m0");
+}
+
 // LDS image of one 64-key tile: rows of DH bf16 without padding (the tiles are written by
 // direct global-to-LDS loads, which place the 64 lanes of a wavefront back to back).  Bank
 // conflicts are avoided by permuting the 16-byte chunks of every row, differently for K
@@ -166,8 +179,7 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attention_kernel(AttnArgs a)
       key = key < last ? key : last;
       const int chunk = cslot ^ (is_k ? SM::kswz(row) : SM::vswz(row));
       const uint16_t* src = base + static_cast<size_t>(key) * stride + chunk * 8;
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                       (__attribute__((address_space(3))) void*)(dst + row0_ * DH), 16, 0, 0);
+      global_to_lds_16(src, dst + row0_ * DH);
     }
   };
   // Fast path for a prefix tile that lies wholly below the prefix length: no clamping, and
@@ -193,11 +205,9 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attention_kernel(AttnArgs a)
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
       if (want_k)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kt_ + i * load_step + kchunk[i]),
-                                         (__attribute__((address_space(3))) void*)(sK + i * ROWS_PER_LOAD * DH), 16, 0, 0);
+        global_to_lds_16(kt_ + i * load_step + kchunk[i], sK + i * ROWS_PER_LOAD * DH);
       if (want_v)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vt_ + i * load_step + vchunk[i]),
-                                         (__attribute__((address_space(3))) void*)(sV + i * ROWS_PER_LOAD * DH), 16, 0, 0);
+        global_to_lds_16(vt_ + i * load_step + vchunk[i], sV + i * ROWS_PER_LOAD * DH);
     }
   };
   auto is_full_prefix = [&](int t) { return t < nPT && (t + 1) * kKeyTile <= L; };
