@@ -64,7 +64,8 @@ template <int DH>
 struct Smem {
   static constexpr int CPR = DH / 8;                     // 16-byte chunks per key row
   static constexpr int T_ELEMS = kKeyTile * DH;          // one tensor, one tile
-  static constexpr int BYTES = 4 * T_ELEMS * 2;          // two K stages and two V stages
+  static constexpr int MASK_BYTES = 128 * (TALON_N_MAX / 64) * 8;   // ancestor words of the workgroup's 128 rows
+  static constexpr int BYTES = 4 * T_ELEMS * 2 + MASK_BYTES;        // two K stages, two V stages, the mask words
   __device__ static int kswz(int row) { return DH == 128 ? (row & 15) : ((row >> 1) & 7); }
   __device__ static int vswz(int row) { return DH == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2); }
 };
@@ -134,6 +135,23 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attention_kernel(AttnArgs a)
     }
   }
 
+  // Make the compiler wait for the query loads here, in straight-line code: otherwise it
+  // places its wait for them at their first use inside the loop, where it would also wait
+  // for every tile load in flight (see global_to_lds_16).
+  {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    static_assert(RB == 1 && (DSTEPS == 8 || DSTEPS == 4), "one statement names every query fragment");
+    u32x4 qv[DSTEPS];
+#pragma unroll
+    for (int ds = 0; ds < DSTEPS; ++ds) qv[ds] = __builtin_bit_cast(u32x4, bq[0][ds]);
+    if constexpr (DSTEPS == 8)
+      asm volatile("" : "+v"(qv[0]), "+v"(qv[1]), "+v"(qv[2]), "+v"(qv[3]), "+v"(qv[4]), "+v"(qv[5]), "+v"(qv[6]), "+v"(qv[7]));
+    else
+      asm volatile("" : "+v"(qv[0]), "+v"(qv[1]), "+v"(qv[2]), "+v"(qv[3]));
+#pragma unroll
+    for (int ds = 0; ds < DSTEPS; ++ds) bq[0][ds] = __builtin_bit_cast(bf16x8, qv[ds]);
+  }
+
   float m_run[RB], l_run[RB];
   floatx16 o[DB][RB];
 #pragma unroll
@@ -162,6 +180,7 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attention_kernel(AttnArgs a)
   constexpr int ROWS_PER_LOAD = 64 / CPR;                 // key rows per wavefront load
   constexpr int LOADS = kKeyTile / ROWS_PER_LOAD / 4;     // loads per wavefront, tile and tensor
   // LDS: two K stages then two V stages.
+  unsigned long long* s_mask = reinterpret_cast<unsigned long long*>(smem + 4 * SM::T_ELEMS);
   auto stage_k = [&](int st_) { return smem + st_ * SM::T_ELEMS; };
   auto stage_v = [&](int st_) { return smem + (2 + st_) * SM::T_ELEMS; };
   auto load_tensor = [&](int t, const uint16_t* pre_base, const uint16_t* tree_base, uint16_t* dst, bool is_k) {
@@ -257,7 +276,7 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attention_kernel(AttnArgs a)
     for (int rb = 0; rb < RB; ++rb) {
       unsigned long long allow;
       if (is_prefix) allow = (1ull << (L - key0)) - 1ull;
-      else allow = valid_rb[rb] ? a.mask[(static_cast<size_t>(b) * a.N_pad + node_rb[rb]) * words + (t - nPT)] : 0ull;
+      else allow = s_mask[(wave * 32 * RB + 32 * rb + l32) * words + (t - nPT)];
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
         const uint32_t w = static_cast<uint32_t>(allow >> (32 * kb)) >> (4 * h);
@@ -381,6 +400,15 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attention_kernel(AttnArgs a)
     tile_landed();
   };
 
+  // The ancestor words of this workgroup's rows go to LDS once: inside the loop the only
+  // global loads are then the tile loads above, whose waits are all explicit.
+  for (int idx = tid; idx < 128 * RB * words; idx += kThreads) {
+    const int r = idx / words;
+    const int rho = row0 + r;
+    unsigned long long wv = 0ull;
+    if (rho < rows) wv = a.mask[(static_cast<size_t>(b) * a.N_pad + rho / G) * words + (idx - r * words)];
+    s_mask[idx] = wv;
+  }
   floatx16 s_a[2][RB], s_b[2][RB];
   if (nt > 0) {
     load_k(t_begin, 0);
