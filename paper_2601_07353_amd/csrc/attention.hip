@@ -38,6 +38,14 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef short short4v __attribute__((ext_vector_type(4)));
 
 constexpr int kKeyTile = 64;
+#ifndef TALON_AHEAD_QK
+#define TALON_AHEAD_QK 2
+#endif
+#ifndef TALON_AHEAD_PV
+#define TALON_AHEAD_PV 2
+#endif
+constexpr int kAheadQK = TALON_AHEAD_QK;   // K fragments read from LDS ahead of the matrix instruction that uses them
+constexpr int kAheadPV = TALON_AHEAD_PV;   // V^T fragments (two reads each) read ahead
 constexpr float kNegInfF = -__builtin_huge_valf();
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
@@ -350,11 +358,19 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attention_kernel(AttnArgs a)
       // ask the scheduler for: one LDS fragment read, one matrix instruction, a handful of
       // vector instructions, repeated; then keep the probabilities from sinking past the
       // branch below (which would undo the overlap)
+      // (the LDS reads run two fragments ahead of the matrix instruction that consumes them,
+      // so that an LDS round trip is not exposed before every matrix instruction)
+      __builtin_amdgcn_sched_group_barrier(0x100, kAheadQK, 0);     // DS reads up front
 #pragma unroll
-      for (int g_ = 0; g_ < 2 * DSTEPS; ++g_) {
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
+      for (int g_ = 0; g_ < 2 * DSTEPS - kAheadQK; ++g_) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
         __builtin_amdgcn_sched_group_barrier(0x002, DH == 128 ? 7 : 14, 0);   // VALU
+      }
+#pragma unroll
+      for (int g_ = 0; g_ < kAheadQK; ++g_) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, DH == 128 ? 7 : 14, 0);
       }
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
@@ -395,6 +411,15 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attention_kernel(AttnArgs a)
           }
         }
       }
+      // the transposing reads of a V^T fragment (two per matrix instruction) run two matrix
+      // instructions ahead
+      __builtin_amdgcn_sched_group_barrier(0x100, 2 * kAheadPV, 0);
+#pragma unroll
+      for (int g_ = 0; g_ < 4 * DB - kAheadPV; ++g_) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, kAheadPV, 0);
     }
     // loads of K(t+2), V(t+1) have landed; every wavefront is done with K(t+1) and V(t)
     tile_landed();
