@@ -569,6 +569,10 @@ int talon_tree_attention(const void* q, const void* k_prefix, const void* v_pref
       set_error("prefix K/V strides must be >= Dh and multiples of 8 elements");
       return TALON_ERR_INVALID_ARG;
     }
+    if (kv_stride_t > (1ll << 24)) {   // a tile's 64 rows are addressed with 32-bit byte offsets
+      set_error("prefix K/V token stride of %lld elements is above 2^24", (long long)kv_stride_t);
+      return TALON_ERR_UNSUPPORTED;
+    }
   }
   if (out_lse && (reinterpret_cast<uintptr_t>(out_lse) & 3u)) { set_error("out_lse is misaligned"); return TALON_ERR_INVALID_ARG; }
   if (!(scale >= 0.f) || isinf(scale)) { set_error("scale=%g must be finite and >= 0 (0 selects 1/sqrt(Dh))", (double)scale); return TALON_ERR_INVALID_ARG; }

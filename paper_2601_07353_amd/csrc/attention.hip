@@ -56,6 +56,16 @@ __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast
 // next LDS read of any address, which exposes the whole memory latency inside every step;
 // here the only waits are the explicit ones of tile_landed().  (Loads complete in order, so
 // a compiler-inserted wait for one of its own loads can only wait longer, never less.)
+// Same with the address split into a wave-uniform base (scalar registers) and a 32-bit
+// per-lane byte offset: the per-tile address arithmetic then runs on the scalar unit.
+__device__ __forceinline__ void global_to_lds_16(const uint16_t* uniform_base, uint32_t lane_byte_offset,
+                                                 const uint16_t* lds_base) {
+  const uint32_t lds_addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+      (__attribute__((address_space(3))) void*)(lds_base)));
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :: "v"(lane_byte_offset), "s"(uniform_base), "s"(lds_addr) : "memory", "m0");
+}
+
 __device__ __forceinline__ void global_to_lds_16(const uint16_t* src, const uint16_t* lds_base) {
   const uint32_t lds_addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
       (__attribute__((address_space(3))) void*)(lds_base)));
@@ -212,29 +222,24 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attention_kernel(AttnArgs a)
   // Fast path for a prefix tile that lies wholly below the prefix length: no clamping, and
   // the address is a per-lane base plus tile and load offsets (no 64-bit multiplies).
   const int lrow = lane / CPR;                       // key row of this lane inside one load
-  const size_t lane_off = static_cast<size_t>(wave * LOADS * ROWS_PER_LOAD + lrow) * a.kv_stride_t;
-  const uint16_t* kp_lane = kp_base + lane_off;
-  const uint16_t* vp_lane = vp_base + lane_off;
-  const size_t load_step = static_cast<size_t>(ROWS_PER_LOAD) * a.kv_stride_t;   // elements between loads
   const size_t tile_step = static_cast<size_t>(kKeyTile) * a.kv_stride_t;       // elements between tiles
-  int kchunk[LOADS], vchunk[LOADS];                  // permuted chunk of this lane, in elements
+  uint32_t koff[LOADS], voff[LOADS];                 // byte offset of this lane's chunk inside a tile, per load
 #pragma unroll
   for (int i = 0; i < LOADS; ++i) {
     const int row = (wave * LOADS + i) * ROWS_PER_LOAD + lrow;
-    kchunk[i] = ((lane % CPR) ^ SM::kswz(row)) * 8;
-    vchunk[i] = ((lane % CPR) ^ SM::vswz(row)) * 8;
+    const uint32_t row_bytes = static_cast<uint32_t>(row) * static_cast<uint32_t>(a.kv_stride_t) * 2u;
+    koff[i] = row_bytes + static_cast<uint32_t>(((lane % CPR) ^ SM::kswz(row)) * 16);
+    voff[i] = row_bytes + static_cast<uint32_t>(((lane % CPR) ^ SM::vswz(row)) * 16);
   }
   auto load_full_prefix = [&](int t, int kst, int vst, bool want_k, bool want_v) {
-    const uint16_t* kt_ = kp_lane + static_cast<size_t>(t) * tile_step;
-    const uint16_t* vt_ = vp_lane + static_cast<size_t>(t) * tile_step;
+    const uint16_t* kt_ = kp_base + static_cast<size_t>(t) * tile_step;   // wave-uniform
+    const uint16_t* vt_ = vp_base + static_cast<size_t>(t) * tile_step;
     uint16_t* sK = stage_k(kst) + wave * LOADS * ROWS_PER_LOAD * DH;
     uint16_t* sV = stage_v(vst) + wave * LOADS * ROWS_PER_LOAD * DH;
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
-      if (want_k)
-        global_to_lds_16(kt_ + i * load_step + kchunk[i], sK + i * ROWS_PER_LOAD * DH);
-      if (want_v)
-        global_to_lds_16(vt_ + i * load_step + vchunk[i], sV + i * ROWS_PER_LOAD * DH);
+      if (want_k) global_to_lds_16(kt_, koff[i], sK + i * ROWS_PER_LOAD * DH);
+      if (want_v) global_to_lds_16(vt_, voff[i], sV + i * ROWS_PER_LOAD * DH);
     }
   };
   auto is_full_prefix = [&](int t) { return t < nPT && (t + 1) * kKeyTile <= L; };
