@@ -667,12 +667,16 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
         // ---- sequence ticket: the workgroup that writes the last row of a sequence's frontier
         // runs that sequence's budget selection
         const int F = s_prefix[b + 1] - s_prefix[b];
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        __syncthreads();
-        if (tid == 0) {
-          const int old = __hip_atomic_fetch_add(&a.seq_ticket[b], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          s_last = (old == F - 1) ? 1 : 0;
-          if (s_last) store_agent(a.seq_ticket + b, 0);
+        if (F > 1) {
+          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+          __syncthreads();
+          if (tid == 0) {
+            const int old = __hip_atomic_fetch_add(&a.seq_ticket[b], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_last = (old == F - 1) ? 1 : 0;
+            if (s_last) store_agent(a.seq_ticket + b, 0);
+          }
+        } else if (tid == 0) {
+          s_last = 1;   // a one-row frontier: the workgroup that wrote the row selects right away
         }
         __syncthreads();
         if (s_last) {
