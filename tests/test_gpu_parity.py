@@ -216,6 +216,14 @@ def test_budget_of_one_and_two():
         H.compare_step(cfg, gpu, ref)
 
 
+def test_maximum_batch_of_256_sequences():
+    """B at the library's limit: 256 tiny sequences in one call (prefix over sequences, item
+    map and the per-sequence tickets at their largest)."""
+    cfg = small(name="b256", B=256, V=520, logits_dtype="bf16", K=3, N=9, Dmax=5, Hq=4, Hkv=4, Dh=64, L=16,
+                recipe=("gauss", 1.0, 4.0))
+    step_and_compare(cfg)
+
+
 def test_integer_outputs_are_reproducible_run_to_run():
     cfg = small(name="repro", V=50000, logits_dtype="bf16", K=10, N=60, Dmax=12, B=2, recipe=("gauss", 0.5, 8.0))
     seeds = [cfg.seed, cfg.seed]

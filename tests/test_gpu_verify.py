@@ -67,3 +67,23 @@ def test_c2_llama3_8b_verify_full_size():
 
 def test_c3_qwen3_8b_x4_verify_full_size():
     verify_case(CONFIGS["c3"])
+
+
+def test_nan_target_row_is_reported():
+    import torch
+    import paper_2601_07353_amd as T
+    cfg = small(name="verify-nan", V=2048, logits_dtype="f32", K=3, N=12, Dmax=6, B=2, Hq=4, Hkv=4, Dh=64, L=32)
+    seeds = admissible_seeds(cfg)
+    pool = H.build_pool(cfg, seeds)
+    st, _, _, _ = H.run_gpu_expand(cfg, H.to_device_logits(pool))
+    tpool = pool.copy()
+    tpool[1, 2, 77] = np.nan                      # one bad target row in sequence 1
+    attn = [attention_inputs(cfg, seeds[b], b) for b in range(cfg.B)]
+    gpu = H.run_gpu_verify(cfg, st, tpool, attn)
+    assert int(gpu["scan_status"][0]) == 0 and int(gpu["scan_status"][1]) & T.TALON_STATUS_BAD_ROW
+    status = st.status.cpu().numpy()
+    assert not (int(status[0]) & T.TALON_STATUS_BAD_ROW) and int(status[1]) & T.TALON_STATUS_BAD_ROW
+    # the clean sequence is unaffected: the target equals the draft, so greedy decoding follows the draft's best child
+    n0 = int(st.n_nodes[0])
+    rows = [storage_to_f64(tpool[0, i]) for i in range(n0)]
+    H.compare_verify(cfg, gpu, 0, st.token[0, :n0].cpu().numpy(), st.parent[0, :n0].cpu().numpy(), rows, attn[0])
