@@ -43,6 +43,9 @@ def parse_args():
     ap.add_argument("--attainable", action="store_true",
                     help="only run the library's two probes: a streaming read of 1 GiB and 512 MiB buffers (cold) "
                          "and a register-resident bf16 MFMA loop; prints the rates they reach")
+    ap.add_argument("--cap", type=int, default=0,
+                    help="per-row candidate cap k (default: the config's K).  A cap >= N - 1 gives the tree of "
+                         "Alg. 2 as printed (every token of every parent in the pool); the first layer stays Top-K")
     ap.add_argument("--accept", action="store_true",
                     help="also time the greedy verification outcome that follows a step (target argmax over every "
                          "tree node, acceptance walk, accepted-path KV compaction) on synthetic target logits")
@@ -115,10 +118,11 @@ def main():
     n_slots = args.slots or max(2, min(32, int(np.ceil(512e6 / (pool_bytes + kv_bytes)))))
     slots = [Slot(cfg, cfg.seed + 1000 * i, torch, H) for i in range(n_slots)]
 
+    cap = args.cap or cfg.K
     st = T.TreeState(cfg.B, cfg.N)
-    cand = T.Candidates(cfg.B, st.N_pad, cfg.K)
+    cand = T.Candidates(cfg.B, st.N_pad, cap)
     dt = T.TALON_DTYPE_F32 if cfg.logits_dtype == "f32" else T.TALON_DTYPE_BF16
-    ws_expand = T.make_expand_workspace(cfg.B, st.N_pad, cfg.V, cfg.K, dt)
+    ws_expand = T.make_expand_workspace(cfg.B, st.N_pad, cfg.V, cap, dt)
     roots = torch.from_numpy(H.root_tokens(cfg)).cuda()
     mask = torch.zeros(cfg.B, st.N_pad, st.N_pad // 64, dtype=torch.int64, device=dev)
     out = torch.zeros(cfg.B, st.N_pad, cfg.Hq, cfg.Dh, dtype=torch.bfloat16, device=dev)
@@ -127,7 +131,7 @@ def main():
     ws_attn = torch.empty(max(nb, 256), dtype=torch.uint8, device=dev)
 
     def expand(s):   # tree init, the whole loop of Alg. 2 and the ancestor mask: two launches
-        T.talon_build_tree(roots, s.logits, st, cfg.K, cfg.mu, cfg.K, 1, cfg.Dmax, cand, ws_expand, mask=mask)
+        T.talon_build_tree(roots, s.logits, st, cap, cfg.mu, cfg.K, 1, cfg.Dmax, cand, ws_expand, mask=mask)
 
     def attention(s):
         T.talon_tree_attention(s.q, s.kp, s.vp, s.kt, s.vt, mask, st.n_nodes, plen, cfg.L, out, None, ws_attn)
@@ -232,7 +236,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if cfg.logits_dtype == "bf16" else "f32",
         "data": "synthetic",
         "config": {"workload": cfg.name, "B": cfg.B, "vocab": cfg.V, "K": cfg.K, "N": cfg.N, "Dmax": cfg.Dmax,
-                   "mu": cfg.mu, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "Dh": cfg.Dh, "prefix_len": cfg.L,
+                   "mu": cfg.mu, "row_cap": cap, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "Dh": cfg.Dh, "prefix_len": cfg.L,
                    "input_slots": n_slots, "hip_graph": use_graph},
         "roofline": roofline,
         "kernels": kernels,

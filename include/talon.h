@@ -39,7 +39,7 @@ extern "C" {
 #define TALON_DTYPE_BF16 1
 
 /* limits */
-#define TALON_K_MAX 16     /* per-row candidate cap k                           */
+#define TALON_K_MAX 64     /* per-row candidate cap k; the selection also needs (N-1)*k <= 4096 */
 #define TALON_N_MAX 256    /* node budget N (root included)                     */
 #define TALON_B_MAX 256    /* sequences per call                                */
 

@@ -22,7 +22,7 @@ TALON_ERR_WORKSPACE = -3
 TALON_ERR_RUNTIME = -4
 TALON_DTYPE_F32 = 0
 TALON_DTYPE_BF16 = 1
-TALON_K_MAX = 16
+TALON_K_MAX = 64
 TALON_N_MAX = 256
 TALON_B_MAX = 256
 TALON_STATUS_DONE_BUDGET = 1

@@ -109,6 +109,10 @@ int check_select_args(const talon_tree_state* st, int32_t k, const void* cand_to
   if (init_layers < 0) { set_error("init_layers=%d must be >= 0", init_layers); return TALON_ERR_INVALID_ARG; }
   if (max_depth < 1) { set_error("max_depth=%d must be >= 1", max_depth); return TALON_ERR_INVALID_ARG; }
   if (!cand_token || !cand_prob || !cand_edge_logp) { set_error("NULL candidate pointer"); return TALON_ERR_INVALID_ARG; }
+  if (static_cast<long long>(st->N - 1) * k > 4096) {
+    set_error("(N-1)*k = %lld candidates per layer; the selection holds at most 4096", static_cast<long long>(st->N - 1) * k);
+    return TALON_ERR_UNSUPPORTED;
+  }
   return TALON_OK;
 }
 

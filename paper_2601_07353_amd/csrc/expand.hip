@@ -310,8 +310,8 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
   __shared__ double s_wsum[4];
   __shared__ int s_wcnt[4];
   __shared__ int s_last;
-  static_assert(sizeof(uint4) * 4 * kHitCap >= sizeof(unsigned long long) * kMergeCap,
-                "the vector buffers double as the row-merge staging array");
+  static_assert(kScanBytes >= static_cast<int>(sizeof(unsigned long long)) * kMergeCap,
+                "the scan buffers double as the row-merge staging array");
   unsigned long long* s_keys = reinterpret_cast<unsigned long long*>(&s_hitv[0][0]);
 
   const int tid = threadIdx.x;
@@ -576,7 +576,8 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
       const double sl = (m_l == kNegInf) ? 0.0 : s_l * static_cast<double>(__expf(m_l - wmax));
       const double wsum = wave_sum_f64(sl);
       if (lane == 0) { s_wmax[wave] = wmax; s_wsum[wave] = wsum; s_wcnt[wave] = tcnt; }
-      if (lane >= tcnt && lane < 16) topw[lane] = 0ull;   // unused slots of the list: zero keys
+      static_assert(TALON_K_MAX == 64, "a list has one slot per lane");
+      if (lane >= tcnt) topw[lane] = 0ull;   // unused slots of the list: zero keys
     }
     __syncthreads();
     PHASE(4);
@@ -585,16 +586,23 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
     // chunk's k best, sorted.  Lane 16w+i of every wavefront holds key i of list w; wavefront v
     // counts how many keys of list v are greater; the four counts add up to the rank.
     const int ctot = s_wcnt[0] + s_wcnt[1] + s_wcnt[2] + s_wcnt[3];
-    const unsigned long long mkey = s_topw[lane >> 4][lane & 15];
-    {
-      static_assert(TALON_K_MAX == 16, "16 slots per list");
+    if (k <= 16) {
+      const unsigned long long mkey = s_topw[lane >> 4][lane & 15];
       s_part[wave][lane] = count_greater_pad16(s_topw[wave], 16, mkey);
-    }
-    __syncthreads();
-    if (wave == 0) {
-      const int r = s_part[0][lane] + s_part[1][lane] + s_part[2][lane] + s_part[3][lane];
+      __syncthreads();
+      if (wave == 0) {
+        const int r = s_part[0][lane] + s_part[1][lane] + s_part[2][lane] + s_part[3][lane];
+        if (mkey != 0ull && r < k) s_top[r] = mkey;
+        if (lane >= ctot && lane < k) s_top[lane] = 0ull;   // fewer than k logits in this chunk
+      }
+    } else {
+      // long lists: thread t holds key t % 64 of its own wavefront's list and counts against all four
+      const unsigned long long mkey = s_topw[wave][lane];
+      int r = 0;
+#pragma unroll 1   // a rare path: keep it small in registers
+      for (int w = 0; w < 4; ++w) r += count_greater_pad16(s_topw[w], 64, mkey);
       if (mkey != 0ull && r < k) s_top[r] = mkey;
-      if (lane >= ctot && lane < k) s_top[lane] = 0ull;   // fewer than k logits in this chunk
+      if (tid >= ctot && tid < k) s_top[tid] = 0ull;
     }
     const float cm = fmaxf(fmaxf(s_wmax[0], s_wmax[1]), fmaxf(s_wmax[2], s_wmax[3]));
     double csum = 0.0;

@@ -18,7 +18,7 @@
 
 namespace talon {
 
-constexpr int kMaxCand = TALON_N_MAX * TALON_K_MAX;  // frontier <= N-1 rows of k candidates
+constexpr int kMaxCand = 4096;                       // candidates of one layer: frontier rows * k (checked on the host)
 constexpr int kPerThread = kMaxCand / kThreads;      // at most 16 consecutive candidates per thread
 constexpr int kSelectKeySlots = kThreads * (kPerThread + 1);
 

@@ -11,7 +11,7 @@ namespace talon {
 constexpr int kThreads = 256;       // every kernel here runs 4 wavefronts per workgroup
 constexpr int kScanTiles = 4;       // 16-byte vectors per thread per vocab chunk
 constexpr int kChunkBytes = kThreads * kScanTiles * 16;  // 16 KiB of a logits row per workgroup pass
-constexpr int kMergeCap = 1024;     // chunks * k keys one row merge stages in LDS
+constexpr int kMergeCap = 2048;     // chunks * k keys one row merge stages in LDS
 constexpr uint32_t kDoneMask = TALON_STATUS_DONE_BUDGET | TALON_STATUS_DONE_DEPTH | TALON_STATUS_ABORTED;
 
 void set_error(const char* fmt, ...);

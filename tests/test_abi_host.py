@@ -55,7 +55,7 @@ def expand_call(lib, st, logits=P, dtype=1, row_stride=1024, seq_stride=1024 * 6
 def test_expand_rejects_bad_arguments(lib):
     st = fake_state()
     assert expand_call(lib, st, k=0) == T.TALON_ERR_INVALID_ARG and "k=0" in err(lib)
-    assert expand_call(lib, st, k=17) == T.TALON_ERR_INVALID_ARG
+    assert expand_call(lib, st, k=65) == T.TALON_ERR_INVALID_ARG
     assert expand_call(lib, st, vocab=0) == T.TALON_ERR_INVALID_ARG
     assert expand_call(lib, st, dtype=7) == T.TALON_ERR_UNSUPPORTED
     assert expand_call(lib, st, logits=0) == T.TALON_ERR_INVALID_ARG
@@ -64,7 +64,7 @@ def test_expand_rejects_bad_arguments(lib):
     assert expand_call(lib, st, row_stride=1028) == T.TALON_ERR_INVALID_ARG   # not a multiple of 8 bf16
     assert expand_call(lib, st, row_mode=5) == T.TALON_ERR_INVALID_ARG
     assert expand_call(lib, st, ws_bytes=16) == T.TALON_ERR_WORKSPACE and "smaller" in err(lib)
-    assert expand_call(lib, st, vocab=16 * 8192 * 5, row_stride=16 * 8192 * 5, k=16) == T.TALON_ERR_UNSUPPORTED
+    assert expand_call(lib, st, vocab=16 * 8192 * 9, row_stride=16 * 8192 * 9, k=16) == T.TALON_ERR_UNSUPPORTED
     assert expand_call(lib, fake_state(N=300, N_pad=320)) == T.TALON_ERR_INVALID_ARG
     assert expand_call(lib, fake_state(N_pad=48)) == T.TALON_ERR_INVALID_ARG
     assert expand_call(lib, fake_state(B=0)) == T.TALON_ERR_INVALID_ARG
@@ -96,6 +96,7 @@ def test_select_rejects_bad_arguments(lib):
     assert select_call(lib, st, max_depth=0) == T.TALON_ERR_INVALID_ARG
     assert select_call(lib, st, k=0) == T.TALON_ERR_INVALID_ARG
     assert select_call(lib, st, cand=0) == T.TALON_ERR_INVALID_ARG
+    assert select_call(lib, fake_state(N=256, N_pad=256), k=32) == T.TALON_ERR_UNSUPPORTED   # 255 * 32 candidates per layer
     assert lib.talon_select_budget(None, 4, P, P, P, ctypes.c_float(0.03), 4, 1, 8, None) == T.TALON_ERR_INVALID_ARG
 
 

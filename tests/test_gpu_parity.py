@@ -339,3 +339,66 @@ def test_tree_attention_strided_prefix_view():
         want, _ = O.tree_attention(f(q[b, :n]), f(cache_k[b, 10:10 + L, 1:1 + Hkv]), f(cache_v[b, 10:10 + L, 1:1 + Hkv]),
                                    f(kt[b, :n]), f(vt[b, :n]), m)
         assert np.abs(got[b, :n] - want).max() <= H.ATTN_ATOL
+
+
+# ----------------------------------------------------------------------------- long candidate lists
+def _seeds_for_kinit(cfg, K_init):
+    from workloads import logits_row
+    roots = H.root_tokens(cfg)
+    seeds = []
+    for b in range(cfg.B):
+        for s in range(cfg.seed, cfg.seed + 64):
+            rows = {}
+
+            class Lazy:
+                def __getitem__(self, i):
+                    if i not in rows:
+                        rows[i] = logits_row(cfg, s, b, i)
+                    return rows[i]
+
+            t = H.oracle_tree(cfg, Lazy(), roots[b], K_init=K_init)
+            if t.margin > H.MARGIN_TOL:
+                seeds.append(s)
+                break
+        else:
+            raise RuntimeError("no admissible seed")
+    return seeds
+
+
+@pytest.mark.parametrize("kw", [
+    dict(V=5000, logits_dtype="f32", K=40, N=33, Dmax=10),                                    # cap 40 >= N - 1
+    dict(V=40000, logits_dtype="bf16", K=64, N=60, Dmax=12, B=2, Hq=8, Hkv=2, Dh=128, L=100,
+         recipe=(("gauss", 0.5, 1.0), ("gauss", 2.0, 6.0))),                                   # flat and peaked rows
+])
+def test_per_row_cap_up_to_64(kw):
+    """Candidate lists longer than 16 per row (the long-list merge paths), first layer Top-10."""
+    cfg = small(name="cap64", **kw)
+    seeds = _seeds_for_kinit(cfg, 10)
+    step_and_compare(cfg, seeds=seeds, K_init=10, with_attention=False)
+
+
+def test_c2_shape_uncapped_gate_is_the_paper_literal_tree():
+    """Alg. 2 pools every token of every parent.  With a per-row cap of 64 >= N - 1 = 59 the capped
+    pool gives exactly that tree: the GPU (k = 64) is compared with the oracle run on the full
+    vocabulary (cap = V), Llama-3-8B shape, Top-10 first layer."""
+    import dataclasses
+    from oracle import talon_oracle as O
+    from workloads import logits_row, storage_to_f64
+    cfg = dataclasses.replace(CONFIGS["c2"], name="c2-cap64", K=64)
+    seeds = _seeds_for_kinit(cfg, 10)
+    worst, gpu, ref = step_and_compare(cfg, seeds=seeds, K_init=10, with_attention=False)
+    rows = {}
+
+    def row_of(i):
+        if i not in rows:
+            rows[i] = storage_to_f64(logits_row(cfg, seeds[0], 0, i))
+        return rows[i]
+
+    full = O.build_tree(row_of, int(H.root_tokens(cfg)[0]), N=cfg.N, K=10, mu=float(np.float32(cfg.mu)), cap=cfg.V,
+                        Dmax=cfg.Dmax, init_layers=1)
+    n = full.n
+    assert int(gpu["n_nodes"][0]) == n
+    np.testing.assert_array_equal(gpu["token"][0, :n], np.asarray(full.token, dtype=np.int32))
+    np.testing.assert_array_equal(gpu["parent"][0, :n], np.asarray(full.parent, dtype=np.int32))
+    fan = np.bincount(np.asarray(full.parent[1:]), minlength=n)
+    print("c2 shape, uncapped gate: largest fan-out", int(fan.max()), "depths", np.bincount(full.depth).tolist())
