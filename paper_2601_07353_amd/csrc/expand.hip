@@ -193,61 +193,81 @@ __device__ __forceinline__ double log_of_sum(double sum) {
   return static_cast<double>(e) * 0.69314718055994530942 + static_cast<double>(__logf(static_cast<float>(f)));
 }
 
+constexpr int kCandCap = 512;   // keys of a row merge that can still be among the k best, after the filter below
+
 // Write the outputs of one row from its candidate keys (in LDS) and softmax statistics.
-// `keys` holds `lists` lists of k keys, each sorted in descending order.
+// `keys` holds `lists` lists of k keys, each sorted in descending order, zero keys in unused
+// slots and up to the next multiple of 16.  s_cand: kCandCap + 16 keys of LDS, 16-byte aligned.
 // FUSED: the candidates are read by another workgroup of this launch (the one that runs the
 // sequence's selection), so they are stored at the device-coherent level.
 template <bool FUSED>
 __device__ __forceinline__ void write_row(const ExpandArgs& a, int b, int out_row, const unsigned long long* keys,
-                                          int lists, float m, double sum) {
+                                          int lists, float m, double sum, unsigned long long* s_cand, int* s_nc) {
   const int tid = threadIdx.x;
   const int k = a.k;
   const double lse = static_cast<double>(m) + log_of_sum(sum);
   const size_t ob = static_cast<size_t>(out_row) * k;
-  // Rank by counting.  Thread t ranks keys t and t + 256 in one sweep over all keys (LDS
-  // broadcast reads, several in flight); a key's own list contributes its position.
   const int nkeys = lists * k;
-  for (int i0 = 0; i0 < nkeys; i0 += 2 * kThreads) {
-    const int ia = i0 + tid, ib = i0 + kThreads + tid;
-    const unsigned long long ka = ia < nkeys ? keys[ia] : 0ull;
-    const unsigned long long kb = ib < nkeys ? keys[ib] : 0ull;
-    const bool two = i0 + kThreads < nkeys;   // uniform: the second key of this sweep exists for some thread
-    int ra = 0, rb = 0;
-    if (lists > 1) {
-      // the key array is padded with zero keys to a multiple of 16
-      const ulonglong2* kp = reinterpret_cast<const ulonglong2*>(keys);
-      for (int j = 0; j < nkeys; j += 16) {
-        ulonglong2 v[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = kp[(j >> 1) + u];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          ra += ((v[u].x > ka) ? 1 : 0) + ((v[u].y > ka) ? 1 : 0);
-          if (two) rb += ((v[u].x > kb) ? 1 : 0) + ((v[u].y > kb) ? 1 : 0);
+  auto emit = [&](unsigned long long ki, int r) {
+    const float lg = key_logit(ki);
+    const double edge = static_cast<double>(lg) - lse;
+    const int32_t tok = static_cast<int32_t>(0xFFFFFFFFu - static_cast<uint32_t>(ki));
+    const float pr = __expf(static_cast<float>(edge));
+    a.cand_logit[ob + r] = lg;
+    if constexpr (FUSED) {
+      store_agent(a.cand_token + ob + r, tok);
+      store_agent(a.cand_edge_logp + ob + r, edge);
+      store_agent(a.cand_prob + ob + r, pr);
+    } else {
+      a.cand_token[ob + r] = tok;
+      a.cand_edge_logp[ob + r] = edge;
+      a.cand_prob[ob + r] = pr;
+    }
+  };
+  if (lists == 1) {   // a single sorted list: a key's position is its rank
+    for (int i = tid; i < k; i += kThreads) {
+      const unsigned long long ki = keys[i];
+      if (ki != 0ull) emit(ki, i);
+    }
+  } else {
+    // Rank by counting keys greater than mine.  First a filter: with q = ceil(k / lists), the
+    // q-th key of every list is >= T = their minimum, so at least k keys are >= T and only keys
+    // >= T can be among the k best; usually that leaves little more than k of the lists * k keys.
+    bool done = false;
+    if (lists <= 64) {
+      const int q = (k + lists - 1) / lists;
+      const int lane = tid & 63;
+      unsigned long long inv = 0ull;   // ~key of this lane's list (0 beyond the lists: no effect on the max)
+      if (lane < lists) inv = ~keys[lane * k + q - 1];
+      const unsigned long long T = ~wave_max_u64(inv);   // 0 if a list is shorter than q: no filter then
+      if (tid == 0) *s_nc = 0;
+      __syncthreads();
+      for (int i = tid; i < nkeys; i += kThreads) {
+        const unsigned long long ki = keys[i];
+        if (ki != 0ull && ki >= T) {
+          const int slot = atomicAdd(s_nc, 1);
+          if (slot < kCandCap) s_cand[slot] = ki;
         }
       }
-    } else {
-      ra = ia; rb = ib;   // a single sorted list
-    }
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const unsigned long long ki = h == 0 ? ka : kb;
-      const int r = h == 0 ? ra : rb;
-      if (ki != 0ull && r < k) {
-        const float lg = key_logit(ki);
-        const double edge = static_cast<double>(lg) - lse;
-        const int32_t tok = static_cast<int32_t>(0xFFFFFFFFu - static_cast<uint32_t>(ki));
-        const float pr = __expf(static_cast<float>(edge));
-        a.cand_logit[ob + r] = lg;
-        if constexpr (FUSED) {
-          store_agent(a.cand_token + ob + r, tok);
-          store_agent(a.cand_edge_logp + ob + r, edge);
-          store_agent(a.cand_prob + ob + r, pr);
-        } else {
-          a.cand_token[ob + r] = tok;
-          a.cand_edge_logp[ob + r] = edge;
-          a.cand_prob[ob + r] = pr;
+      __syncthreads();
+      const int nc = *s_nc;
+      if (nc <= kCandCap) {
+        if (tid < 16) s_cand[nc + tid] = 0ull;
+        __syncthreads();
+        for (int j = tid; j < nc; j += kThreads) {
+          const unsigned long long ki = s_cand[j];
+          const int r = count_greater_pad16(s_cand, nc, ki);
+          if (r < k) emit(ki, r);
         }
+        done = true;
+      }
+    }
+    if (!done) {   // every key against every key
+      for (int i = tid; i < nkeys; i += kThreads) {
+        const unsigned long long ki = keys[i];
+        if (ki == 0ull) continue;
+        const int r = count_greater_pad16(keys, nkeys, ki);
+        if (r < k) emit(ki, r);
       }
     }
   }
@@ -312,7 +332,11 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
   __shared__ int s_last;
   static_assert(kScanBytes >= static_cast<int>(sizeof(unsigned long long)) * kMergeCap,
                 "the scan buffers double as the row-merge staging array");
-  unsigned long long* s_keys = reinterpret_cast<unsigned long long*>(&s_hitv[0][0]);
+  static_assert(kScanBytes >= static_cast<int>(sizeof(unsigned long long)) * (kMergeCap + kCandCap + 16),
+                "... and hold the filtered candidates of a row merge behind it");
+  unsigned long long* s_keys = reinterpret_cast<unsigned long long*>(s_pool);
+  unsigned long long* s_cand = s_keys + kMergeCap;
+  __shared__ int s_nc;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -615,7 +639,7 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
 
     bool row_written = false;   // this workgroup has just written a whole row's outputs
     if (chunks == 1) {
-      write_row<FUSED>(a, b, out_row, s_top, 1, cm, csum);
+      write_row<FUSED>(a, b, out_row, s_top, 1, cm, csum, s_cand, &s_nc);
       row_written = true;
     } else {
       unsigned long long* pk = a.part_keys + (static_cast<size_t>(out_row) * blocks_per_row + ch) * k;
@@ -663,7 +687,7 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
         WG_MARK2(10);
         PHASE(7);
         PHASE_MAX(12);
-        write_row<FUSED>(a, b, out_row, s_keys, chunks, m, sum);
+        write_row<FUSED>(a, b, out_row, s_keys, chunks, m, sum, s_cand, &s_nc);
         PHASE_MAX(13);
         WG_MARK2(12);
         if (tid == 0) store_agent(a.ticket + out_row, 0);  // leave the workspace clean for the next layer
