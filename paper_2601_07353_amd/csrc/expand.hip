@@ -304,6 +304,7 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
   constexpr int NX = kScanTiles * EPL;          // logits per thread per block
   constexpr int BLOCK = kThreads * NX;          // logits per block
   __shared__ int s_prefix[TALON_B_MAX + 1];     // exclusive prefix of frontier sizes
+  __shared__ int s_begin[TALON_B_MAX];          // first frontier node of every sequence
   // One LDS pool: the scan's buffers (buffered vectors per wavefront, their tile*64+lane tags,
   // ranking scratch per wavefront; the vector buffers double as row-merge staging) and, in
   // fused mode, the key array and histogram of the budget selection, which runs when the
@@ -348,11 +349,15 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
     static_assert(TALON_B_MAX <= kThreads, "one thread per sequence");
     int c = 0;
     if (tid < a.B) {
-      if constexpr (FUSED) {
-        c = ld<TREE, int32_t>(a.desc + (launch_idx * a.B + tid) * 2 + 1);
-      } else {  // both loads are issued together; the select below is register-only
+      if constexpr (FUSED) {   // {begin, count} in one 8-byte load
+        const unsigned long long d2 = ld<TREE, unsigned long long>(
+            reinterpret_cast<const unsigned long long*>(a.desc) + (launch_idx * a.B + tid));
+        s_begin[tid] = static_cast<int>(static_cast<uint32_t>(d2));
+        c = static_cast<int>(static_cast<uint32_t>(d2 >> 32));
+      } else {  // the loads are issued together; the select below is register-only
         const uint32_t stat = a.status[tid];
         const int fc = a.frontier_count[tid];
+        s_begin[tid] = a.frontier_begin[tid];
         c = (stat & kDoneMask) ? 0 : fc;
       }
       // a finished sequence gets no selection in this launch: carry its empty frontier over
@@ -392,7 +397,7 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
     }
     const int b = lo;
     const int local = rg - s_prefix[b];
-    const int fbegin = FUSED ? ld<TREE, int32_t>(a.desc + (launch_idx * a.B + b) * 2) : a.frontier_begin[b];
+    const int fbegin = s_begin[b];
     const int node = fbegin + local;
     const int in_row = a.row_mode == TALON_ROWS_BY_FRONTIER ? local : node;
     const char* row = static_cast<const char*>(a.logits) +
