@@ -70,7 +70,7 @@ int expand_layout(int B, int N_pad, int vocab, int k, int dtype, ExpandLayout* L
   L->off_seq_ticket = align_up(rows * sizeof(int32_t), 256);
   L->off_desc = L->off_seq_ticket + align_up(static_cast<size_t>(B) * sizeof(int32_t), 256);
   L->off_layer_done = L->off_desc + align_up(static_cast<size_t>(N_pad) * B * 2 * sizeof(int32_t), 256);
-  L->off_max = L->off_layer_done + align_up(static_cast<size_t>(N_pad) * sizeof(uint32_t), 256);
+  L->off_max = L->off_layer_done + align_up(static_cast<size_t>(N_pad + 1) * sizeof(uint32_t), 256);   // + the exit ticket
   L->off_sum = L->off_max + align_up(rows * chunks * sizeof(float), 256);
   L->off_keys = L->off_sum + align_up(rows * chunks * sizeof(double), 256);
   L->total = L->off_keys + align_up(rows * chunks * k * sizeof(uint64_t), 256);
@@ -143,6 +143,8 @@ ExpandArgs make_expand_args(const void* logits, int64_t row_stride, int64_t seq_
   a.seq_ticket = reinterpret_cast<int32_t*>(w + L.off_seq_ticket);
   a.desc = reinterpret_cast<int32_t*>(w + L.off_desc);
   a.layer_done = reinterpret_cast<uint32_t*>(w + L.off_layer_done);
+  a.exit_ticket = a.layer_done + st->N_pad;
+  a.root_token = nullptr;
   a.launch_idx = 0;
   a.layers = 0;
   a.spin_ticks = 0;
@@ -312,8 +314,11 @@ int run_fused_layers(bool single_launch, const int32_t* root_token, uint64_t* ma
     if (mask) return check_hip(launch_mask(*st, mask, s), "mask launch");
     return TALON_OK;
   }
-  rc = check_hip(launch_fused_init(*st, root_token, ea, s), "fused init launch");
-  if (rc) return rc;
+  // The single launch starts fresh trees itself and leaves its counters clean; every other
+  // mode takes its first frontier from the public tree state in a small launch of its own.
+  const bool starts_trees = single_launch && root_token && first_layer == 0;
+  if (starts_trees) ea.root_token = root_token;
+  else if ((rc = check_hip(launch_fused_init(*st, root_token, ea, s), "fused init launch"))) return rc;
   if (!single_launch) {
     for (int d = 0; d < layers; ++d) {
       ea.launch_idx = d;
@@ -335,6 +340,7 @@ int run_fused_layers(bool single_launch, const int32_t* root_token, uint64_t* ma
   const int resident = tree_grid_limit(dtype);
   if (resident < 1) { set_error("occupancy query for the single-launch kernel failed"); return TALON_ERR_RUNTIME; }
   grid = grid < resident ? grid : resident;
+  if (grid > 0xFFFF) grid = 0xFFFF;   // the exit ticket counts workgroups in 16 bits
   ea.layers = layers;
   ea.spin_ticks = spin_limit_ticks();
   ea.tree_mask = mask;

@@ -126,6 +126,19 @@ __device__ __forceinline__ T load_agent(const T* p) {
   return __hip_atomic_load(const_cast<T*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Release half of a ticket: every global store and atomic this wavefront has issued so far
+// has been performed at the device-coherent level when this returns.  A workgroup-scope
+// fence does not give that (the compiler emits no wait on the vector memory counter for
+// it), and without the wait a ticket's atomic can overtake the partial results it
+// announces, even those of its own wavefront.  An agent-scope fence would also write the
+// whole L2 back, which nothing here needs: everything that crosses workgroups is stored at
+// agent scope.  Every wavefront of the workgroup calls this before the barrier that
+// precedes the ticket.
+__device__ __forceinline__ void stores_performed() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
 // Number of keys in s[0..n) greater than key (LDS broadcast reads, 4 in flight).
 __device__ __forceinline__ int count_greater(const unsigned long long* s, int n, unsigned long long key) {
   int r = 0;
@@ -349,7 +362,10 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
     static_assert(TALON_B_MAX <= kThreads, "one thread per sequence");
     int c = 0;
     if (tid < a.B) {
-      if constexpr (FUSED) {   // {begin, count} in one 8-byte load
+      if (TREE && a.root_token && launch_idx == 0) {   // fresh trees: the frontier is the root
+        s_begin[tid] = 0;
+        c = 1;
+      } else if constexpr (FUSED) {   // {begin, count} in one 8-byte load
         const unsigned long long d2 = ld<TREE, unsigned long long>(
             reinterpret_cast<const unsigned long long*>(a.desc) + (launch_idx * a.B + tid));
         s_begin[tid] = static_cast<int>(static_cast<uint32_t>(d2));
@@ -643,7 +659,31 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
     WG_MARK(2);
 
     bool row_written = false;   // this workgroup has just written a whole row's outputs
+    // Alg. 2 line 1 inside the single launch: T = {x_t}, p(x_t) = 1, d = 0.  The workgroup that
+    // writes the root's row (and then runs the sequence's first selection) sets the state up.
+    auto start_tree = [&]() {
+      if constexpr (TREE) {
+        if (a.root_token && launch_idx == 0) {
+          if (tid == 0) {
+            const talon_tree_state& st = a.sel.st;
+            const size_t o = static_cast<size_t>(b) * st.N_pad;
+            store_agent(st.token + o, a.root_token[b]);
+            store_agent(st.parent + o, -1);
+            store_agent(st.depth + o, 0);
+            store_agent(st.prob + o, 1.f);
+            store_agent(st.logp + o, 0.0);
+            store_agent(st.n_nodes + b, 1);
+            store_agent(st.frontier_begin + b, 0);
+            store_agent(st.frontier_count + b, 1);
+            store_agent(st.depth_cur + b, 0);
+            store_agent(st.status + b, 0u);
+          }
+          __syncthreads();
+        }
+      }
+    };
     if (chunks == 1) {
+      start_tree();
       write_row<FUSED>(a, b, out_row, s_top, 1, cm, csum, s_cand, &s_nc);
       row_written = true;
     } else {
@@ -654,7 +694,7 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
         store_agent(a.part_sum + static_cast<size_t>(out_row) * blocks_per_row + ch, csum);
       }
       // every partial store of this workgroup has completed before the ticket is taken
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      stores_performed();
       __syncthreads();
       if (tid == 0) {
         const int old = __hip_atomic_fetch_add(&a.ticket[out_row], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -692,6 +732,7 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
         WG_MARK2(10);
         PHASE(7);
         PHASE_MAX(12);
+        start_tree();
         write_row<FUSED>(a, b, out_row, s_keys, chunks, m, sum, s_cand, &s_nc);
         PHASE_MAX(13);
         WG_MARK2(12);
@@ -705,15 +746,16 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
         // runs that sequence's budget selection
         const int F = s_prefix[b + 1] - s_prefix[b];
         if (F > 1) {
-          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+          stores_performed();
           __syncthreads();
           if (tid == 0) {
             const int old = __hip_atomic_fetch_add(&a.seq_ticket[b], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             s_last = (old == F - 1) ? 1 : 0;
             if (s_last) store_agent(a.seq_ticket + b, 0);
           }
-        } else if (tid == 0) {
-          s_last = 1;   // a one-row frontier: the workgroup that wrote the row selects right away
+        } else {
+          stores_performed();   // the selection reads the row's candidates back from global memory
+          if (tid == 0) s_last = 1;   // a one-row frontier: the workgroup that wrote the row selects right away
         }
         __syncthreads();
         if (s_last) {
@@ -734,7 +776,7 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
           if constexpr (TREE) {
             // everything this layer wrote for the sequence is complete before its rows are
             // counted as done
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            stores_performed();
             __syncthreads();
             if (tid == 0)
               __hip_atomic_fetch_add(&a.layer_done[launch_idx], static_cast<uint32_t>(F), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -766,12 +808,14 @@ __global__ __launch_bounds__(kThreads, MODE == kModeSplit ? 4 : 3) void expand_k
 template <int EPL>
 __global__ __launch_bounds__(kThreads, 3) void expand_tree_kernel(ExpandArgs a) {
   __shared__ int s_go;
+  bool gave_up = false;
   for (int d = 0; d < a.layers; ++d) {
     TL_MARK(d, 0);
     const int rows = expand_body<EPL, kModeTree>(a, d);
     TL_MARK(d, 1);
     if (rows == 0) break;   // uniform over the grid: every workgroup reads the same descriptors
-    if (d + 1 == a.layers && !a.tree_mask) return;
+    // (the wait after the last layer is for the masks, and for the counters to be at rest
+    // before they are cleared)
     if (threadIdx.x == 0) {
       const unsigned long long t0 = wall_clock64();
       int go = 1;
@@ -784,20 +828,27 @@ __global__ __launch_bounds__(kThreads, 3) void expand_tree_kernel(ExpandArgs a) 
     __syncthreads();
     if (!s_go) {
       for (int b = threadIdx.x; b < a.B; b += kThreads) atomicOr(&a.status[b], TALON_STATUS_ABORTED);
-      return;
+      gave_up = true;
+      break;
     }
     __syncthreads();   // s_go is rewritten in the next round
     TL_MARK(d, 2);
   }
   TL_MARK(31, 0);
+  // ---- exit ticket: this workgroup has finished with the tickets and layer counters (all its
+  // own updates of them have completed).  The answer is needed only after the masks.
+  stores_performed();
+  __syncthreads();
+  uint32_t left_before = 0u;
+  if (threadIdx.x == 0)
+    left_before = __hip_atomic_fetch_add(a.exit_ticket, gave_up ? 0x10001u : 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   // ---- ancestor masks (Fig. 5(b), App. B): every selection of every layer is published by
   // now.  Bit j of row i is set iff j is i or an ancestor of i; one thread per node walks its
   // parent chain in LDS.
-  if (!a.tree_mask) return;
   __shared__ int s_par[TALON_N_MAX];
   const talon_tree_state& st = a.sel.st;
   const int words = st.N_pad / 64;
-  for (int b = blockIdx.x; b < a.B; b += gridDim.x) {
+  for (int b = blockIdx.x; a.tree_mask && !gave_up && b < a.B; b += gridDim.x) {
     const int tid = threadIdx.x;
     const int n = load_agent(st.n_nodes + b);
     const size_t base = static_cast<size_t>(b) * st.N_pad;
@@ -823,6 +874,25 @@ __global__ __launch_bounds__(kThreads, 3) void expand_tree_kernel(ExpandArgs a) 
     }
   }
   TL_MARK(31, 1);
+  // ---- the last workgroup to leave puts the counters back to zero for the next launch; if
+  // any workgroup gave up, tickets may be half taken: clear them all, and mark every sequence
+  // (a tree started late in the launch may have overwritten the mark)
+  if (threadIdx.x == 0) {
+    const bool last = (left_before & 0xFFFFu) == gridDim.x - 1u;
+    s_go = last ? (((left_before >> 16) != 0u || gave_up) ? 2 : 1) : 0;
+  }
+  __syncthreads();
+  if (s_go == 0) return;
+  const int t = threadIdx.x;
+  if (t < a.N_pad) store_agent(a.layer_done + t, 0u);
+  if (s_go == 2) {
+    for (int i = t; i < a.B * a.N_pad; i += kThreads) store_agent(a.ticket + i, 0);
+    for (int i = t; i < a.B; i += kThreads) {
+      store_agent(a.seq_ticket + i, 0);
+      atomicOr(&a.status[i], TALON_STATUS_ABORTED);
+    }
+  }
+  if (t == 0) store_agent(a.exit_ticket, 0u);
 }
 
 __global__ __launch_bounds__(kThreads) void fill_zero_kernel(uint32_t* p, size_t n) {

@@ -62,10 +62,17 @@ struct ExpandArgs {
   // Single-launch mode: one grid walks all layers; layer_done[i] counts the frontier rows of
   // layer i whose sequence has finished its selection, and a workgroup enters layer i+1 when
   // it equals the rows of layer i.  spin_ticks bounds that wait (100 MHz wall clock).
+  // The launch leaves these counters as it found them (all zero): every workgroup takes an
+  // exit ticket when it has finished with them and the last one clears them.  With
+  // root_token set the launch also starts the trees itself (Alg. 2 line 1): layer 0 is the
+  // root row of every sequence, and the workgroup that writes that row initialises the
+  // sequence's state first.
   int layers;
   uint32_t* layer_done;  // [N_pad]
+  uint32_t* exit_ticket; // low 16 bits: workgroups that have left; above: those that gave up
   unsigned long long spin_ticks;
   uint64_t* tree_mask;   // optional: ancestor masks written at the end of the single launch
+  const int32_t* root_token;   // optional [B]
 };
 
 struct AttnArgs {

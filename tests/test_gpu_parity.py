@@ -85,6 +85,42 @@ def test_layerwise_entry_points_against_oracle(mode):
     step_and_compare(cfg, with_attention=False, layerwise=mode)
 
 
+def test_repeated_calls_agree_on_every_row():
+    """The same call 200 times, each on a freshly cleared workspace: every row's softmax
+    statistics, every candidate and every tree must come out the same each time, and equal to
+    the oracle's.  (A chunk's partial results must have been performed before the ticket that
+    announces them: a ticket that overtakes them shows up here as a row whose log-sum-exp
+    misses one chunk, once in some tens of calls.)"""
+    import torch
+    cfg = small(name="repeat", V=40000, logits_dtype="bf16", K=8, N=130, Dmax=20, B=3, Hq=8, Hkv=2, Dh=128, L=200,
+                recipe=(("gauss", 6.0, 8.0), ("gauss", 0.5, 1.0), ("zipf_mix", 1.2, 0.05)))
+    seeds = admissible_seeds(cfg)
+    pool = H.build_pool(cfg, seeds)
+    ref = H.run_oracle_step(cfg, seeds, pool=pool, with_attention=False)
+    pool_dev = H.to_device_logits(pool)
+    first = None
+    for rep in range(200):
+        st, cand, _, mask = H.run_gpu_expand(cfg, pool_dev)
+        got = {"row_lse": cand.row_lse, "row_max": cand.row_max, "cand_token": cand.token, "token": st.token,
+               "parent": st.parent, "n_nodes": st.n_nodes, "mask": mask}
+        n = [int(x) for x in st.n_nodes.cpu()]
+        assert n == [t.n for t in ref["trees"]], (rep, n)
+        rows = [(b, r.node) for b, t in enumerate(ref["trees"]) for pl in t.pools for r in pl]
+        bi = torch.tensor([b for b, _ in rows], device="cuda"); ni = torch.tensor([i for _, i in rows], device="cuda")
+        snap = {"row_lse": got["row_lse"][bi, ni].clone(), "row_max": got["row_max"][bi, ni].clone(),
+                "cand_token": got["cand_token"][bi, ni].clone(),
+                "token": torch.cat([got["token"][b, :k] for b, k in enumerate(n)]),
+                "parent": torch.cat([got["parent"][b, :k] for b, k in enumerate(n)]),
+                "mask": torch.cat([got["mask"][b, :k].reshape(-1) for b, k in enumerate(n)])}
+        if first is None:
+            first = snap
+            want = np.array([r.row_lse for t in ref["trees"] for pl in t.pools for r in pl])
+            assert np.abs(snap["row_lse"].cpu().numpy() - want).max() <= H.LSE_ATOL
+        else:
+            for key, v in snap.items():
+                assert torch.equal(v, first[key]), (rep, key)
+
+
 def test_c2_llama3_8b_step_full_size():
     worst, gpu, ref = step_and_compare(CONFIGS["c2"])
     print("c2 attention worst abs err", worst)
