@@ -70,7 +70,7 @@ int expand_layout(int B, int N_pad, int vocab, int k, int dtype, ExpandLayout* L
   L->off_seq_ticket = align_up(rows * sizeof(int32_t), 256);
   L->off_desc = L->off_seq_ticket + align_up(static_cast<size_t>(B) * sizeof(int32_t), 256);
   L->off_layer_done = L->off_desc + align_up(static_cast<size_t>(N_pad) * B * 2 * sizeof(int32_t), 256);
-  L->off_max = L->off_layer_done + align_up(static_cast<size_t>(N_pad + 1) * sizeof(uint32_t), 256);   // + the exit ticket
+  L->off_max = L->off_layer_done + align_up(static_cast<size_t>(N_pad + kExitGroups + 1) * sizeof(uint32_t), 256);   // + the exit tickets
   L->off_sum = L->off_max + align_up(rows * chunks * sizeof(float), 256);
   L->off_keys = L->off_sum + align_up(rows * chunks * sizeof(double), 256);
   L->total = L->off_keys + align_up(rows * chunks * k * sizeof(uint64_t), 256);

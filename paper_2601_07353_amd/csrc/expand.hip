@@ -839,9 +839,14 @@ __global__ __launch_bounds__(kThreads, 3) void expand_tree_kernel(ExpandArgs a) 
   // own updates of them have completed).  The answer is needed only after the masks.
   stores_performed();
   __syncthreads();
+  // Two levels: workgroup i counts in group i % kExitGroups; the last of a group counts the
+  // group.  Low 16 bits: arrivals; above: how many of them gave up.
+  const uint32_t group = blockIdx.x % kExitGroups;
+  const uint32_t group_size = (gridDim.x - group + kExitGroups - 1) / kExitGroups;
+  const uint32_t n_groups = gridDim.x < kExitGroups ? gridDim.x : kExitGroups;
   uint32_t left_before = 0u;
   if (threadIdx.x == 0)
-    left_before = __hip_atomic_fetch_add(a.exit_ticket, gave_up ? 0x10001u : 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    left_before = __hip_atomic_fetch_add(a.exit_ticket + 1 + group, gave_up ? 0x10001u : 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   // ---- ancestor masks (Fig. 5(b), App. B): every selection of every layer is published by
   // now.  Bit j of row i is set iff j is i or an ancestor of i; one thread per node walks its
   // parent chain in LDS.
@@ -878,8 +883,13 @@ __global__ __launch_bounds__(kThreads, 3) void expand_tree_kernel(ExpandArgs a) 
   // any workgroup gave up, tickets may be half taken: clear them all, and mark every sequence
   // (a tree started late in the launch may have overwritten the mark)
   if (threadIdx.x == 0) {
-    const bool last = (left_before & 0xFFFFu) == gridDim.x - 1u;
-    s_go = last ? (((left_before >> 16) != 0u || gave_up) ? 2 : 1) : 0;
+    int go = 0;
+    if ((left_before & 0xFFFFu) == group_size - 1u) {   // last of its group
+      const bool bad = (left_before >> 16) != 0u || gave_up;
+      const uint32_t groups_before = __hip_atomic_fetch_add(a.exit_ticket, bad ? 0x10001u : 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if ((groups_before & 0xFFFFu) == n_groups - 1u) go = ((groups_before >> 16) != 0u || bad) ? 2 : 1;
+    }
+    s_go = go;
   }
   __syncthreads();
   if (s_go == 0) return;
@@ -892,7 +902,7 @@ __global__ __launch_bounds__(kThreads, 3) void expand_tree_kernel(ExpandArgs a) 
       atomicOr(&a.status[i], TALON_STATUS_ABORTED);
     }
   }
-  if (t == 0) store_agent(a.exit_ticket, 0u);
+  if (t <= kExitGroups) store_agent(a.exit_ticket + t, 0u);
 }
 
 __global__ __launch_bounds__(kThreads) void fill_zero_kernel(uint32_t* p, size_t n) {

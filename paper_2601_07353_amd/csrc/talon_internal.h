@@ -29,6 +29,10 @@ struct SelectArgs {
   int K_init, init_layers, max_depth;
 };
 
+// Workgroups leave the single-launch kernel through a two-level ticket (one counter for all
+// of them would serialise several hundred atomics on one address at the end of the launch).
+constexpr int kExitGroups = 64;
+
 struct ExpandArgs {
   const void* logits;
   int64_t row_stride, seq_stride;
@@ -69,7 +73,7 @@ struct ExpandArgs {
   // sequence's state first.
   int layers;
   uint32_t* layer_done;  // [N_pad]
-  uint32_t* exit_ticket; // low 16 bits: workgroups that have left; above: those that gave up
+  uint32_t* exit_ticket; // [kExitGroups + 1] workgroups that have left, counted per group, then the groups
   unsigned long long spin_ticks;
   uint64_t* tree_mask;   // optional: ancestor masks written at the end of the single launch
   const int32_t* root_token;   // optional [B]
