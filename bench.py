@@ -130,7 +130,7 @@ def main():
     nb = T.talon_tree_attention_workspace_bytes(cfg.B, st.N_pad, cfg.Hq, cfg.Hkv, cfg.Dh, cfg.L)
     ws_attn = torch.empty(max(nb, 256), dtype=torch.uint8, device=dev)
 
-    def expand(s):   # tree init, the whole loop of Alg. 2 and the ancestor mask: two launches
+    def expand(s):   # tree init, the whole loop of Alg. 2 and the ancestor mask: one launch
         T.talon_build_tree(roots, s.logits, st, cap, cfg.mu, cfg.K, 1, cfg.Dmax, cand, ws_expand, mask=mask)
 
     def attention(s):

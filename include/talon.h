@@ -154,9 +154,13 @@ int talon_expand_select_layer(const void* logits, int dtype, int64_t row_stride,
                               double* row_lse, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * The whole while-loop of Alg. 2 enqueued in one call: min(max_depth, N-1) fused
- * scan+selection launches (see talon_expand_select_layer).  Finished sequences cost nothing
- * in the later iterations.  Arguments as in the calls above.
+ * The whole while-loop of Alg. 2 in one call and one scan launch: the grid walks up to
+ * min(max_depth, N-1) layers, each as talon_expand_select_layer runs it, and moves on to the
+ * next layer when every selection of a layer is done; it ends at the first layer with no
+ * frontier.  The workgroups wait for each other between layers, so the grid is limited to
+ * what the device holds at once; the wait is bounded, and a launch whose wait runs out
+ * (it never should) marks every sequence TALON_STATUS_ABORTED and ends.  Arguments as in the
+ * calls above; `workspace` initialised by talon_expand_workspace_init.
  */
 int talon_expand_tree(const void* logits, int dtype, int64_t row_stride, int64_t seq_stride,
                       int row_mode, const talon_tree_state* st, int32_t vocab, int32_t k,
@@ -166,11 +170,13 @@ int talon_expand_tree(const void* logits, int dtype, int64_t row_stride, int64_t
                       void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Alg. 2 from its first line to its last, and the tree's attention mask, in two launches:
+ * Alg. 2 from its first line to its last, and the tree's attention mask, in one launch:
  * T = {x_t} as talon_tree_init sets it (root_token: device, [B]), the whole loop as
  * talon_expand_tree runs it, and, if `mask` is not NULL, the ancestor mask of
  * talon_build_tree_mask written by the same launch once every sequence is complete.
- * Same results as the three calls in a row; arguments and errors as theirs.
+ * Same results as the three calls in a row; arguments and errors as theirs.  `workspace`
+ * must have been initialised by talon_expand_workspace_init (once: every launch leaves it
+ * as it found it).
  */
 int talon_build_tree(const int32_t* root_token, const void* logits, int dtype, int64_t row_stride,
                      int64_t seq_stride, int row_mode, const talon_tree_state* st, int32_t vocab,
