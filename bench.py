@@ -49,6 +49,9 @@ def parse_args():
     ap.add_argument("--accept", action="store_true",
                     help="also time the greedy verification outcome that follows a step (target argmax over every "
                          "tree node, acceptance walk, accepted-path KV compaction) on synthetic target logits")
+    ap.add_argument("--sweep", action="store_true",
+                    help="budget N, threshold mu and top-K-initialised layers swept on the c2 shape, with the "
+                         "bookkeeping of Sec. 5.3 / App. C per variant (tree size, depth, rows scanned, accepted length)")
     ap.add_argument("--zipf-grid", action="store_true",
                     help="only run the paper's tree-construction micro-benchmark shape (App. E.6): latency of one "
                          "layer expansion over K parents with Zipf rows, exponent x vocabulary grid, 20 warm-ups and "
@@ -110,6 +113,9 @@ def main():
         return
     if args.zipf_grid:
         print(json.dumps({"zipf_grid": zipf_grid(T, torch, np, H)}))
+        return
+    if args.sweep:
+        print(json.dumps({"sweep": variant_sweep(T, torch, np, H, args.steps)}))
         return
 
     elem = cfg.elem_bytes
@@ -299,6 +305,82 @@ def accept_outcome(T, torch, np, cfg, slots, st, steps, elem):
     by = rows * cfg.V * elem
     return {"us_per_call": us, "target_rows": rows, "bytes": by, "GBps": by / (us * 1e-6) / 1e9,
             "accepted_mean": float(alen.float().mean().item())}
+
+
+def variant_sweep(T, torch, np, H, steps):
+    """The knobs of Alg. 2 as the paper varies them (budget N, Table 5; threshold mu, Fig. 6; number
+    of top-K-initialised layers, Table 6), on the c2 shape: whole steps (talon_build_tree +
+    talon_tree_attention) replayed as HIP graphs over rotating inputs, then the temperature-0
+    outcome on synthetic target rows (the draft row plus noise: a stand-in for a target model that
+    mostly agrees with its draft) for the accepted length.  Per variant: steps/s, tree size n,
+    depth reached, rows scanned R, accepted draft tokens and tau = accepted + 1 (the bonus token)."""
+    import dataclasses
+    from workloads import CONFIGS, target_logits_pool
+    base = dataclasses.replace(CONFIGS["c2"], N=96)          # pools hold rows for the largest budget
+    n_slots = 12
+    slots, targets = [], []
+    for i in range(n_slots):
+        sl = Slot(base, base.seed + 1000 * i, torch, H)
+        slots.append(sl)
+        targets.append(H.to_device_logits(target_logits_pool(base, sl.seed)))
+    dev = "cuda"
+    dt = T.TALON_DTYPE_BF16
+    variants = [dict(N=N, mu=0.03, init_layers=1) for N in (32, 48, 60, 64, 80, 96)]
+    variants += [dict(N=60, mu=mu, init_layers=1) for mu in (0.003, 0.01, 0.1, 0.3)]
+    variants += [dict(N=60, mu=0.03, init_layers=k) for k in (0, 2, 3)]
+    rows_out = []
+    for v in variants:
+        cfg = dataclasses.replace(base, N=v["N"], mu=v["mu"])
+        st = T.TreeState(1, cfg.N)
+        Np = st.N_pad
+        cand = T.Candidates(1, Np, cfg.K)
+        ws = T.make_expand_workspace(1, Np, cfg.V, cfg.K, dt)
+        vws = T.make_verify_workspace(1, Np, cfg.V, dt)
+        roots = torch.from_numpy(H.root_tokens(cfg)).cuda()
+        mask = torch.zeros(1, Np, Np // 64, dtype=torch.int64, device=dev)
+        out = torch.zeros(1, Np, cfg.Hq, cfg.Dh, dtype=torch.bfloat16, device=dev)
+        plen = torch.full((1,), cfg.L, dtype=torch.int32, device=dev)
+        nb = T.talon_tree_attention_workspace_bytes(1, Np, cfg.Hq, cfg.Hkv, cfg.Dh, cfg.L)
+        wa = torch.empty(max(nb, 256), dtype=torch.uint8, device=dev)
+        tgt = torch.zeros(1, Np, dtype=torch.int32, device=dev)
+        prob = torch.zeros(1, Np, dtype=torch.float32, device=dev)
+        sstat = torch.zeros(1, dtype=torch.int32, device=dev)
+        path = torch.zeros(1, Np, dtype=torch.int32, device=dev)
+        alen = torch.zeros(1, dtype=torch.int32, device=dev)
+        bonus = torch.zeros(1, dtype=torch.int32, device=dev)
+
+        def step(sl):
+            T.talon_build_tree(roots, sl.logits, st, cfg.K, cfg.mu, cfg.K, v["init_layers"], cfg.Dmax, cand, ws, mask=mask)
+            T.talon_tree_attention(sl.q[:, :Np], sl.kp, sl.vp, sl.kt[:, :Np], sl.vt[:, :Np], mask, st.n_nodes, plen,
+                                   cfg.L, out, None, wa)
+
+        n, depth, rows, acc = [], [], [], []
+        graphs = []
+        for sl, tg in zip(slots, targets):
+            step(sl)
+            T.talon_target_argmax(tg, st, tgt, prob, sstat, vws)
+            T.talon_greedy_accept(st, tgt, sstat, path, alen, bonus)
+            torch.cuda.synchronize()
+            n.append(int(st.n_nodes[0])); depth.append(int(st.depth_cur[0]))
+            rows.append(int(st.n_nodes[0]) - int(st.frontier_count[0])); acc.append(int(alen[0]))
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                step(sl)
+            graphs.append(g)
+        for g in graphs:
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            graphs[i % n_slots].replay()
+        torch.cuda.synchronize()
+        us = (time.perf_counter() - t0) * 1e6 / steps
+        rows_out.append({"N": v["N"], "mu": v["mu"], "init_layers": v["init_layers"], "us_per_step": us,
+                         "steps_per_s": 1e6 / us, "n_mean": float(np.mean(n)), "depth_mean": float(np.mean(depth)),
+                         "rows_scanned_mean": float(np.mean(rows)), "accepted_mean": float(np.mean(acc)),
+                         "tau": float(np.mean(acc)) + 1.0})
+        del graphs
+    return rows_out
 
 
 def zipf_grid(T, torch, np, H, K=10, N=60, warm=20, runs=100):
