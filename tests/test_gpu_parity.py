@@ -76,6 +76,64 @@ def test_tree_launch_gives_up_cleanly_when_the_wait_is_cut_short(monkeypatch):
         np.testing.assert_array_equal(again[key], ref[key])
 
 
+def _expand_on(cfg, pool_dev, st, cand, ws, mask, roots):
+    import torch
+    import paper_2601_07353_amd as T
+    T.talon_build_tree(roots, pool_dev, st, cfg.K, cfg.mu, cfg.K, 1, cfg.Dmax, cand, ws, mask=mask)
+    torch.cuda.synchronize()
+    n = [int(x) for x in st.n_nodes.cpu()]
+    return {"n": n, "status": st.status.cpu().numpy().copy(),
+            "token": [st.token[b, :k].cpu().numpy().copy() for b, k in enumerate(n)],
+            "parent": [st.parent[b, :k].cpu().numpy().copy() for b, k in enumerate(n)],
+            "logp": [st.logp[b, :k].cpu().numpy().copy() for b, k in enumerate(n)],
+            "mask": [mask[b, :k].cpu().numpy().copy() for b, k in enumerate(n)]}
+
+
+def _same_trees(a, b):
+    assert a["n"] == b["n"]
+    np.testing.assert_array_equal(a["status"], b["status"])
+    for key in ("token", "parent", "logp", "mask"):
+        for x, y in zip(a[key], b[key]):
+            np.testing.assert_array_equal(x, y)
+
+
+def test_one_workspace_serves_call_after_call(monkeypatch):
+    """talon_build_tree leaves its workspace as it found it: the same workspace, tree state and
+    output buffers serve 40 calls that alternate between two inputs, then a launch that is
+    made to give up (wait bound forced to zero from the host), then the two inputs again;
+    every complete call must give exactly what a call on a fresh workspace gives."""
+    import torch
+    import paper_2601_07353_amd as T
+    cfg = small(name="reuse", V=40000, logits_dtype="bf16", K=8, N=100, Dmax=12, B=3,
+                recipe=(("gauss", 6.0, 8.0), ("gauss", 0.5, 1.0), ("gauss", 2.0, 8.0)))
+    seeds_a = admissible_seeds(cfg)
+    seeds_b = admissible_seeds(dataclasses.replace(cfg, seed=cfg.seed + 77))
+    pools = [H.to_device_logits(H.build_pool(cfg, seeds_a)), H.to_device_logits(H.build_pool(cfg, seeds_b))]
+    roots = torch.from_numpy(H.root_tokens(cfg)).cuda()
+
+    def fresh():
+        st = T.TreeState(cfg.B, cfg.N)
+        return (st, T.Candidates(cfg.B, st.N_pad, cfg.K),
+                T.make_expand_workspace(cfg.B, st.N_pad, cfg.V, cfg.K, T.TALON_DTYPE_BF16),
+                torch.full((cfg.B, st.N_pad, st.N_pad // 64), -1, dtype=torch.int64, device="cuda"))
+
+    want = []
+    for p in pools:
+        st, cand, ws, mask = fresh()
+        want.append(_expand_on(cfg, p, st, cand, ws, mask, roots))
+    assert want[0]["token"][0].tolist() != want[1]["token"][0].tolist()
+    st, cand, ws, mask = fresh()
+    for i in range(40):
+        _same_trees(_expand_on(cfg, pools[i % 2], st, cand, ws, mask, roots), want[i % 2])
+    monkeypatch.setenv("TALON_SPIN_LIMIT_US", "0")
+    cut = _expand_on(cfg, pools[0], st, cand, ws, mask, roots)
+    monkeypatch.delenv("TALON_SPIN_LIMIT_US")
+    aborted = (cut["status"] & T.TALON_STATUS_ABORTED) != 0
+    assert aborted.all() or not aborted.any()
+    for i in range(6):
+        _same_trees(_expand_on(cfg, pools[i % 2], st, cand, ws, mask, roots), want[i % 2])
+
+
 @pytest.mark.parametrize("mode", ["split", "fused", "tree"])
 def test_layerwise_entry_points_against_oracle(mode):
     """The per-layer entry points (scan and selection as two launches, or as one) on a batch
