@@ -316,9 +316,9 @@ int run_fused_layers(bool single_launch, const int32_t* root_token, uint64_t* ma
   }
   // The single launch starts fresh trees itself and leaves its counters clean; every other
   // mode takes its first frontier from the public tree state in a small launch of its own.
-  const bool starts_trees = single_launch && root_token && first_layer == 0;
+  const bool starts_trees = root_token != nullptr;   // talon_build_tree only: single launch, first layer 0
   if (starts_trees) ea.root_token = root_token;
-  else if ((rc = check_hip(launch_fused_init(*st, root_token, ea, s), "fused init launch"))) return rc;
+  else if ((rc = check_hip(launch_fused_init(*st, ea, s), "fused init launch"))) return rc;
   if (!single_launch) {
     for (int d = 0; d < layers; ++d) {
       ea.launch_idx = d;

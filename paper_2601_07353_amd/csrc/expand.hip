@@ -931,41 +931,25 @@ __global__ __launch_bounds__(kThreads) void tree_init_kernel(talon_tree_state st
 
 int expand_chunk_elems(int dtype) { return dtype == TALON_DTYPE_F32 ? kChunkBytes / 4 : kChunkBytes / 2; }
 
-// Start of a fused call: frontier descriptors of its first layer from the public tree state,
-// zero layer counters, and zero tickets (a launch that gave up may have left some taken).
-__global__ void fused_init_kernel(talon_tree_state st, const int32_t* root_token, int32_t* desc, uint32_t* layer_done,
-                                  int32_t* ticket, int32_t* seq_ticket) {
+// Start of a fused call that continues trees already begun: frontier descriptors of its first
+// layer from the public tree state; zero tickets and layer counters (nothing leaves them
+// taken, but a caller may hand over a workspace that other launch forms have used).
+__global__ void fused_init_kernel(talon_tree_state st, int32_t* desc, uint32_t* layer_done, int32_t* ticket,
+                                  int32_t* seq_ticket) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < st.B * st.N_pad) ticket[i] = 0;
   if (i < st.N_pad) layer_done[i] = 0u;
   if (i >= st.B) return;
   seq_ticket[i] = 0;
-  if (root_token) {   // start from T = {x_t} (Alg. 2 line 1), as talon_tree_init does
-    const size_t o = static_cast<size_t>(i) * st.N_pad;
-    st.token[o] = root_token[i];
-    st.parent[o] = -1;
-    st.depth[o] = 0;
-    st.prob[o] = 1.f;
-    st.logp[o] = 0.0;
-    st.n_nodes[i] = 1;
-    st.frontier_begin[i] = 0;
-    st.frontier_count[i] = 1;
-    st.depth_cur[i] = 0;
-    const uint32_t s0 = st.N <= 1 ? TALON_STATUS_DONE_BUDGET : 0u;
-    st.status[i] = s0;
-    desc[2 * i] = 0;
-    desc[2 * i + 1] = s0 ? 0 : 1;
-    return;
-  }
   desc[2 * i] = st.frontier_begin[i];
   desc[2 * i + 1] = (st.status[i] & kDoneMask) ? 0 : st.frontier_count[i];
 }
 
-hipError_t launch_fused_init(const talon_tree_state& st, const int32_t* root_token, const ExpandArgs& a, hipStream_t s) {
+hipError_t launch_fused_init(const talon_tree_state& st, const ExpandArgs& a, hipStream_t s) {
   static_assert(TALON_B_MAX <= 256 && TALON_N_MAX <= 256, "the first workgroup covers the per-sequence and per-layer arrays");
   const int n = st.B * st.N_pad;
-  hipLaunchKernelGGL(fused_init_kernel, dim3((n + 255) / 256), dim3(256), 0, s, st, root_token, a.desc, a.layer_done,
-                     a.ticket, a.seq_ticket);
+  hipLaunchKernelGGL(fused_init_kernel, dim3((n + 255) / 256), dim3(256), 0, s, st, a.desc, a.layer_done, a.ticket,
+                     a.seq_ticket);
   return hipGetLastError();
 }
 
