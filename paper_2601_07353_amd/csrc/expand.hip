@@ -771,7 +771,10 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
             const SelectLds lds{reinterpret_cast<unsigned long long*>(s_pool),
                                 reinterpret_cast<int*>(s_pool + sizeof(unsigned long long) * kSelectKeySlots),
                                 s_red_u64, s_red_i32, s_misc};
-            select_sequence<true>(a.sel, b, F, fbegin, status, lds, next_desc);
+            // a launch that started the tree itself knows |T| and the layer without asking memory
+            const bool own = TREE && a.root_token != nullptr;
+            select_sequence<true>(a.sel, b, F, fbegin, status, lds, next_desc, own ? fbegin + F : -1,
+                                  own ? launch_idx : -1);
           }
           if constexpr (TREE) {
             // everything this layer wrote for the sequence is complete before its rows are

@@ -54,9 +54,17 @@ __device__ __forceinline__ void st_(T* p, T v) {
 
 // Runs on all 256 threads of the workgroup.  F, fb: the frontier being expanded.  next_desc
 // (optional): receives {begin, count} of the new frontier, count 0 if the sequence is done.
+// n_known / d_known (>= 0): |T| and the layer index when the caller knows them (a launch that
+// started the tree itself: the frontier is the newest F nodes, so |T| = fb + F); otherwise
+// they are read from the tree state.  Either way the selection costs dependent memory round
+// trips, which is what its time is made of, so it avoids every one it can: the token, edge
+// probability and path score of a thread's first kRegCand candidates stay in registers from
+// the scoring pass to the append.
+constexpr int kRegCand = 4;
 template <bool AGENT>
 __device__ __forceinline__ void select_sequence(const SelectArgs& a, int b, int F, int fb, uint32_t status,
-                                                const SelectLds& lds, int* next_desc) {
+                                                const SelectLds& lds, int* next_desc, int n_known = -1,
+                                                int d_known = -1) {
   const talon_tree_state& st = a.st;
   const int tid = threadIdx.x;
   unsigned long long* s_key = lds.key;
@@ -65,8 +73,8 @@ __device__ __forceinline__ void select_sequence(const SelectArgs& a, int b, int 
   int* s_red_i32 = lds.red_i32;
   int& s_digit = lds.misc[0];
   int& s_remaining = lds.misc[1];
-  const int n = ld<AGENT, int32_t>(st.n_nodes + b);
-  const int d = ld<AGENT, int32_t>(st.depth_cur + b);
+  const int n = n_known >= 0 ? n_known : ld<AGENT, int32_t>(st.n_nodes + b);
+  const int d = d_known >= 0 ? d_known : ld<AGENT, int32_t>(st.depth_cur + b);
   const int R = st.N - n;
   const int k = a.k;
   const int C = F * k;
@@ -82,21 +90,33 @@ __device__ __forceinline__ void select_sequence(const SelectArgs& a, int b, int 
 
   // ---- path scores of the pool, as sortable keys (0 = no candidate)
   unsigned long long anchor_key = 0ull;
-  for (int i = 0; i < per; ++i) {
+  int tok_r[kRegCand];
+  float prob_r[kRegCand];
+  double score_r[kRegCand];
+  auto score_one = [&](int i, int* tok_out, float* prob_out, double* score_out) {
     const int c = c_begin + i;
     unsigned long long key = 0ull;
     if (c < C) {
       const int p = c / k;
       const size_t ci = (base + fb + p) * k + (c - p * k);
+      const int tok = ld<AGENT, int32_t>(a.cand_token + ci);
+      if (prob_out) *prob_out = ld<AGENT, float>(a.cand_prob + ci);
       const double s = ld<AGENT, double>(st.logp + base + fb + p) + ld<AGENT, double>(a.cand_edge_logp + ci);
-      if (ld<AGENT, int32_t>(a.cand_token + ci) >= 0 && s == s) {
+      if (tok_out) { *tok_out = tok; *score_out = s; }
+      if (tok >= 0 && s == s) {
         key = sortable_u64(s);
         if (key == 0ull) key = 1ull;
       }
     }
     my[i] = key;
     anchor_key = key > anchor_key ? key : anchor_key;
+  };
+#pragma unroll
+  for (int i = 0; i < kRegCand; ++i) {
+    tok_r[i] = -1; prob_r[i] = 0.f; score_r[i] = 0.0;
+    if (i < per) score_one(i, &tok_r[i], &prob_r[i], &score_r[i]);
   }
+  for (int i = kRegCand; i < per; ++i) score_one(i, nullptr, nullptr, nullptr);
   anchor_key = block_max_u64(anchor_key, s_red_u64);
 
   const bool init = d < a.init_layers;
@@ -207,14 +227,27 @@ __device__ __forceinline__ void select_sequence(const SelectArgs& a, int b, int 
   }
   int n_keep;
   int pos = block_exclusive_scan_i32(keep_local, s_red_i32, &n_keep);
-  for (int i = 0; i < per; ++i) {
+#pragma unroll
+  for (int i = 0; i < kRegCand; ++i) {
+    if (i < per && (keep_bits & (1u << i))) {
+      const int p = (c_begin + i) / k;
+      const size_t o = base + n + pos;
+      st.token[o] = tok_r[i];
+      st_<AGENT, int32_t>(st.parent + o, fb + p);   // read again by the in-launch mask build
+      st.depth[o] = d + 1;
+      st.prob[o] = prob_r[i];
+      st_<AGENT, double>(st.logp + o, score_r[i]);
+      ++pos;
+    }
+  }
+  for (int i = kRegCand; i < per; ++i) {
     if (keep_bits & (1u << i)) {
       const int c = c_begin + i;
       const int p = c / k;
       const size_t ci = (base + fb + p) * k + (c - p * k);
       const size_t o = base + n + pos;
       st.token[o] = ld<AGENT, int32_t>(a.cand_token + ci);
-      st_<AGENT, int32_t>(st.parent + o, fb + p);   // read again by the in-launch mask build
+      st_<AGENT, int32_t>(st.parent + o, fb + p);
       st.depth[o] = d + 1;
       st.prob[o] = ld<AGENT, float>(a.cand_prob + ci);
       st_<AGENT, double>(st.logp + o, ld<AGENT, double>(st.logp + base + fb + p) + ld<AGENT, double>(a.cand_edge_logp + ci));
