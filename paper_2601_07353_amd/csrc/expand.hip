@@ -213,8 +213,9 @@ constexpr int kCandCap = 512;   // keys of a row merge that can still be among t
 // slots and up to the next multiple of 16.  s_cand: kCandCap + 16 keys of LDS, 16-byte aligned.
 // FUSED: the candidates are read by another workgroup of this launch (the one that runs the
 // sequence's selection), so they are stored at the device-coherent level.
+// Returns whether the row could not be normalised (the same value in every thread).
 template <bool FUSED>
-__device__ __forceinline__ void write_row(const ExpandArgs& a, int b, int out_row, const unsigned long long* keys,
+__device__ __forceinline__ bool write_row(const ExpandArgs& a, int b, int out_row, const unsigned long long* keys,
                                           int lists, float m, double sum, unsigned long long* s_cand, int* s_nc) {
   const int tid = threadIdx.x;
   const int k = a.k;
@@ -298,11 +299,13 @@ __device__ __forceinline__ void write_row(const ExpandArgs& a, int b, int out_ro
       a.cand_prob[ob + tid] = 0.f;
     }
   }
+  const bool bad = !(fabs(lse) <= 1.7e308);
   if (tid == 0) {
     a.row_max[out_row] = m;
     a.row_lse[out_row] = lse;
-    if (!(fabs(lse) <= 1.7e308)) atomicOr(&a.status[b], TALON_STATUS_BAD_ROW);
+    if (bad) atomicOr(&a.status[b], TALON_STATUS_BAD_ROW);
   }
+  return bad;
 }
 
 // How a launch is used: scan only; scan with the selection in its tail (one layer per launch);
@@ -659,6 +662,7 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
     WG_MARK(2);
 
     bool row_written = false;   // this workgroup has just written a whole row's outputs
+    bool row_bad = false;       // ... and the row could not be normalised
     // Alg. 2 line 1 inside the single launch: T = {x_t}, p(x_t) = 1, d = 0.  The workgroup that
     // writes the root's row (and then runs the sequence's first selection) sets the state up.
     auto start_tree = [&]() {
@@ -684,7 +688,7 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
     };
     if (chunks == 1) {
       start_tree();
-      write_row<FUSED>(a, b, out_row, s_top, 1, cm, csum, s_cand, &s_nc);
+      row_bad = write_row<FUSED>(a, b, out_row, s_top, 1, cm, csum, s_cand, &s_nc);
       row_written = true;
     } else {
       unsigned long long* pk = a.part_keys + (static_cast<size_t>(out_row) * blocks_per_row + ch) * k;
@@ -733,7 +737,7 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
         PHASE(7);
         PHASE_MAX(12);
         start_tree();
-        write_row<FUSED>(a, b, out_row, s_keys, chunks, m, sum, s_cand, &s_nc);
+        row_bad = write_row<FUSED>(a, b, out_row, s_keys, chunks, m, sum, s_cand, &s_nc);
         PHASE_MAX(13);
         WG_MARK2(12);
         if (tid == 0) store_agent(a.ticket + out_row, 0);  // leave the workspace clean for the next layer
@@ -749,17 +753,24 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
           stores_performed();
           __syncthreads();
           if (tid == 0) {
-            const int old = __hip_atomic_fetch_add(&a.seq_ticket[b], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            s_last = (old == F - 1) ? 1 : 0;
-            if (s_last) store_agent(a.seq_ticket + b, 0);
+            // low 16 bits: rows written; above: how many of them could not be normalised
+            const int old = __hip_atomic_fetch_add(&a.seq_ticket[b], row_bad ? 0x10001 : 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const bool last = (old & 0xFFFF) == F - 1;
+            s_last = last ? ((old >> 16) != 0 || row_bad ? 2 : 1) : 0;
+            if (last) store_agent(a.seq_ticket + b, 0);
           }
         } else {
           stores_performed();   // the selection reads the row's candidates back from global memory
-          if (tid == 0) s_last = 1;   // a one-row frontier: the workgroup that wrote the row selects right away
+          if (tid == 0) s_last = row_bad ? 2 : 1;   // a one-row frontier: the workgroup that wrote the row selects right away
         }
         __syncthreads();
         if (s_last) {
-          const uint32_t status = __hip_atomic_load(&a.status[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          // A launch that started the tree itself knows the sequence's status (nothing but a
+          // row that cannot be normalised can have touched it), its size and its layer
+          // without asking memory.
+          const bool own = TREE && a.root_token != nullptr;
+          const uint32_t status = own ? (s_last == 2 ? static_cast<uint32_t>(TALON_STATUS_BAD_ROW) : 0u)
+                                      : __hip_atomic_load(&a.status[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           int* next_desc = a.desc + ((launch_idx + 1) * a.B + b) * 2;
           if (status & TALON_STATUS_BAD_ROW) {   // a row could not be normalised: stop the sequence here
             if (tid == 0) {
@@ -771,8 +782,6 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
             const SelectLds lds{reinterpret_cast<unsigned long long*>(s_pool),
                                 reinterpret_cast<int*>(s_pool + sizeof(unsigned long long) * kSelectKeySlots),
                                 s_red_u64, s_red_i32, s_misc};
-            // a launch that started the tree itself knows |T| and the layer without asking memory
-            const bool own = TREE && a.root_token != nullptr;
             select_sequence<true>(a.sel, b, F, fbegin, status, lds, next_desc, own ? fbegin + F : -1,
                                   own ? launch_idx : -1);
           }

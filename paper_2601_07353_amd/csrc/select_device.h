@@ -80,6 +80,53 @@ __device__ __forceinline__ void select_sequence(const SelectArgs& a, int b, int 
   const int C = F * k;
   const size_t base = static_cast<size_t>(b) * st.N_pad;
 
+  // One frontier row in a top-K-initialised layer (the first layer of every tree): the row's
+  // candidates are already in key order (edge log-probability falls with the rank, ties in
+  // rank order), so the K_init best of the pool are simply its first ones.
+  if (F == 1 && d < a.init_layers && k <= 64) {
+    const int limit = a.K_init < R ? a.K_init : R;
+    const size_t ci = (base + fb) * k + tid;
+    int tok = -1;
+    float pr = 0.f;
+    double score = 0.0;
+    if (tid < k) {
+      tok = ld<AGENT, int32_t>(a.cand_token + ci);
+      pr = ld<AGENT, float>(a.cand_prob + ci);
+      score = ld<AGENT, double>(st.logp + base + fb) + ld<AGENT, double>(a.cand_edge_logp + ci);
+    }
+    if (tid < 64) {   // the first wavefront holds the whole row
+      const bool valid = tid < k && tok >= 0 && score == score;
+      const unsigned long long vb = __ballot(valid);
+      // candidates are valid up to the first invalid one (missing candidates sit at the end)
+      const int n_valid = vb == ~0ull ? 64 : __builtin_ctzll(~vb);
+      const int n_keep = n_valid < limit ? n_valid : limit;
+      if (tid < n_keep) {
+        const size_t o = base + n + tid;
+        st.token[o] = tok;
+        st_<AGENT, int32_t>(st.parent + o, fb);
+        st.depth[o] = d + 1;
+        st.prob[o] = pr;
+        st_<AGENT, double>(st.logp + o, score);
+      }
+      if (tid == 0) {
+        const int n_new = n + n_keep;
+        uint32_t s = status;
+        if (n_new >= st.N) s |= TALON_STATUS_DONE_BUDGET;
+        else if (d + 1 >= a.max_depth) s |= TALON_STATUS_DONE_DEPTH;
+        st_<AGENT, int32_t>(st.n_nodes + b, n_new);
+        st_<AGENT, int32_t>(st.frontier_begin + b, n);
+        st_<AGENT, int32_t>(st.frontier_count + b, n_keep);
+        st_<AGENT, int32_t>(st.depth_cur + b, d + 1);
+        st_<AGENT, uint32_t>(st.status + b, s);
+        if (next_desc) {
+          st_<AGENT, int>(next_desc, n);
+          st_<AGENT, int>(next_desc + 1, (s & kDoneMask) ? 0 : n_keep);
+        }
+      }
+    }
+    return;
+  }
+
   // Thread t owns the `per` consecutive candidates [t*per, t*per+per) of the flat
   // (parent, rank) order.  Its LDS slots start at t*stride with stride odd, so that the
   // 64-bit accesses of a wavefront fall on distinct banks.
