@@ -49,7 +49,7 @@ int check_state(const talon_tree_state* st) {
 }
 
 struct ExpandLayout {
-  size_t off_max, off_sum, off_keys, off_ticket, off_seq_ticket, off_desc, off_layer_done, total;
+  size_t off_max, off_sum, off_keys, off_ticket, off_seq_ticket, off_desc, off_exit, total;
   int chunks;
 };
 
@@ -69,8 +69,8 @@ int expand_layout(int B, int N_pad, int vocab, int k, int dtype, ExpandLayout* L
   L->off_ticket = 0;
   L->off_seq_ticket = align_up(rows * sizeof(int32_t), 256);
   L->off_desc = L->off_seq_ticket + align_up(static_cast<size_t>(B) * sizeof(int32_t), 256);
-  L->off_layer_done = L->off_desc + align_up(static_cast<size_t>(N_pad) * B * 2 * sizeof(int32_t), 256);
-  L->off_max = L->off_layer_done + align_up(static_cast<size_t>(N_pad + kExitGroups + 1) * sizeof(uint32_t), 256);   // + the exit tickets
+  L->off_exit = L->off_desc + align_up(static_cast<size_t>(N_pad) * B * sizeof(uint64_t), 256);
+  L->off_max = L->off_exit + align_up(static_cast<size_t>(kExitGroups + 1) * sizeof(uint32_t), 256);
   L->off_sum = L->off_max + align_up(rows * chunks * sizeof(float), 256);
   L->off_keys = L->off_sum + align_up(rows * chunks * sizeof(double), 256);
   L->total = L->off_keys + align_up(rows * chunks * k * sizeof(uint64_t), 256);
@@ -141,9 +141,9 @@ ExpandArgs make_expand_args(const void* logits, int64_t row_stride, int64_t seq_
   char* w = static_cast<char*>(workspace);
   a.ticket = reinterpret_cast<int32_t*>(w + L.off_ticket);
   a.seq_ticket = reinterpret_cast<int32_t*>(w + L.off_seq_ticket);
-  a.desc = reinterpret_cast<int32_t*>(w + L.off_desc);
-  a.layer_done = reinterpret_cast<uint32_t*>(w + L.off_layer_done);
-  a.exit_ticket = a.layer_done + st->N_pad;
+  a.desc = reinterpret_cast<unsigned long long*>(w + L.off_desc);
+  a.exit_ticket = reinterpret_cast<uint32_t*>(w + L.off_exit);
+  a.layers = 0;
   a.root_token = nullptr;
   a.launch_idx = 0;
   a.layers = 0;
@@ -319,15 +319,12 @@ int run_fused_layers(bool single_launch, const int32_t* root_token, uint64_t* ma
   const bool starts_trees = root_token != nullptr;   // talon_build_tree only: single launch, first layer 0
   if (starts_trees) ea.root_token = root_token;
   else if ((rc = check_hip(launch_fused_init(*st, ea, s), "fused init launch"))) return rc;
-  if (!single_launch) {
-    for (int d = 0; d < layers; ++d) {
-      ea.launch_idx = d;
-      const int layer = first_layer < 0 ? -1 : first_layer + d;
-      if (g_profile.enabled && (rc = check_hip(profile_record(s), "profile event"))) return rc;
-      rc = check_hip(launch_expand(ea, dtype, expand_grid(st, L.chunks, layer, k, K_init, init_layers), true, s), "expand launch");
-      if (rc) return rc;
-      if (g_profile.enabled && (rc = check_hip(profile_record(s), "profile event"))) return rc;
-    }
+  if (!single_launch) {   // one layer, one launch
+    ea.launch_idx = 0;
+    if (g_profile.enabled && (rc = check_hip(profile_record(s), "profile event"))) return rc;
+    rc = check_hip(launch_expand(ea, dtype, expand_grid(st, L.chunks, first_layer, k, K_init, init_layers), true, s), "expand launch");
+    if (rc) return rc;
+    if (g_profile.enabled && (rc = check_hip(profile_record(s), "profile event"))) return rc;
     return TALON_OK;
   }
   // One launch walks all layers.  Its grid is the widest layer's, capped by what the device

@@ -361,18 +361,33 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
   PHASE(0);
 
   // ---- frontier sizes of all sequences -> item map (identical in every workgroup)
+  __shared__ int s_gave_up;
   {
     static_assert(TALON_B_MAX <= kThreads, "one thread per sequence");
+    if (TREE && tid == 0) s_gave_up = 0;
+    if constexpr (TREE) __syncthreads();
     int c = 0;
     if (tid < a.B) {
       if (TREE && a.root_token && launch_idx == 0) {   // fresh trees: the frontier is the root
         s_begin[tid] = 0;
         c = 1;
       } else if constexpr (FUSED) {   // {begin, count} in one 8-byte load
-        const unsigned long long d2 = ld<TREE, unsigned long long>(
-            reinterpret_cast<const unsigned long long*>(a.desc) + (launch_idx * a.B + tid));
+        const unsigned long long* dp = a.desc + (launch_idx * a.B + tid);
+        unsigned long long d2 = ld<TREE, unsigned long long>(dp);
+        if constexpr (TREE) {
+          // the selection of the layer before stores this word when all it wrote has been
+          // performed: wait for it (bounded)
+          if (!(d2 & kDescReady)) {
+            const unsigned long long t0 = wall_clock64();
+            do {
+              if (wall_clock64() - t0 > a.spin_ticks) { s_gave_up = 1; break; }
+              __builtin_amdgcn_s_sleep(2);
+              d2 = ld<true, unsigned long long>(dp);
+            } while (!(d2 & kDescReady));
+          }
+        }
         s_begin[tid] = static_cast<int>(static_cast<uint32_t>(d2));
-        c = static_cast<int>(static_cast<uint32_t>(d2 >> 32));
+        c = static_cast<int>(static_cast<uint32_t>(d2 >> 32) & 0x7FFFFFFFu);
       } else {  // the loads are issued together; the select below is register-only
         const uint32_t stat = a.status[tid];
         const int fc = a.frontier_count[tid];
@@ -380,13 +395,18 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
         c = (stat & kDoneMask) ? 0 : fc;
       }
       // a finished sequence gets no selection in this launch: carry its empty frontier over
-      if (FUSED && blockIdx.x == 0 && c == 0) st_<TREE, int32_t>(a.desc + ((launch_idx + 1) * a.B + tid) * 2 + 1, 0);
+      if (TREE && blockIdx.x == 0 && c == 0 && launch_idx + 1 < a.N_pad)
+        st_<true, unsigned long long>(a.desc + ((launch_idx + 1) * a.B + tid),
+                                      kDescReady | static_cast<unsigned long long>(static_cast<uint32_t>(s_begin[tid])));
     }
     int total;
     const int base = block_exclusive_scan_i32(c, s_red_i32, &total);
     if (tid < a.B) s_prefix[tid] = base;
     if (tid == 0) s_prefix[a.B] = total;
     __syncthreads();
+    if constexpr (TREE) {
+      if (s_gave_up) return -1;
+    }
   }
   PHASE(1);
   PHASE_MAX(10);
@@ -771,28 +791,24 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
           const bool own = TREE && a.root_token != nullptr;
           const uint32_t status = own ? (s_last == 2 ? static_cast<uint32_t>(TALON_STATUS_BAD_ROW) : 0u)
                                       : __hip_atomic_load(&a.status[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          int* next_desc = a.desc + ((launch_idx + 1) * a.B + b) * 2;
+          unsigned long long next = static_cast<unsigned long long>(static_cast<uint32_t>(fbegin));   // count 0
           if (status & TALON_STATUS_BAD_ROW) {   // a row could not be normalised: stop the sequence here
-            if (tid == 0) {
-              st_<TREE, int32_t>(a.sel.st.frontier_count + b, 0);
-              st_<TREE, int32_t>(next_desc, fbegin);
-              st_<TREE, int32_t>(next_desc + 1, 0);
-            }
+            if (tid == 0) st_<TREE, int32_t>(a.sel.st.frontier_count + b, 0);
           } else {
             const SelectLds lds{reinterpret_cast<unsigned long long*>(s_pool),
                                 reinterpret_cast<int*>(s_pool + sizeof(unsigned long long) * kSelectKeySlots),
                                 s_red_u64, s_red_i32, s_misc};
-            select_sequence<true>(a.sel, b, F, fbegin, status, lds, next_desc, own ? fbegin + F : -1,
-                                  own ? launch_idx : -1);
+            next = select_sequence<true>(a.sel, b, F, fbegin, status, lds, own ? fbegin + F : -1,
+                                         own ? launch_idx : -1);
           }
           if constexpr (TREE) {
-            // everything this layer wrote for the sequence is complete before its rows are
-            // counted as done
+            // everything this layer wrote for the sequence has been performed before the
+            // descriptor that lets the grid into the next layer is stored
             stores_performed();
             __syncthreads();
-            if (tid == 0)
-              __hip_atomic_fetch_add(&a.layer_done[launch_idx], static_cast<uint32_t>(F), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          }
+            if (tid == 0 && launch_idx + 1 < a.N_pad)
+              st_<true, unsigned long long>(a.desc + ((launch_idx + 1) * a.B + b), next | kDescReady);
+          }   // (a launch of one layer leaves no descriptor: the next call starts from the public state)
         }
       }
     }
@@ -821,30 +837,20 @@ template <int EPL>
 __global__ __launch_bounds__(kThreads, 3) void expand_tree_kernel(ExpandArgs a) {
   __shared__ int s_go;
   bool gave_up = false;
-  for (int d = 0; d < a.layers; ++d) {
+  // One pass more than there are layers: the pass after the last layer finds every sequence
+  // finished (depth cap or budget), which is also the proof that every selection is
+  // published.  A pass starts by waiting for the descriptors of its layer.
+  int d = 0;
+  for (; d <= a.layers; ++d) {
     TL_MARK(d, 0);
     const int rows = expand_body<EPL, kModeTree>(a, d);
     TL_MARK(d, 1);
-    if (rows == 0) break;   // uniform over the grid: every workgroup reads the same descriptors
-    // (the wait after the last layer is for the masks, and for the counters to be at rest
-    // before they are cleared)
-    if (threadIdx.x == 0) {
-      const unsigned long long t0 = wall_clock64();
-      int go = 1;
-      while (load_agent(a.layer_done + d) < static_cast<uint32_t>(rows)) {
-        if (wall_clock64() - t0 > a.spin_ticks) { go = 0; break; }
-        __builtin_amdgcn_s_sleep(4);
-      }
-      s_go = go;
-    }
-    __syncthreads();
-    if (!s_go) {
+    if (rows < 0) {   // the wait for a descriptor ran out
       for (int b = threadIdx.x; b < a.B; b += kThreads) atomicOr(&a.status[b], TALON_STATUS_ABORTED);
       gave_up = true;
       break;
     }
-    __syncthreads();   // s_go is rewritten in the next round
-    TL_MARK(d, 2);
+    if (rows == 0) break;   // uniform over the grid: every workgroup reads the same descriptors
   }
   TL_MARK(31, 0);
   // ---- exit ticket: this workgroup has finished with the tickets and layer counters (all its
@@ -906,7 +912,9 @@ __global__ __launch_bounds__(kThreads, 3) void expand_tree_kernel(ExpandArgs a) 
   __syncthreads();
   if (s_go == 0) return;
   const int t = threadIdx.x;
-  if (t < a.N_pad) store_agent(a.layer_done + t, 0u);
+  // descriptors of the layers this launch has written (all of them if a workgroup gave up)
+  const int used = s_go == 2 ? a.N_pad - 1 : (d + 1 < a.N_pad ? d + 1 : a.N_pad - 1);
+  for (int i = t; i < used * a.B; i += kThreads) store_agent(a.desc + a.B + i, 0ull);
   if (s_go == 2) {
     for (int i = t; i < a.B * a.N_pad; i += kThreads) store_agent(a.ticket + i, 0);
     for (int i = t; i < a.B; i += kThreads) {
@@ -944,24 +952,21 @@ __global__ __launch_bounds__(kThreads) void tree_init_kernel(talon_tree_state st
 int expand_chunk_elems(int dtype) { return dtype == TALON_DTYPE_F32 ? kChunkBytes / 4 : kChunkBytes / 2; }
 
 // Start of a fused call that continues trees already begun: frontier descriptors of its first
-// layer from the public tree state; zero tickets and layer counters (nothing leaves them
-// taken, but a caller may hand over a workspace that other launch forms have used).
-__global__ void fused_init_kernel(talon_tree_state st, int32_t* desc, uint32_t* layer_done, int32_t* ticket,
-                                  int32_t* seq_ticket) {
+// layer from the public tree state, none for the later layers; zero tickets (nothing leaves
+// them taken, but a caller may hand over a workspace that other launch forms have used).
+__global__ void fused_init_kernel(talon_tree_state st, unsigned long long* desc, int32_t* ticket, int32_t* seq_ticket) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < st.B * st.N_pad) ticket[i] = 0;
-  if (i < st.N_pad) layer_done[i] = 0u;
-  if (i >= st.B) return;
+  if (i >= st.B * st.N_pad) return;
+  ticket[i] = 0;
+  if (i >= st.B) { desc[i] = 0ull; return; }
   seq_ticket[i] = 0;
-  desc[2 * i] = st.frontier_begin[i];
-  desc[2 * i + 1] = (st.status[i] & kDoneMask) ? 0 : st.frontier_count[i];
+  const uint32_t count = (st.status[i] & kDoneMask) ? 0u : static_cast<uint32_t>(st.frontier_count[i]);
+  desc[i] = kDescReady | (static_cast<unsigned long long>(count) << 32) | static_cast<uint32_t>(st.frontier_begin[i]);
 }
 
 hipError_t launch_fused_init(const talon_tree_state& st, const ExpandArgs& a, hipStream_t s) {
-  static_assert(TALON_B_MAX <= 256 && TALON_N_MAX <= 256, "the first workgroup covers the per-sequence and per-layer arrays");
   const int n = st.B * st.N_pad;
-  hipLaunchKernelGGL(fused_init_kernel, dim3((n + 255) / 256), dim3(256), 0, s, st, a.desc, a.layer_done, a.ticket,
-                     a.seq_ticket);
+  hipLaunchKernelGGL(fused_init_kernel, dim3((n + 255) / 256), dim3(256), 0, s, st, a.desc, a.ticket, a.seq_ticket);
   return hipGetLastError();
 }
 

@@ -23,7 +23,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(SelectArgs a) {
     return;
   }
   const SelectLds lds{s_key, s_hist, s_red_u64, s_red_i32, s_misc};
-  select_sequence<false>(a, b, F, st.frontier_begin[b], status, lds, nullptr);
+  select_sequence<false>(a, b, F, st.frontier_begin[b], status, lds);
 }
 
 // Tree attention mask: bit j of row i set iff j is i or an ancestor of i (Fig. 5(b), App. B).

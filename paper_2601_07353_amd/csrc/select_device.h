@@ -52,8 +52,8 @@ __device__ __forceinline__ void st_(T* p, T v) {
   else *p = v;
 }
 
-// Runs on all 256 threads of the workgroup.  F, fb: the frontier being expanded.  next_desc
-// (optional): receives {begin, count} of the new frontier, count 0 if the sequence is done.
+// Runs on all 256 threads of the workgroup.  F, fb: the frontier being expanded.  Returns, in
+// thread 0, the new frontier as begin + (count << 32), count 0 if the sequence is done.
 // n_known / d_known (>= 0): |T| and the layer index when the caller knows them (a launch that
 // started the tree itself: the frontier is the newest F nodes, so |T| = fb + F); otherwise
 // they are read from the tree state.  Either way the selection costs dependent memory round
@@ -62,9 +62,9 @@ __device__ __forceinline__ void st_(T* p, T v) {
 // the scoring pass to the append.
 constexpr int kRegCand = 4;
 template <bool AGENT>
-__device__ __forceinline__ void select_sequence(const SelectArgs& a, int b, int F, int fb, uint32_t status,
-                                                const SelectLds& lds, int* next_desc, int n_known = -1,
-                                                int d_known = -1) {
+__device__ __forceinline__ unsigned long long select_sequence(const SelectArgs& a, int b, int F, int fb,
+                                                              uint32_t status, const SelectLds& lds,
+                                                              int n_known = -1, int d_known = -1) {
   const talon_tree_state& st = a.st;
   const int tid = threadIdx.x;
   unsigned long long* s_key = lds.key;
@@ -118,13 +118,11 @@ __device__ __forceinline__ void select_sequence(const SelectArgs& a, int b, int 
         st_<AGENT, int32_t>(st.frontier_count + b, n_keep);
         st_<AGENT, int32_t>(st.depth_cur + b, d + 1);
         st_<AGENT, uint32_t>(st.status + b, s);
-        if (next_desc) {
-          st_<AGENT, int>(next_desc, n);
-          st_<AGENT, int>(next_desc + 1, (s & kDoneMask) ? 0 : n_keep);
-        }
+        return static_cast<unsigned long long>(static_cast<uint32_t>(n)) |
+               (static_cast<unsigned long long>((s & kDoneMask) ? 0 : n_keep) << 32);
       }
     }
-    return;
+    return 0ull;
   }
 
   // Thread t owns the `per` consecutive candidates [t*per, t*per+per) of the flat
@@ -311,11 +309,10 @@ __device__ __forceinline__ void select_sequence(const SelectArgs& a, int b, int 
     st_<AGENT, int32_t>(st.frontier_count + b, n_keep);   // possibly from different compute dies in one launch
     st_<AGENT, int32_t>(st.depth_cur + b, d + 1);
     st_<AGENT, uint32_t>(st.status + b, s);
-    if (next_desc) {
-      st_<AGENT, int>(next_desc, n);
-      st_<AGENT, int>(next_desc + 1, (s & kDoneMask) ? 0 : n_keep);
-    }
+    return static_cast<unsigned long long>(static_cast<uint32_t>(n)) |
+           (static_cast<unsigned long long>((s & kDoneMask) ? 0 : n_keep) << 32);
   }
+  return 0ull;
 }
 
 }  // namespace talon

@@ -32,6 +32,7 @@ struct SelectArgs {
 // Workgroups leave the single-launch kernel through a two-level ticket (one counter for all
 // of them would serialise several hundred atomics on one address at the end of the launch).
 constexpr int kExitGroups = 64;
+constexpr unsigned long long kDescReady = 1ull << 63;
 
 struct ExpandArgs {
   const void* logits;
@@ -56,23 +57,24 @@ struct ExpandArgs {
   // Fused modes (the scan runs the budget selection of a sequence in its tail, when the last
   // row of that sequence's frontier has been written): selection parameters, the index of
   // this launch in the loop, per-sequence row tickets and per-layer frontier descriptors
-  // {begin, count} [N_pad][B]: layer i of a call reads desc[i] (desc[0] is copied from the
-  // public tree state) and its selections write desc[i+1], so a workgroup that starts late
-  // still sees the frontier of its own layer.
+  // [N_pad][B], one 8-byte word each: begin in the low half, count and kDescReady in the
+  // high half.  Layer i of a call reads desc[i] (desc[0] is copied from the public tree
+  // state, or known when the launch starts the trees itself) and its selections write
+  // desc[i+1], so a workgroup that starts late still sees the frontier of its own layer.
   SelectArgs sel;
   int launch_idx;
   int32_t* seq_ticket;   // [B]
-  int32_t* desc;         // [N_pad][B][2]
-  // Single-launch mode: one grid walks all layers; layer_done[i] counts the frontier rows of
-  // layer i whose sequence has finished its selection, and a workgroup enters layer i+1 when
-  // it equals the rows of layer i.  spin_ticks bounds that wait (100 MHz wall clock).
-  // The launch leaves these counters as it found them (all zero): every workgroup takes an
-  // exit ticket when it has finished with them and the last one clears them.  With
+  unsigned long long* desc;
+  // Single-launch mode: one grid walks all layers.  A descriptor is stored once everything
+  // its selection wrote has been performed, with kDescReady set; a workgroup enters layer i
+  // when every desc[i][b] is ready (it polls them; the wait is bounded by spin_ticks of the
+  // 100 MHz wall clock).  Descriptors of layers >= 1 are zero between launches.
+  // The launch leaves its workspace as it found it: every workgroup takes an exit ticket
+  // when it has finished with tickets and descriptors and the last one clears them.  With
   // root_token set the launch also starts the trees itself (Alg. 2 line 1): layer 0 is the
   // root row of every sequence, and the workgroup that writes that row initialises the
   // sequence's state first.
   int layers;
-  uint32_t* layer_done;  // [N_pad]
   uint32_t* exit_ticket; // [kExitGroups + 1] workgroups that have left, counted per group, then the groups
   unsigned long long spin_ticks;
   uint64_t* tree_mask;   // optional: ancestor masks written at the end of the single launch

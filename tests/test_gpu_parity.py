@@ -134,6 +134,67 @@ def test_one_workspace_serves_call_after_call(monkeypatch):
         _same_trees(_expand_on(cfg, pools[i % 2], st, cand, ws, mask, roots), want[i % 2])
 
 
+def test_launch_forms_share_one_workspace():
+    """All four launch forms (whole tree in one launch, continued tree in one launch, one fused
+    launch per layer, scan and selection as separate launches) take turns on ONE workspace and
+    tree state, on two inputs: none may leave anything behind that another one trips over."""
+    import torch
+    import paper_2601_07353_amd as T
+    cfg = small(name="forms", V=40000, logits_dtype="bf16", K=8, N=100, Dmax=12, B=3,
+                recipe=(("gauss", 6.0, 8.0), ("gauss", 0.5, 1.0), ("gauss", 2.0, 8.0)))
+    seeds_a = admissible_seeds(cfg)
+    seeds_b = admissible_seeds(dataclasses.replace(cfg, seed=cfg.seed + 77))
+    pools = [H.to_device_logits(H.build_pool(cfg, seeds_a)), H.to_device_logits(H.build_pool(cfg, seeds_b))]
+    roots = torch.from_numpy(H.root_tokens(cfg)).cuda()
+    st = T.TreeState(cfg.B, cfg.N)
+    cand = T.Candidates(cfg.B, st.N_pad, cfg.K)
+    ws = T.make_expand_workspace(cfg.B, st.N_pad, cfg.V, cfg.K, T.TALON_DTYPE_BF16)
+    mask = torch.full((cfg.B, st.N_pad, st.N_pad // 64), -1, dtype=torch.int64, device="cuda")
+
+    def snapshot():
+        torch.cuda.synchronize()
+        n = [int(x) for x in st.n_nodes.cpu()]
+        return {"n": n, "status": st.status.cpu().numpy().copy(),
+                "token": [st.token[b, :k].cpu().numpy().copy() for b, k in enumerate(n)],
+                "parent": [st.parent[b, :k].cpu().numpy().copy() for b, k in enumerate(n)],
+                "logp": [st.logp[b, :k].cpu().numpy().copy() for b, k in enumerate(n)]}
+
+    def same(a, b):
+        assert a["n"] == b["n"]
+        np.testing.assert_array_equal(a["status"], b["status"])
+        for key in ("token", "parent", "logp"):
+            for x, y in zip(a[key], b[key]):
+                np.testing.assert_array_equal(x, y)
+
+    def whole(p):
+        T.talon_build_tree(roots, p, st, cfg.K, cfg.mu, cfg.K, 1, cfg.Dmax, cand, ws, mask=mask)
+
+    def continued(p):
+        T.talon_tree_init(st, roots)
+        T.talon_expand_tree(p, st, cfg.K, cfg.mu, cfg.K, 1, cfg.Dmax, cand, ws)
+
+    def per_layer(p):
+        T.talon_tree_init(st, roots)
+        for d in range(cfg.Dmax):
+            T.talon_expand_select_layer(p, st, cfg.K, cfg.mu, cfg.K, 1, cfg.Dmax, cand, ws, layer=d)
+
+    def split(p):
+        T.talon_tree_init(st, roots)
+        for d in range(cfg.Dmax):
+            T.talon_expand_layer(p, st, cfg.K, cand, ws, layer=d)
+            T.talon_select_budget(st, cfg.K, cand, cfg.mu, cfg.K, 1, cfg.Dmax)
+
+    want = []
+    for p in pools:
+        whole(p)
+        want.append(snapshot())
+    order = [(whole, 0), (per_layer, 1), (whole, 0), (continued, 1), (split, 0), (whole, 1), (continued, 0),
+             (per_layer, 0), (whole, 1), (split, 1), (continued, 1), (whole, 0)]
+    for form, which in order:
+        form(pools[which])
+        same(snapshot(), want[which])
+
+
 @pytest.mark.parametrize("mode", ["split", "fused", "tree"])
 def test_layerwise_entry_points_against_oracle(mode):
     """The per-layer entry points (scan and selection as two launches, or as one) on a batch
