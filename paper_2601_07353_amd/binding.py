@@ -278,6 +278,8 @@ def talon_tree_attention(q, k_prefix, v_prefix, k_tree, v_tree, mask, n_nodes, p
     for t in (q, k_tree, v_tree, out, mask):
         if not t.is_contiguous():
             raise TalonError(TALON_ERR_INVALID_ARG, "q, k_tree, v_tree, mask and out must be contiguous")
+    if max_prefix_len == 0 or (k_prefix is not None and k_prefix.numel() == 0):
+        k_prefix = v_prefix = None     # no prefix: the tree attends to itself only
     if k_prefix is not None:
         if k_prefix.stride() != v_prefix.stride() or k_prefix.stride(3) != 1:
             raise TalonError(TALON_ERR_INVALID_ARG, "k_prefix and v_prefix must share strides, Dh contiguous")
