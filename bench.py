@@ -205,7 +205,23 @@ def main():
     assert n_rec == args.steps * layers, (n_rec, args.steps, layers)
     scan_ms_step = float(np.sum(scan_us)) * 1e-3 / args.steps
     scan_ms_launch = scan_ms_step / layers
-    attn_ms = float(np.mean([e0.elapsed_time(e1) for e0, e1 in ev_attn]))
+    attn_all = [e0.elapsed_time(e1) for e0, e1 in ev_attn]
+    attn_ms = float(np.mean(attn_all))
+    # one step at a time (a graph replay between two events, the device idle before it): the
+    # latency a single request sees, as mean and median beside the back-to-back rate above
+    lat = []
+    if use_graph:
+        for i in range(min(args.steps, 100)):
+            s = slots[i % n_slots]
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record(); s.graph.replay(); e1.record()
+            torch.cuda.synchronize()
+            lat.append(e0.elapsed_time(e1) * 1e3)
+    latency = {"expand_launch_us_mean": float(np.mean(scan_us)), "expand_launch_us_p50": float(np.median(scan_us)),
+               "attention_us_mean": attn_ms * 1e3, "attention_us_p50": float(np.median(attn_all)) * 1e3,
+               "single_step_us_mean": float(np.mean(lat)) if lat else None,
+               "single_step_us_p50": float(np.median(lat)) if lat else None}
 
     used = [i % n_slots for i in range(args.steps)]
     mean_rows = float(np.mean([rows_scanned[u] for u in used]))
@@ -246,6 +262,7 @@ def main():
                    "input_slots": n_slots, "hip_graph": use_graph},
         "roofline": roofline,
         "kernels": kernels,
+        "latency": latency,
     }
 
     if args.accept:
