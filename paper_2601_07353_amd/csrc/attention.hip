@@ -6,9 +6,9 @@
 //
 // Tiling.  The G = Hq/Hkv query heads that share a KV head are packed with the tree nodes
 // into one row dimension (row = node * G + head-in-group), so one K/V tile read from HBM
-// feeds G * n query rows.  A workgroup (4 wavefronts) owns 128*RB packed rows of one
+// feeds G * n query rows.  A workgroup (NW = 4 or 8 wavefronts) owns 32*NW packed rows of one
 // (sequence, KV head) and a contiguous range of 64-key tiles (split-KV); each wavefront
-// owns RB blocks of 32 rows.  K and V tiles are staged through LDS (double buffered, one
+// owns one block of 32 rows.  K and V tiles are staged through LDS (double buffered, one
 // barrier per tile).  Both products are computed transposed so that a query is a lane:
 //   S^T[key][query] = K . Q^T        A = K fragment (LDS, 16-byte reads), B = Q^T (registers)
 //   O^T[dh][query] += V^T . P^T      A = V^T fragment (LDS transpose reads), B = P^T
@@ -82,14 +82,16 @@ template <int DH>
 struct Smem {
   static constexpr int CPR = DH / 8;                     // 16-byte chunks per key row
   static constexpr int T_ELEMS = kKeyTile * DH;          // one tensor, one tile
-  static constexpr int MASK_BYTES = 128 * (TALON_N_MAX / 64) * 8;   // ancestor words of the workgroup's 128 rows
+  static constexpr int MASK_BYTES = 256 * (TALON_N_MAX / 64) * 8;   // ancestor words of the workgroup's rows (at most 256)
   static constexpr int BYTES = 4 * T_ELEMS * 2 + MASK_BYTES;        // two K stages, two V stages, the mask words
   __device__ static int kswz(int row) { return DH == 128 ? (row & 15) : ((row >> 1) & 7); }
   __device__ static int vswz(int row) { return DH == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2); }
 };
 
-template <int DH, int RB>
-__global__ __launch_bounds__(kThreads, 2) void tree_attention_kernel(AttnArgs a) {
+template <int DH, int NW>
+__global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void tree_attention_kernel(AttnArgs a) {
+  constexpr int RB = 1;             // 32-row blocks per wavefront
+  constexpr int kWgThreads = 64 * NW;
   using SM = Smem<DH>;
   constexpr int DSTEPS = DH / 16;   // MFMA steps over the head dimension for S^T
   constexpr int DB = DH / 32;       // 32-row blocks of O^T
@@ -119,7 +121,7 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attention_kernel(AttnArgs a)
   int L = a.prefix_len[b];
   L = L < 0 ? 0 : (L > a.max_prefix_len ? a.max_prefix_len : L);
   const int rows = n * G;
-  const int row0 = rt * (128 * RB);
+  const int row0 = rt * (32 * NW * RB);
   if (row0 >= rows) return;
 
   const int nPT = (L + kKeyTile - 1) / kKeyTile;
@@ -196,7 +198,8 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attention_kernel(AttnArgs a)
   // key instead: its score is masked to -inf below, so its probability is exactly 0 and the
   // (finite) value row it brought along adds nothing.
   constexpr int ROWS_PER_LOAD = 64 / CPR;                 // key rows per wavefront load
-  constexpr int LOADS = kKeyTile / ROWS_PER_LOAD / 4;     // loads per wavefront, tile and tensor
+  constexpr int LOADS = kKeyTile / ROWS_PER_LOAD / NW;    // loads per wavefront, tile and tensor
+  static_assert(LOADS >= 1, "every wavefront loads at least one group of key rows");
   // LDS: two K stages then two V stages.
   unsigned long long* s_mask = reinterpret_cast<unsigned long long*>(smem + 4 * SM::T_ELEMS);
   auto stage_k = [&](int st_) { return smem + st_ * SM::T_ELEMS; };
@@ -432,7 +435,7 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attention_kernel(AttnArgs a)
 
   // The ancestor words of this workgroup's rows go to LDS once: inside the loop the only
   // global loads are then the tile loads above, whose waits are all explicit.
-  for (int idx = tid; idx < 128 * RB * words; idx += kThreads) {
+  for (int idx = tid; idx < 32 * NW * RB * words; idx += kWgThreads) {
     const int r = idx / words;
     const int rho = row0 + r;
     unsigned long long wv = 0ull;
@@ -556,12 +559,12 @@ __global__ __launch_bounds__(kThreads) void tree_attention_combine_kernel(AttnAr
   if (a.out_lse && c == 0) a.out_lse[orow] = (M + __builtin_amdgcn_logf(den)) * 0.6931471805599453f;
 }
 
-template <int DH, int RB>
+template <int DH, int NW>
 hipError_t launch_one(const AttnArgs& a_in, hipStream_t s) {
   AttnArgs a = a_in;
-  a.row_tiles = (a.N_pad * a.G + 128 * RB - 1) / (128 * RB);
+  a.row_tiles = (a.N_pad * a.G + 32 * NW - 1) / (32 * NW);
   a.total_items = a.row_tiles * a.splits * a.B * a.Hkv;
-  auto kern = tree_attention_kernel<DH, RB>;
+  auto kern = tree_attention_kernel<DH, NW>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -569,7 +572,7 @@ hipError_t launch_one(const AttnArgs& a_in, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3(8 * ((a.total_items + 7) / 8)), dim3(kThreads), Smem<DH>::BYTES, s, a);
+  hipLaunchKernelGGL(kern, dim3(8 * ((a.total_items + 7) / 8)), dim3(64 * NW), Smem<DH>::BYTES, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (a.splits > 1) {
@@ -583,9 +586,24 @@ hipError_t launch_one(const AttnArgs& a_in, hipStream_t s) {
 
 }  // namespace
 
-// Launch plan: the number of KV splits.  Two workgroups fit one compute unit, so the grid
-// aims at 512 workgroups; but a split must keep enough key tiles to amortise its fixed work
-// (query load, first tile, the partial result it writes and the merge reads back).
+// Launch plan: rows per workgroup and the number of KV splits.  A workgroup is 4 wavefronts
+// (128 packed rows, two workgroups per compute unit) or, when a (sequence, KV head) has at
+// least 512 packed rows, 8 wavefronts (256 rows, one per compute unit): the same 8 wavefronts
+// per compute unit, but a K/V tile is loaded once for 256 rows instead of twice.  Either way
+// the grid aims at filling 256 compute units; but a split must keep enough key tiles to
+// amortise its fixed work (query load, first tile, the partial result it writes and the
+// merge reads back).
+int attention_waves(int rows) {
+  static int forced = -1;   // tuning knob: TALON_ATTN_WAVES = 4 or 8
+  if (forced < 0) {
+    const char* e = getenv("TALON_ATTN_WAVES");
+    forced = e ? atoi(e) : 0;
+    if (forced != 4 && forced != 8) forced = 0;
+  }
+  if (forced) return forced;
+  return rows >= 512 ? 8 : 4;
+}
+
 void attention_plan(int B, int N_pad, int Hq, int Hkv, int Dh, int max_prefix_len, int* splits,
                     int* tiles_per_split, int* rows_pad) {
   (void)Dh;
@@ -597,11 +615,13 @@ void attention_plan(int B, int N_pad, int Hq, int Hkv, int Dh, int max_prefix_le
   }
   const int G = Hq / Hkv;
   const int rows = N_pad * G;
-  const int mt = 128;
+  const int waves = attention_waves(rows);
+  const int mt = 32 * waves;
   const int row_tiles = (rows + mt - 1) / mt;
   const int tiles = (max_prefix_len + kKeyTile - 1) / kKeyTile + N_pad / kKeyTile;
   const long long base = static_cast<long long>(B) * Hkv * row_tiles;
-  long long want = (512 + base - 1) / base;
+  const long long slots = waves == 8 ? 256 : 512;
+  long long want = (slots + base - 1) / base;
   const long long cap = tiles / min_tiles > 1 ? tiles / min_tiles : 1;
   if (want > cap) want = cap;
   if (want < 1) want = 1;
@@ -612,8 +632,9 @@ void attention_plan(int B, int N_pad, int Hq, int Hkv, int Dh, int max_prefix_le
 }
 
 hipError_t launch_attention(const AttnArgs& a, hipStream_t s) {
-  if (a.Dh == 128) return launch_one<128, 1>(a, s);
-  return launch_one<64, 1>(a, s);
+  const bool wide = attention_waves(a.N_pad * a.G) == 8;
+  if (a.Dh == 128) return wide ? launch_one<128, 8>(a, s) : launch_one<128, 4>(a, s);
+  return wide ? launch_one<64, 8>(a, s) : launch_one<64, 4>(a, s);
 }
 
 }  // namespace talon
