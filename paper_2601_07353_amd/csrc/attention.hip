@@ -493,15 +493,19 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void tree_attention_kerne
       }
       if (a.out_lse && h == 0) a.out_lse[orow_rb[rb]] = (m_run[rb] + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
     } else {
+      // Partial O^T of a (KV head, split) is laid out in slabs of 8 head-dim values:
+      // [DH / 8][rows_pad][8], so that the 64 lanes of a store (32 rows x 2 halves of a slab
+      // entry) cover 1 KiB of consecutive addresses; row-major would give 32-byte pieces.
       const int rho = wrow0 + 32 * rb + l32;
-      const size_t prow = (static_cast<size_t>(bg) * a.splits + split) * a.rows_pad + rho;
-      float* po = a.part_o + prow * DH;
+      const size_t pblock = (static_cast<size_t>(bg) * a.splits + split) * a.rows_pad;
+      const size_t prow = pblock + rho;
+      float* po = a.part_o + pblock * DH + static_cast<size_t>(rho) * 8 + 4 * h;
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
           float4 v = make_float4(o[db][rb][4 * q4], o[db][rb][4 * q4 + 1], o[db][rb][4 * q4 + 2], o[db][rb][4 * q4 + 3]);
-          *reinterpret_cast<float4*>(po + 32 * db + 8 * q4 + 4 * h) = v;
+          *reinterpret_cast<float4*>(po + static_cast<size_t>(4 * db + q4) * a.rows_pad * 8) = v;
         }
       }
       if (h == 0) {
@@ -513,50 +517,72 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void tree_attention_kerne
 }
 
 // Merge of the split-KV partial results: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
-// One thread per (packed row, 4 head-dim values).
+// One thread per (packed row, 4 head-dim values).  A workgroup takes 256 / (DH / 4) rows.  It
+// reads the partial results in their slab order (thread = (slab, row, half): consecutive
+// threads, consecutive addresses) and turns its results through LDS to write whole output
+// rows.
 template <int DH>
 __global__ __launch_bounds__(kThreads) void tree_attention_combine_kernel(AttnArgs a) {
-  constexpr int QPR = DH / 4;
+  constexpr int QPR = DH / 4;            // threads per row
+  constexpr int RPW = kThreads / QPR;    // rows per workgroup
+  __shared__ bf16x4 s_out[RPW][QPR];
   const int bg = blockIdx.y;
   const int b = bg / a.Hkv;
   const int g = bg - b * a.Hkv;
   const int rows = a.n_nodes[b] * a.G;
-  const int idx = blockIdx.x * kThreads + threadIdx.x;
-  const int rho = idx / QPR;
-  const int c = idx - rho * QPR;
-  if (rho >= rows) return;
+  const int t = threadIdx.x;
+  const int h = t & 1;
+  const int r = (t >> 1) % RPW;
+  const int slab = t / (2 * RPW);        // 8 head-dim values: c = 2 * slab + h
+  const int c = 2 * slab + h;
+  const int rho = blockIdx.x * RPW + r;
+  if (blockIdx.x * RPW >= rows) return;  // the whole workgroup is past the end
+  const bool valid = rho < rows;
   int L = a.prefix_len[b];
   L = L < 0 ? 0 : (L > a.max_prefix_len ? a.max_prefix_len : L);
   const int T = (L + kKeyTile - 1) / kKeyTile + (a.n_nodes[b] + kKeyTile - 1) / kKeyTile;
   int ns = (T + a.tiles_per_split - 1) / a.tiles_per_split;  // splits that held at least one tile
   ns = ns < a.splits ? ns : a.splits;
-  const size_t base = static_cast<size_t>(bg) * a.splits * a.rows_pad + rho;
+  const size_t block0 = static_cast<size_t>(bg) * a.splits * a.rows_pad;
+  const size_t base = block0 + (valid ? rho : 0);
   // branch-free, so that the loads of all splits are in flight together
   float M = kNegInfF;
   for (int s = 0; s < ns; ++s) M = fmaxf(M, a.part_m[base + static_cast<size_t>(s) * a.rows_pad]);
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   float den = 0.f;
+  const size_t in_block = (static_cast<size_t>(slab) * a.rows_pad + (valid ? rho : 0)) * 8 + 4 * h;
 #pragma unroll 4
   for (int s = 0; s < ns; ++s) {
     const size_t pr = base + static_cast<size_t>(s) * a.rows_pad;
     const float ms = a.part_m[pr];
     const float ls = a.part_l[pr];
-    const float4 v = *reinterpret_cast<const float4*>(a.part_o + pr * DH + 4 * c);
+    const float4 v = *reinterpret_cast<const float4*>(
+        a.part_o + (block0 + static_cast<size_t>(s) * a.rows_pad) * DH + in_block);
     const float w = ms == kNegInfF ? 0.f : __builtin_amdgcn_exp2f(ms - M);   // an empty split stores zeros
     den += w * ls;
     acc.x += w * v.x; acc.y += w * v.y; acc.z += w * v.z; acc.w += w * v.w;
   }
   const float inv = 1.f / den;
-  const int node = rho / a.G;
-  const int j = rho - node * a.G;
-  const size_t orow = (static_cast<size_t>(b) * a.N_pad + node) * a.Hq + g * a.G + j;
   bf16x4 v;
   v[0] = static_cast<__bf16>(acc.x * inv);
   v[1] = static_cast<__bf16>(acc.y * inv);
   v[2] = static_cast<__bf16>(acc.z * inv);
   v[3] = static_cast<__bf16>(acc.w * inv);
-  *reinterpret_cast<bf16x4*>(a.out + orow * DH + 4 * c) = v;
-  if (a.out_lse && c == 0) a.out_lse[orow] = (M + __builtin_amdgcn_logf(den)) * 0.6931471805599453f;
+  s_out[r][c] = v;
+  if (a.out_lse && c == 0 && valid) {
+    const int node = rho / a.G;
+    const size_t orow = (static_cast<size_t>(b) * a.N_pad + node) * a.Hq + g * a.G + (rho - node * a.G);
+    a.out_lse[orow] = (M + __builtin_amdgcn_logf(den)) * 0.6931471805599453f;
+  }
+  __syncthreads();
+  const int r2 = t / QPR;
+  const int c2 = t - r2 * QPR;
+  const int rho2 = blockIdx.x * RPW + r2;
+  if (rho2 < rows) {
+    const int node = rho2 / a.G;
+    const size_t orow = (static_cast<size_t>(b) * a.N_pad + node) * a.Hq + g * a.G + (rho2 - node * a.G);
+    *reinterpret_cast<bf16x4*>(a.out + orow * DH + 4 * c2) = s_out[r2][c2];
+  }
 }
 
 template <int DH, int NW>
