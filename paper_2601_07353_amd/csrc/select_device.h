@@ -134,34 +134,52 @@ __device__ __forceinline__ unsigned long long select_sequence(const SelectArgs& 
   unsigned long long* my = s_key + tid * stride;
 
   // ---- path scores of the pool, as sortable keys (0 = no candidate)
+  // Loads first, arithmetic after, four candidates at a time: the loads of a group are all in
+  // flight together (one memory round trip per group, not one per candidate).
   unsigned long long anchor_key = 0ull;
   int tok_r[kRegCand];
   float prob_r[kRegCand];
   double score_r[kRegCand];
-  auto score_one = [&](int i, int* tok_out, float* prob_out, double* score_out) {
-    const int c = c_begin + i;
-    unsigned long long key = 0ull;
-    if (c < C) {
-      const int p = c / k;
-      const size_t ci = (base + fb + p) * k + (c - p * k);
-      const int tok = ld<AGENT, int32_t>(a.cand_token + ci);
-      if (prob_out) *prob_out = ld<AGENT, float>(a.cand_prob + ci);
-      const double s = ld<AGENT, double>(st.logp + base + fb + p) + ld<AGENT, double>(a.cand_edge_logp + ci);
-      if (tok_out) { *tok_out = tok; *score_out = s; }
-      if (tok >= 0 && s == s) {
-        key = sortable_u64(s);
-        if (key == 0ull) key = 1ull;
+  auto score_group = [&](int i0, int (&tok)[kRegCand], float (&prob)[kRegCand], double (&score)[kRegCand]) {
+    double edge[kRegCand], plogp[kRegCand];
+    // (no branch around the loads: a slot past the end reads candidate 0 of the frontier and
+    // drops it, so that nothing makes the compiler wait between two slots)
+#pragma unroll
+    for (int u = 0; u < kRegCand; ++u) {
+      const int c = c_begin + i0 + u;
+      const bool have = i0 + u < per && c < C;
+      const int cc = have ? c : 0;
+      const int p = cc / k;
+      const size_t ci = (base + fb + p) * k + (cc - p * k);
+      const int t_ = ld<AGENT, int32_t>(a.cand_token + ci);
+      const float pr_ = ld<AGENT, float>(a.cand_prob + ci);
+      plogp[u] = ld<AGENT, double>(st.logp + base + fb + p);
+      edge[u] = ld<AGENT, double>(a.cand_edge_logp + ci);
+      tok[u] = have ? t_ : -1;
+      prob[u] = pr_;
+    }
+#pragma unroll
+    for (int u = 0; u < kRegCand; ++u) {
+      if (i0 + u < per) {
+        const double sc = plogp[u] + edge[u];
+        score[u] = sc;
+        unsigned long long key = 0ull;
+        if (tok[u] >= 0 && sc == sc) {
+          key = sortable_u64(sc);
+          if (key == 0ull) key = 1ull;
+        }
+        my[i0 + u] = key;
+        anchor_key = key > anchor_key ? key : anchor_key;
       }
     }
-    my[i] = key;
-    anchor_key = key > anchor_key ? key : anchor_key;
   };
-#pragma unroll
-  for (int i = 0; i < kRegCand; ++i) {
-    tok_r[i] = -1; prob_r[i] = 0.f; score_r[i] = 0.0;
-    if (i < per) score_one(i, &tok_r[i], &prob_r[i], &score_r[i]);
+  score_group(0, tok_r, prob_r, score_r);
+  for (int i0 = kRegCand; i0 < per; i0 += kRegCand) {
+    int tok_x[kRegCand];
+    float prob_x[kRegCand];
+    double score_x[kRegCand];
+    score_group(i0, tok_x, prob_x, score_x);
   }
-  for (int i = kRegCand; i < per; ++i) score_one(i, nullptr, nullptr, nullptr);
   anchor_key = block_max_u64(anchor_key, s_red_u64);
 
   const bool init = d < a.init_layers;
