@@ -52,6 +52,9 @@ def parse_args():
     ap.add_argument("--sweep", action="store_true",
                     help="budget N, threshold mu and top-K-initialised layers swept on the c2 shape, with the "
                          "bookkeeping of Sec. 5.3 / App. C per variant (tree size, depth, rows scanned, accepted length)")
+    ap.add_argument("--scan-grid", action="store_true",
+                    help="the vocabulary scan alone (talon_expand_layer) on the c5 pool with every node a frontier row: "
+                         "HBM rate against the number of rows and the per-row k")
     ap.add_argument("--zipf-grid", action="store_true",
                     help="only run the paper's tree-construction micro-benchmark shape (App. E.6): latency of one "
                          "layer expansion over K parents with Zipf rows, exponent x vocabulary grid, 20 warm-ups and "
@@ -113,6 +116,9 @@ def main():
         return
     if args.zipf_grid:
         print(json.dumps({"zipf_grid": zipf_grid(T, torch, np, H)}))
+        return
+    if args.scan_grid:
+        print(json.dumps({"scan_grid": scan_grid(T, torch, np, H)}))
         return
     if args.sweep:
         print(json.dumps({"sweep": variant_sweep(T, torch, np, H, args.steps)}))
@@ -322,6 +328,41 @@ def accept_outcome(T, torch, np, cfg, slots, st, steps, elem):
     by = rows * cfg.V * elem
     return {"us_per_call": us, "target_rows": rows, "bytes": by, "GBps": by / (us * 1e-6) / 1e9,
             "accepted_mean": float(alen.float().mean().item())}
+
+
+def scan_grid(T, torch, np, H):
+    """talon_expand_layer alone on the c5 pool (16 sequences, 151936 bf16 logits per row), the
+    frontier set by hand to the first 32 / 128 / 256 nodes of every sequence, k = 1, 8, 16: what
+    the one-pass softmax + top-k scan sustains when nothing else is in the launch.  Two copies
+    of the 1.24 GB pool alternate, so no launch finds its rows in a cache."""
+    from workloads import CONFIGS
+    cfg = CONFIGS["c5"]
+    dev = H.to_device_logits(H.build_pool(cfg, [cfg.seed] * cfg.B))
+    other = dev.clone()
+    out = []
+    for rows_per_seq in (256, 128, 32):
+        for k in (1, 8, 16):
+            st = T.TreeState(cfg.B, cfg.N)
+            st.n_nodes.fill_(rows_per_seq); st.frontier_begin.fill_(0); st.frontier_count.fill_(rows_per_seq)
+            st.status.fill_(0)
+            cand = T.Candidates(cfg.B, st.N_pad, k)
+            ws = T.make_expand_workspace(cfg.B, st.N_pad, cfg.V, k, T.TALON_DTYPE_BF16)
+            for _ in range(2):
+                T.talon_expand_layer(dev, st, k, cand, ws)
+                T.talon_expand_layer(other, st, k, cand, ws)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = 10
+            e0.record()
+            for i in range(reps):
+                T.talon_expand_layer(dev if i % 2 == 0 else other, st, k, cand, ws)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / reps
+            by = cfg.B * rows_per_seq * cfg.V * 2
+            out.append({"rows": cfg.B * rows_per_seq, "k": k, "us": us, "bytes": by, "GBps": by / us / 1e3,
+                        "frac_of_8TBps": by / us / 1e3 / HBM_PEAK_GBS})
+    return out
 
 
 def variant_sweep(T, torch, np, H, steps):
