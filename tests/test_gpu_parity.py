@@ -195,6 +195,51 @@ def test_launch_forms_share_one_workspace():
         same(snapshot(), want[which])
 
 
+@pytest.mark.parametrize("fused", [True, False])
+def test_dense_frontier_batches_with_padded_rows(fused):
+    """The layout a serving loop has: after every layer the draft model's logits exist for the
+    new frontier only, as a dense batch [B][frontier rows][padded row] (TALON_ROWS_BY_FRONTIER,
+    row stride larger than the vocabulary, garbage in the padding).  One call per layer on a
+    freshly gathered batch must build the tree the oracle builds."""
+    import torch
+    import paper_2601_07353_amd as T
+    cfg = small(name="dense", V=20011, logits_dtype="bf16", K=6, N=70, Dmax=9, B=3,
+                recipe=(("gauss", 4.0, 8.0), ("gauss", 0.5, 1.0), ("gauss", 2.0, 6.0)))
+    seeds = admissible_seeds(cfg)
+    pool = H.build_pool(cfg, seeds)
+    ref = H.run_oracle_step(cfg, seeds, pool=pool, with_attention=False)
+    pool_dev = H.to_device_logits(pool)                      # [B][N_pad][V], only used to gather from
+    stride = (cfg.V + 8 + 63) // 64 * 64                     # padded rows
+    st = T.TreeState(cfg.B, cfg.N)
+    cand = T.Candidates(cfg.B, st.N_pad, cfg.K)
+    ws = T.make_expand_workspace(cfg.B, st.N_pad, cfg.V, cfg.K, T.TALON_DTYPE_BF16)
+    T.talon_tree_init(st, torch.from_numpy(H.root_tokens(cfg)).cuda())
+    for d in range(cfg.Dmax):
+        begin = st.frontier_begin.cpu().numpy()
+        count = st.frontier_count.cpu().numpy()
+        done = (st.status.cpu().numpy() & 3) != 0
+        if done.all():
+            break
+        fmax = max(1, int(count.max()))
+        dense = torch.full((cfg.B, fmax, stride), 30000.0, dtype=torch.bfloat16, device="cuda")   # padding would win any max
+        for b in range(cfg.B):
+            if not done[b]:
+                dense[b, :count[b], :cfg.V] = pool_dev[b, begin[b]:begin[b] + count[b]]
+        if fused:
+            T.talon_expand_select_layer(dense, st, cfg.K, cfg.mu, cfg.K, 1, cfg.Dmax, cand, ws, layer=d,
+                                        row_mode=T.TALON_ROWS_BY_FRONTIER, vocab=cfg.V)
+        else:
+            T.talon_expand_layer(dense, st, cfg.K, cand, ws, row_mode=T.TALON_ROWS_BY_FRONTIER, layer=d, vocab=cfg.V)
+            T.talon_select_budget(st, cfg.K, cand, cfg.mu, cfg.K, 1, cfg.Dmax)
+        torch.cuda.synchronize()
+    n = st.n_nodes.cpu().numpy()
+    for b, t in enumerate(ref["trees"]):
+        assert int(n[b]) == t.n
+        np.testing.assert_array_equal(st.token[b, :t.n].cpu().numpy(), np.asarray(t.token, dtype=np.int32))
+        np.testing.assert_array_equal(st.parent[b, :t.n].cpu().numpy(), np.asarray(t.parent, dtype=np.int32))
+        np.testing.assert_allclose(np.exp(st.logp[b, :t.n].cpu().numpy()), t.confidence(), rtol=H.PROB_RTOL, atol=0)
+
+
 @pytest.mark.parametrize("mode", ["split", "fused", "tree"])
 def test_layerwise_entry_points_against_oracle(mode):
     """The per-layer entry points (scan and selection as two launches, or as one) on a batch
