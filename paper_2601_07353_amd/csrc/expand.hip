@@ -922,7 +922,7 @@ __global__ __launch_bounds__(kThreads, 3) void expand_tree_kernel(ExpandArgs a) 
       atomicOr(&a.status[i], TALON_STATUS_ABORTED);
     }
   }
-  if (t <= kExitGroups) store_agent(a.exit_ticket + t, 0u);
+  for (int i = t; i <= kExitGroups; i += kThreads) store_agent(a.exit_ticket + i, 0u);
 }
 
 __global__ __launch_bounds__(kThreads) void fill_zero_kernel(uint32_t* p, size_t n) {
