@@ -186,6 +186,28 @@ int talon_build_tree(const int32_t* root_token, const void* logits, int dtype, i
                      void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Alg. 2 with the candidate pool exactly as the listing writes it (Sec. 5.2, "Hybrid Expansion
+ * Strategy" and "Budget Check"): S_d holds every token of every frontier row, with no per-row
+ * cap, for any budget N <= TALON_N_MAX.  The calls above cap a row at k <= TALON_K_MAX
+ * candidates, which gives the same tree whenever k >= N - |T|; this is the general, slower
+ * form: per layer one vocabulary scan for the row statistics, then per frontier row the
+ * tokens that pass the gate (at most the remaining budget of them, found by a radix select
+ * over the row when more pass), then per sequence the budget check over what the rows kept.
+ * Runs `layers` >= 1 layers from the tree state as it stands (1: one layer between two draft
+ * passes; >= max_depth: the whole loop); sequences that are finished are skipped.  Same tree
+ * state, node order, ties and status bits as talon_expand_select_layer; no candidate
+ * arrays are written.
+ *   `workspace`: talon_literal_workspace_bytes bytes of device memory, no initialisation
+ *   needed; it must not be shared with a call running at the same time.
+ *   Errors: as talon_expand_layer and talon_select_budget (k does not apply).
+ */
+size_t talon_literal_workspace_bytes(int32_t B, int32_t N_pad, int32_t vocab, int dtype);
+int talon_expand_literal(const void* logits, int dtype, int64_t row_stride, int64_t seq_stride,
+                         int row_mode, int32_t layers, const talon_tree_state* st, int32_t vocab,
+                         float mu, int32_t K_init, int32_t init_layers, int32_t max_depth,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Measurement hook (no counterpart in the paper).  While enabled, talon_expand_tree and
  * talon_expand_select_layer record a HIP event on the launch stream before and after every
  * fused scan launch; talon_profile_read waits for them, writes the first `capacity`

@@ -4,4 +4,4 @@ hand-written HIP kernels behind the C ABI of include/talon.h.  This package hold
 kernels (csrc/), their build script and the ctypes binding."""
 from .binding import *  # noqa: F401,F403
 from .binding import (Candidates, TalonError, TreeState, load_library, make_expand_workspace,
-                      make_verify_workspace)  # noqa: F401
+                      make_literal_workspace, make_verify_workspace)  # noqa: F401

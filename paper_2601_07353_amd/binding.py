@@ -36,6 +36,7 @@ EXPORTS = [
     "talon_last_error_string", "talon_tree_init", "talon_expand_workspace_bytes",
     "talon_expand_workspace_init", "talon_expand_layer", "talon_select_budget", "talon_expand_select_layer",
     "talon_expand_tree", "talon_build_tree", "talon_profile_scan_launches", "talon_profile_read", "talon_probe_read", "talon_probe_mfma", "talon_verify_workspace_bytes", "talon_target_argmax",
+    "talon_literal_workspace_bytes", "talon_expand_literal",
     "talon_greedy_accept", "talon_compact_kv", "talon_prune_tree",
     "talon_build_tree_mask", "talon_tree_attention_workspace_bytes", "talon_tree_attention",
 ]
@@ -86,6 +87,10 @@ def load_library() -> ctypes.CDLL:
                                      c_float, c_int32, c_int32, c_int32, P, P, P, P, P, P, P, P, c_size_t, P]
     lib.talon_profile_scan_launches.argtypes = [c_int]
     lib.talon_profile_read.argtypes = [POINTER(c_float), c_int32, POINTER(c_int32)]
+    lib.talon_literal_workspace_bytes.restype = c_size_t
+    lib.talon_literal_workspace_bytes.argtypes = [c_int32, c_int32, c_int32, c_int]
+    lib.talon_expand_literal.argtypes = [P, c_int, c_int64, c_int64, c_int, c_int32, POINTER(_CTreeState), c_int32,
+                                         c_float, c_int32, c_int32, c_int32, P, c_size_t, P]
     lib.talon_verify_workspace_bytes.restype = c_size_t
     lib.talon_verify_workspace_bytes.argtypes = [c_int32, c_int32, c_int32, c_int]
     lib.talon_target_argmax.argtypes = [P, c_int, c_int64, c_int64, POINTER(_CTreeState), c_int32, P, P, P, P, c_size_t, P]
@@ -291,6 +296,22 @@ def talon_tree_attention(q, k_prefix, v_prefix, k_tree, v_tree, mask, n_nodes, p
         _ptr(q), _ptr(k_prefix), _ptr(v_prefix), _ptr(k_tree), _ptr(v_tree), _ptr(mask), _ptr(n_nodes),
         _ptr(prefix_len), B, N_pad, Hq, Hkv, Dh, max_prefix_len, sb, st_, sh, c_float(scale), _ptr(out),
         _ptr(out_lse), _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def make_literal_workspace(B, N_pad, vocab, dtype) -> torch.Tensor:
+    nb = load_library().talon_literal_workspace_bytes(B, N_pad, vocab, dtype)
+    if nb == 0:
+        raise TalonError(TALON_ERR_INVALID_ARG, load_library().talon_last_error_string().decode())
+    return torch.empty(nb, dtype=torch.uint8, device="cuda")
+
+
+def talon_expand_literal(logits, st: TreeState, layers, mu, K_init, init_layers, max_depth, workspace,
+                         row_mode=TALON_ROWS_BY_NODE, vocab=None, stream=None):
+    dt, row_stride, seq_stride, V = _logits_meta(logits)
+    _check(load_library().talon_expand_literal(
+        _ptr(logits), dt, row_stride, seq_stride, row_mode, layers, ctypes.byref(st.c), V if vocab is None else vocab,
+        c_float(mu), K_init, init_layers, max_depth, _ptr(workspace), workspace.numel() * workspace.element_size(),
+        _stream(stream)))
 
 
 def make_verify_workspace(B, N_pad, vocab, dtype) -> torch.Tensor:

@@ -13,7 +13,7 @@ LIB_DIR = os.path.join(PKG, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libtalon.so")
 OBJ_DIR = os.path.join(PKG, "_build")
 
-SOURCES = ["api.hip", "expand.hip", "select.hip", "attention.hip", "accept.hip", "calibrate.hip"]
+SOURCES = ["api.hip", "expand.hip", "select.hip", "literal.hip", "attention.hip", "accept.hip", "calibrate.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -202,6 +202,31 @@ int verify_layout(int B, int N_pad, int vocab, int dtype, VerifyLayout* V) {
   return TALON_OK;
 }
 
+// Workspace of talon_expand_literal: the scan's workspace for k = 1 and its outputs, the
+// per-sequence plan of a layer, and the survivors of every frontier row.
+struct LiteralLayout {
+  ExpandLayout scan;
+  size_t off_token, off_logit, off_prob, off_edge, off_max, off_lse, off_plan, off_count, off_keys, total;
+};
+
+int literal_layout(int B, int N_pad, int vocab, int dtype, LiteralLayout* V) {
+  int rc = expand_layout(B, N_pad, vocab, 1, dtype, &V->scan);
+  if (rc) return rc;
+  const size_t rows = static_cast<size_t>(B) * N_pad;
+  size_t o = V->scan.total;
+  V->off_token = o; o += align_up(rows * sizeof(int32_t), 256);
+  V->off_logit = o; o += align_up(rows * sizeof(float), 256);
+  V->off_prob = o;  o += align_up(rows * sizeof(float), 256);
+  V->off_edge = o;  o += align_up(rows * sizeof(double), 256);
+  V->off_max = o;   o += align_up(rows * sizeof(float), 256);
+  V->off_lse = o;   o += align_up(rows * sizeof(double), 256);
+  V->off_plan = o;  o += align_up(static_cast<size_t>(B) * sizeof(LiteralPlan), 256);
+  V->off_count = o; o += align_up(rows * sizeof(int32_t), 256);
+  V->off_keys = o;  o += align_up(rows * kLiteralRowCap * sizeof(uint64_t), 256);
+  V->total = o;
+  return TALON_OK;
+}
+
 }  // namespace
 }  // namespace talon
 
@@ -387,6 +412,67 @@ int talon_build_tree(const int32_t* root_token, const void* logits, int dtype, i
   return run_fused_layers(true, root_token, mask, logits, dtype, row_stride, seq_stride, row_mode, 0, layers, st, vocab,
                           k, mu, K_init, init_layers, max_depth, cand_token, cand_logit, cand_prob, cand_edge_logp,
                           row_max, row_lse, workspace, workspace_bytes, stream);
+}
+
+size_t talon_literal_workspace_bytes(int32_t B, int32_t N_pad, int32_t vocab, int dtype) {
+  LiteralLayout V;
+  if (literal_layout(B, N_pad, vocab, dtype, &V)) return 0;
+  return V.total;
+}
+
+int talon_expand_literal(const void* logits, int dtype, int64_t row_stride, int64_t seq_stride, int row_mode,
+                         int32_t layers, const talon_tree_state* st, int32_t vocab, float mu, int32_t K_init,
+                         int32_t init_layers, int32_t max_depth, void* workspace, size_t workspace_bytes,
+                         void* stream) {
+  int rc = check_state(st);
+  if (rc) return rc;
+  LiteralLayout V;
+  rc = literal_layout(st->B, st->N_pad, vocab, dtype, &V);
+  if (rc) return rc;
+  char* w = static_cast<char*>(workspace);
+  ExpandLayout L;
+  // the scan's own checks (pointers, alignment, strides), its outputs in the workspace
+  rc = check_expand_args(logits, dtype, row_stride, seq_stride, row_mode, st, vocab, 1, w ? w + V.off_token : nullptr,
+                         w ? w + V.off_logit : nullptr, w ? w + V.off_prob : nullptr, w ? w + V.off_edge : nullptr,
+                         w ? w + V.off_max : nullptr, w ? w + V.off_lse : nullptr, workspace, workspace_bytes, &L);
+  if (rc) return rc;
+  if (workspace_bytes < V.total) {
+    set_error("workspace of %zu bytes is smaller than the %zu needed", workspace_bytes, V.total);
+    return TALON_ERR_WORKSPACE;
+  }
+  if (!(mu > 0.f && mu <= 1.f)) { set_error("mu=%g outside (0, 1]", (double)mu); return TALON_ERR_INVALID_ARG; }
+  if (K_init < 1) { set_error("K_init=%d must be >= 1", K_init); return TALON_ERR_INVALID_ARG; }
+  if (init_layers < 0) { set_error("init_layers=%d must be >= 0", init_layers); return TALON_ERR_INVALID_ARG; }
+  if (max_depth < 1) { set_error("max_depth=%d must be >= 1", max_depth); return TALON_ERR_INVALID_ARG; }
+  if (layers < 1) { set_error("layers=%d must be >= 1", layers); return TALON_ERR_INVALID_ARG; }
+  const ExpandArgs ea = make_expand_args(logits, row_stride, seq_stride, row_mode, st, vocab, 1,
+                                         reinterpret_cast<int32_t*>(w + V.off_token), reinterpret_cast<float*>(w + V.off_logit),
+                                         reinterpret_cast<float*>(w + V.off_prob), reinterpret_cast<double*>(w + V.off_edge),
+                                         reinterpret_cast<float*>(w + V.off_max), reinterpret_cast<double*>(w + V.off_lse),
+                                         workspace, L);
+  LiteralArgs la;
+  la.logits = logits; la.row_stride = row_stride; la.seq_stride = seq_stride; la.row_mode = row_mode; la.vocab = vocab;
+  la.st = *st; la.log_mu = log(static_cast<double>(mu)); la.K_init = K_init; la.init_layers = init_layers;
+  la.max_depth = max_depth;
+  la.top_logit = reinterpret_cast<const float*>(w + V.off_logit);
+  la.row_lse = reinterpret_cast<const double*>(w + V.off_lse);
+  la.plan = reinterpret_cast<LiteralPlan*>(w + V.off_plan);
+  la.row_count = reinterpret_cast<int32_t*>(w + V.off_count);
+  la.row_key = reinterpret_cast<unsigned long long*>(w + V.off_keys);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // the scan's row tickets start at zero and every launch leaves them so
+  rc = check_hip(launch_fill_zero(w + L.off_ticket, L.off_max - L.off_ticket, s), "ticket fill launch");
+  if (rc) return rc;
+  // a tree of N nodes has at most N - 1 layers; a layer of finished sequences costs four empty launches
+  const int most = st->N > 1 ? st->N - 1 : 0;
+  const int run = layers < most ? layers : most;
+  for (int d = 0; d < run; ++d) {
+    rc = check_hip(launch_expand(ea, dtype, expand_grid(st, L.chunks, -1, 1, 1, 0), false, s), "scan launch");
+    if (rc) return rc;
+    rc = check_hip(launch_literal_layer(la, dtype, s), "literal layer launch");
+    if (rc) return rc;
+  }
+  return TALON_OK;
 }
 
 int talon_profile_scan_launches(int enable) {

@@ -83,6 +83,28 @@ struct ExpandArgs {
   const int32_t* root_token;   // optional [B]
 };
 
+// Uncapped ("paper-literal") layer of Alg. 2: the pool of a parent is its whole row.
+constexpr int kLiteralRowCap = 256;   // survivors of one row that can still be chosen: at most N - 1 <= 255
+struct LiteralPlan {   // per sequence, written by the plan kernel of a layer
+  double thr;          // gate threshold on the path score, log(mu) + anchor (-inf on top-K layers)
+  int32_t active, F, fb, n, d, limit;
+  uint32_t status;
+  int32_t pad;
+};
+struct LiteralArgs {
+  const void* logits;
+  int64_t row_stride, seq_stride;
+  int row_mode, vocab;
+  talon_tree_state st;
+  double log_mu;
+  int K_init, init_layers, max_depth;
+  const float* top_logit;          // [B*N_pad] largest logit of a scanned row
+  const double* row_lse;           // [B*N_pad]
+  LiteralPlan* plan;               // [B]
+  int32_t* row_count;              // [B*N_pad] survivors kept of a row
+  unsigned long long* row_key;     // [B*N_pad][kLiteralRowCap] their keys (sortable logit << 32 | ~token)
+};
+
 struct AttnArgs {
   const uint16_t* q;
   const uint16_t* k_prefix;
@@ -128,6 +150,7 @@ int expand_tree_max_grid(int dtype);
 hipError_t launch_expand(const ExpandArgs& a, int dtype, int grid, bool fused, hipStream_t s);
 hipError_t launch_select(const SelectArgs& a, hipStream_t s);
 hipError_t launch_mask(const talon_tree_state& st, uint64_t* mask, hipStream_t s);
+hipError_t launch_literal_layer(const LiteralArgs& a, int dtype, hipStream_t s);
 hipError_t launch_attention(const AttnArgs& a, hipStream_t s);
 
 int expand_chunk_elems(int dtype);

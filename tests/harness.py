@@ -36,7 +36,8 @@ def root_tokens(cfg: WorkloadConfig) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------- oracle side
-def oracle_tree(cfg: WorkloadConfig, pool_b: np.ndarray, root: int, init_layers: int = 1, mu=None, K_init=None):
+def oracle_tree(cfg: WorkloadConfig, pool_b: np.ndarray, root: int, init_layers: int = 1, mu=None, K_init=None,
+                cap=None):
     from oracle import talon_oracle as O
     cache = {}
 
@@ -47,11 +48,12 @@ def oracle_tree(cfg: WorkloadConfig, pool_b: np.ndarray, root: int, init_layers:
 
     mu = float(np.float32(cfg.mu if mu is None else mu))  # the ABI takes mu as a float
     K_init = cfg.K if K_init is None else K_init
-    return O.build_tree(row_of, int(root), N=cfg.N, K=K_init, mu=mu, cap=cfg.K, Dmax=cfg.Dmax,
+    return O.build_tree(row_of, int(root), N=cfg.N, K=K_init, mu=mu, cap=cfg.K if cap is None else cap, Dmax=cfg.Dmax,
                         init_layers=init_layers)
 
 
-def find_admissible_seed(cfg: WorkloadConfig, b: int, base_seed: int, tol: float = MARGIN_TOL, max_tries: int = 64):
+def find_admissible_seed(cfg: WorkloadConfig, b: int, base_seed: int, tol: float = MARGIN_TOL, max_tries: int = 64,
+                         **tree_kw):
     """First seed >= base_seed whose oracle tree for sequence b leaves every cross-parent
     decision a margin > tol, so that an fp32 log-sum-exp cannot change the topology."""
     roots = root_tokens(cfg)
@@ -64,7 +66,7 @@ def find_admissible_seed(cfg: WorkloadConfig, b: int, base_seed: int, tol: float
                     rows[i] = logits_row(cfg, s, b, i)
                 return rows[i]
 
-        t = oracle_tree(cfg, Lazy(), roots[b])
+        t = oracle_tree(cfg, Lazy(), roots[b], **tree_kw)
         if t.margin > tol:
             return s, t
     raise RuntimeError("no admissible seed found for %s sequence %d" % (cfg.name, b))
@@ -149,6 +151,37 @@ def run_gpu_expand(cfg: WorkloadConfig, pool_dev, init_layers=1, mu=None, K_init
         T.talon_build_tree(roots, pool_dev, st, cfg.K, mu, K_init, init_layers, cfg.Dmax, cand, ws, mask=mask)
     torch.cuda.synchronize()
     return st, cand, ws, mask
+
+
+def run_gpu_literal(cfg: WorkloadConfig, pool: np.ndarray, K_init: int, init_layers: int = 1, mu=None,
+                    layer_by_layer: bool = False, row_mode_frontier: bool = False):
+    """Alg. 2 with the uncapped pool through talon_expand_literal: talon_tree_init, the loop (one
+    call, or one call per layer), talon_build_tree_mask."""
+    import torch
+    import paper_2601_07353_amd as T
+    pool_dev = to_device_logits(pool)
+    st = T.TreeState(cfg.B, cfg.N)
+    dt = T.TALON_DTYPE_F32 if cfg.logits_dtype == "f32" else T.TALON_DTYPE_BF16
+    ws = T.make_literal_workspace(cfg.B, st.N_pad, cfg.V, dt)
+    ws.fill_(0xA5)   # the call must not depend on what the workspace holds
+    roots = torch.from_numpy(root_tokens(cfg)).cuda()
+    mu = cfg.mu if mu is None else mu
+    T.talon_tree_init(st, roots)
+    if layer_by_layer:
+        for _ in range(cfg.Dmax):
+            T.talon_expand_literal(pool_dev, st, 1, mu, K_init, init_layers, cfg.Dmax, ws)
+    else:
+        T.talon_expand_literal(pool_dev, st, cfg.Dmax, mu, K_init, init_layers, cfg.Dmax, ws)
+    mask = torch.zeros(cfg.B, st.N_pad, st.N_pad // 64, dtype=torch.int64, device="cuda")
+    T.talon_build_tree_mask(st, mask)
+    torch.cuda.synchronize()
+    return {
+        "token": st.token.cpu().numpy(), "parent": st.parent.cpu().numpy(), "depth": st.depth.cpu().numpy(),
+        "prob": st.prob.cpu().numpy(), "logp": st.logp.cpu().numpy(), "n_nodes": st.n_nodes.cpu().numpy(),
+        "status": st.status.cpu().numpy(), "depth_cur": st.depth_cur.cpu().numpy(),
+        "frontier_begin": st.frontier_begin.cpu().numpy(), "frontier_count": st.frontier_count.cpu().numpy(),
+        "mask": mask.cpu().numpy().view(np.uint64),
+    }
 
 
 def run_gpu_step(cfg: WorkloadConfig, seeds=None, pool=None, attn=None, with_attention=True, init_layers=1,

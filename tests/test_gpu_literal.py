@@ -1,0 +1,81 @@
+"""Alg. 2 with the candidate pool as the listing writes it (every token of every frontier row)
+through talon_expand_literal, against the oracle.
+
+The oracle runs with a per-row cap of N - 1: a layer never takes more than N - |T| <= N - 1
+nodes, so that pool gives the uncapped tree (tests/test_oracle_pins.py checks that equivalence
+against the full-vocabulary pool by brute force).  Seeds are admissible for that pool (every
+cross-parent decision leaves a margin above the harness tolerance); topology, tokens, depths,
+counters, status bits and the mask are then compared bit for bit, probabilities to 1e-5."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+from tests import harness as H
+from workloads import CONFIGS
+
+pytestmark = pytest.mark.gpu
+
+CASES = {
+    # fp32 rows so flat that one parent receives more than 64 children: beyond the capped path
+    "flat-f32-n200": dataclasses.replace(CONFIGS["c1"], name="literal-flat", V=4099, N=200, Dmax=8, K=4,
+                                         recipe=("gauss", 0.3, 0.5)),
+    # tiny fp32 shape, ragged vocabulary, K_init larger than the per-row cap of the fast path's config
+    "tiny-f32": dataclasses.replace(CONFIGS["c1"], name="literal-tiny", V=1021, N=16, K=3),
+    # Qwen3-8B-shaped rows, N = 128: one low-temperature and one high-temperature sequence
+    "qwen-bf16-n128": dataclasses.replace(CONFIGS["c3"], name="literal-c3", B=2,
+                                          recipe=(("gauss", 6.0, 8.0), ("gauss", 0.5, 1.0))),
+    # the stress recipe (Zipf-peaked and near-uniform rows), N = 256, three sequences
+    "zipf-bf16-n256": dataclasses.replace(CONFIGS["c5"], name="literal-n256", B=3, V=32003),
+}
+
+
+def _case(cfg, init_layers=1, layer_by_layer=False):
+    cap = cfg.N - 1
+    seeds, trees = [], []
+    for b in range(cfg.B):
+        s, _ = H.find_admissible_seed(cfg, b, cfg.seed + 100 * b, cap=cap, init_layers=init_layers)
+        seeds.append(s)
+    pool = H.build_pool(cfg, seeds)
+    roots = H.root_tokens(cfg)
+    from oracle import talon_oracle as O
+    masks = []
+    for b in range(cfg.B):
+        t = H.oracle_tree(cfg, pool[b], roots[b], init_layers=init_layers, cap=cap)
+        trees.append(t)
+        masks.append(O.build_tree_mask(t.parent))
+    gpu = H.run_gpu_literal(cfg, pool, cfg.K, init_layers=init_layers, layer_by_layer=layer_by_layer)
+    H.compare_tree(cfg, gpu, trees, check_rows=False)
+    H.compare_mask(cfg, gpu, masks)
+    return trees
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_uncapped_pool_matches_the_oracle(name):
+    trees = _case(CASES[name])
+    fan = max(int(np.bincount(np.asarray(t.parent[1:]), minlength=t.n).max()) for t in trees)
+    print(name, "largest fan-out", fan, "nodes", [t.n for t in trees])
+    if name == "flat-f32-n200":
+        assert fan > 64   # the case the capped path cannot build
+
+
+def test_one_layer_per_call_and_two_top_k_layers():
+    _case(CASES["qwen-bf16-n128"], init_layers=2, layer_by_layer=True)
+    _case(CASES["tiny-f32"], init_layers=0, layer_by_layer=True)
+
+
+def test_capped_path_agrees_where_its_cap_suffices():
+    """N = 60, k = 59: the fast path's tree is the uncapped tree, so both entry points must
+    produce the same arrays, bit for bit (probabilities included: same arithmetic)."""
+    cfg = dataclasses.replace(CONFIGS["c2"], name="c2-cap59", K=59, V=32003)
+    seeds = [H.find_admissible_seed(cfg, 0, cfg.seed, K_init=10)[0]]
+    pool = H.build_pool(cfg, seeds)
+    fast = H.run_gpu_step(cfg, seeds=seeds, pool=pool, with_attention=False, K_init=10)
+    lit = H.run_gpu_literal(cfg, pool, 10)
+    n = int(fast["n_nodes"][0])
+    assert int(lit["n_nodes"][0]) == n
+    for name in ("token", "parent", "depth", "prob", "logp"):
+        np.testing.assert_array_equal(lit[name][0, :n], fast[name][0, :n], err_msg=name)
+    for name in ("status", "depth_cur", "frontier_begin", "frontier_count"):
+        assert int(lit[name][0]) == int(fast[name][0]), name
+    np.testing.assert_array_equal(lit["mask"][0], fast["mask"][0])
