@@ -168,6 +168,35 @@ def test_verification_and_prune_calls_reject_bad_arguments(lib):
     assert lib.talon_probe_mfma(0, 10, P, None, None) == T.TALON_ERR_INVALID_ARG
 
 
+def test_literal_call_rejects_bad_arguments(lib):
+    st = fake_state()
+    need = lib.talon_literal_workspace_bytes(1, 64, 1024, 1)
+    assert need > lib.talon_expand_workspace_bytes(1, 64, 1024, 1, 1) + 64 * 256 * 8
+    assert lib.talon_literal_workspace_bytes(1, 60, 1024, 1) == 0
+    assert lib.talon_literal_workspace_bytes(1, 64, 0, 1) == 0
+
+    def call(logits=P, dtype=1, row_stride=1024, layers=1, state=st, vocab=1024, mu=0.03, K_init=4, init_layers=1,
+             max_depth=8, ws=P, ws_bytes=1 << 30):
+        return lib.talon_expand_literal(logits, dtype, row_stride, 1024 * 64, 0, layers,
+                                        ctypes.byref(state) if state is not None else None, vocab, ctypes.c_float(mu),
+                                        K_init, init_layers, max_depth, ws, ws_bytes, None)
+
+    assert call(logits=0) == T.TALON_ERR_INVALID_ARG
+    assert call(logits=P + 4) == T.TALON_ERR_INVALID_ARG
+    assert call(dtype=7) == T.TALON_ERR_UNSUPPORTED
+    assert call(row_stride=1001) == T.TALON_ERR_INVALID_ARG
+    assert call(layers=0) == T.TALON_ERR_INVALID_ARG and "layers" in err(lib)
+    assert call(state=None) == T.TALON_ERR_INVALID_ARG
+    assert call(vocab=0) == T.TALON_ERR_INVALID_ARG
+    assert call(mu=0.0) == T.TALON_ERR_INVALID_ARG and "mu" in err(lib)
+    assert call(mu=1.5) == T.TALON_ERR_INVALID_ARG
+    assert call(K_init=0) == T.TALON_ERR_INVALID_ARG
+    assert call(init_layers=-1) == T.TALON_ERR_INVALID_ARG
+    assert call(max_depth=0) == T.TALON_ERR_INVALID_ARG
+    assert call(ws=0) == T.TALON_ERR_INVALID_ARG
+    assert call(ws_bytes=need - 1) == T.TALON_ERR_WORKSPACE
+
+
 def test_profile_hook_host_side(lib):
     n = ctypes.c_int32(-1)
     assert lib.talon_profile_read(None, 0, None) == T.TALON_ERR_INVALID_ARG

@@ -79,3 +79,91 @@ def test_capped_path_agrees_where_its_cap_suffices():
     for name in ("status", "depth_cur", "frontier_begin", "frontier_count"):
         assert int(lit[name][0]) == int(fast[name][0]), name
     np.testing.assert_array_equal(lit["mask"][0], fast["mask"][0])
+
+
+# ----------------------------------------------------------------------------- degenerate rows
+def _compare_pool(cfg, pool, need_margin=True, **kw):
+    from oracle import talon_oracle as O
+    from tests.test_gpu_parity import small  # noqa: F401  (shape helper shared with the capped path's tests)
+    roots = H.root_tokens(cfg)
+    trees = [H.oracle_tree(cfg, pool[b], roots[b], cap=max(cfg.N - 1, 1), **kw) for b in range(cfg.B)]
+    if need_margin and min(t.margin for t in trees) <= H.MARGIN_TOL:
+        pytest.skip("not admissible")
+    gpu = H.run_gpu_literal(cfg, pool, cfg.K, **kw)
+    H.compare_tree(cfg, gpu, trees, check_rows=False)
+    H.compare_mask(cfg, gpu, [O.build_tree_mask(t.parent) for t in trees])
+    return gpu, trees
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_constant_rows_every_candidate_ties(dtype):
+    """Every logit equal: all scores of a layer tie exactly, in any arithmetic.  The order
+    (parent ascending, token ascending) must decide: the first child of the root receives the
+    whole remaining budget, 114 children with tokens 0..113."""
+    from tests.test_gpu_parity import custom_pool, small
+    cfg = small(name="lit-const", V=20011, logits_dtype=dtype, K=5, N=120, Dmax=6)
+    pool = custom_pool(cfg, lambda b, i: np.full(cfg.V, 1.5))
+    gpu, _ = _compare_pool(cfg, pool, need_margin=False)
+    assert list(gpu["token"][0, 1:6]) == [0, 1, 2, 3, 4]
+    assert list(gpu["parent"][0, 6:120]) == [1] * 114
+    assert list(gpu["token"][0, 6:120]) == list(range(114))
+
+
+def test_two_valued_rows_cut_inside_a_run_of_equal_logits():
+    """Rows with two distinct values: the budget cut falls inside a long run of equal logits of
+    one parent, after whole runs of its siblings."""
+    from tests.test_gpu_parity import custom_pool, small
+    cfg = small(name="lit-two", V=9001, logits_dtype="f32", K=3, N=150, Dmax=6, mu=0.5)
+
+    def fill(b, i):
+        x = np.full(cfg.V, 0.0)
+        x[(7 * i) % 50::50] = 2.0 + 0.01 * i           # 181 high entries, their level depends on the node
+        return x
+
+    _compare_pool(cfg, custom_pool(cfg, fill))
+
+
+def test_sorted_rows_and_neg_inf_entries():
+    from tests.test_gpu_parity import custom_pool, small
+    cfg = small(name="lit-sorted", V=17003, logits_dtype="f32", K=8, N=90, Dmax=8)
+    rng = np.random.default_rng(5)
+
+    def fill(b, i):
+        if i % 3 == 0:
+            return np.linspace(-3, 3, cfg.V) * (1 + 0.1 * i)
+        if i % 3 == 1:
+            return np.linspace(4, -4, cfg.V) * (1 + 0.05 * i)
+        x = np.full(cfg.V, -np.inf)
+        idx = rng.choice(cfg.V, size=5, replace=False)
+        x[idx] = rng.normal(size=5)
+        return x
+
+    _compare_pool(cfg, custom_pool(cfg, fill))
+
+
+def test_vocab_smaller_than_the_first_layer():
+    from tests.test_gpu_parity import small
+    cfg = small(name="lit-tinyv", V=8, logits_dtype="f32", K=12, N=40, Dmax=4, mu=1e-30)
+    _compare_pool(cfg, H.build_pool(cfg, [cfg.seed]))
+
+
+def test_nan_row_sets_status_and_stops_sequence():
+    from tests.test_gpu_parity import small
+    cfg = small(name="lit-nan", V=5000, logits_dtype="f32", K=3, N=20, Dmax=6, B=2)
+    seeds = [cfg.seed, cfg.seed]
+    pool = H.build_pool(cfg, seeds)
+    pool[1, 2, 1234] = np.nan
+    gpu = H.run_gpu_literal(cfg, pool, cfg.K)
+    assert int(gpu["status"][1]) & 4
+    assert int(gpu["n_nodes"][1]) == 1 + cfg.K          # stopped after the layer that read the bad row
+    assert int(gpu["frontier_count"][1]) == 0
+    t = H.oracle_tree(cfg, pool[0], H.root_tokens(cfg)[0], cap=cfg.N - 1)
+    if t.margin > H.MARGIN_TOL:
+        H.compare_tree(cfg, {k: v[:1] for k, v in gpu.items()}, [t], check_rows=False)
+
+
+def test_budget_of_one_and_two():
+    from tests.test_gpu_parity import small
+    for N in (1, 2):
+        cfg = small(name="lit-n%d" % N, V=2048, logits_dtype="bf16", K=4, N=N, Dmax=4)
+        _compare_pool(cfg, H.build_pool(cfg, [cfg.seed]), need_margin=False)
