@@ -59,6 +59,10 @@ def parse_args():
                     help="only run the paper's tree-construction micro-benchmark shape (App. E.6): latency of one "
                          "layer expansion over K parents with Zipf rows, exponent x vocabulary grid, 20 warm-ups and "
                          "100 timed runs, for the adaptive gate (Alg. 2) and the static top-K of the pool (Alg. 1)")
+    ap.add_argument("--literal", action="store_true",
+                    help="time the expansion with the uncapped candidate pool (talon_tree_init + talon_expand_literal "
+                         "+ talon_build_tree_mask) beside the capped single launch on the same inputs, and report how "
+                         "the two trees differ")
     ap.add_argument("--layerwise", action="store_true",
                     help="also time the expansion layer by layer (one fused scan+selection launch per layer, "
                          "talon_expand_select_layer) and report rows, duration and read bandwidth of each layer")
@@ -122,6 +126,9 @@ def main():
         return
     if args.sweep:
         print(json.dumps({"sweep": variant_sweep(T, torch, np, H, args.steps)}))
+        return
+    if args.literal:
+        print(json.dumps({"literal": literal_timing(T, torch, np, H, cfg, args.steps, args.slots or 2)}))
         return
 
     elem = cfg.elem_bytes
@@ -439,6 +446,66 @@ def variant_sweep(T, torch, np, H, steps):
                          "tau": float(np.mean(acc)) + 1.0})
         del graphs
     return rows_out
+
+
+def literal_timing(T, torch, np, H, cfg, steps, n_slots):
+    """Expansion alone, two ways on the same rotating inputs, each replayed as one HIP graph per
+    slot: the capped single launch (per-row cap = the configuration's K) and the uncapped pool of
+    Alg. 2 as written (one scan, plan, collect and select launch per layer).  Reports time per
+    tree batch, tree sizes, depths, the largest fan-out and in how many sequences the trees differ."""
+    slots = [Slot(cfg, cfg.seed + 1000 * i, torch, H) for i in range(n_slots)]
+    dt = T.TALON_DTYPE_F32 if cfg.logits_dtype == "f32" else T.TALON_DTYPE_BF16
+    roots = torch.from_numpy(H.root_tokens(cfg)).cuda()
+    res = {"workload": cfg.name, "slots": n_slots, "steps": steps}
+    trees = {}
+    for mode in ("capped", "uncapped"):
+        st = T.TreeState(cfg.B, cfg.N)
+        mask = torch.zeros(cfg.B, st.N_pad, st.N_pad // 64, dtype=torch.int64, device="cuda")
+        if mode == "capped":
+            cand = T.Candidates(cfg.B, st.N_pad, cfg.K)
+            ws = T.make_expand_workspace(cfg.B, st.N_pad, cfg.V, cfg.K, dt)
+
+            def run(sl):
+                T.talon_build_tree(roots, sl.logits, st, cfg.K, cfg.mu, cfg.K, 1, cfg.Dmax, cand, ws, mask=mask)
+        else:
+            ws = T.make_literal_workspace(cfg.B, st.N_pad, cfg.V, dt)
+
+            def run(sl):
+                T.talon_tree_init(st, roots)
+                T.talon_expand_literal(sl.logits, st, cfg.Dmax, cfg.mu, cfg.K, 1, cfg.Dmax, ws)
+                T.talon_build_tree_mask(st, mask)
+        graphs, snap = [], []
+        for sl in slots:
+            run(sl)
+            torch.cuda.synchronize()
+            n = st.n_nodes.cpu().numpy()
+            par = st.parent.cpu().numpy()
+            snap.append((n.copy(), par.copy(), st.token.cpu().numpy().copy(), st.depth_cur.cpu().numpy().copy()))
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                run(sl)
+            graphs.append(g)
+        for g in graphs:
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            graphs[i % n_slots].replay()
+        torch.cuda.synchronize()
+        us = (time.perf_counter() - t0) * 1e6 / steps
+        fan = max(int(np.bincount(par[b, 1:int(n[b])], minlength=1).max()) if n[b] > 1 else 0
+                  for n, par, _, _ in snap for b in range(cfg.B))
+        trees[mode] = snap
+        res[mode] = {"us_per_call": us, "n_mean": float(np.mean([n.mean() for n, _, _, _ in snap])),
+                     "layers_mean": float(np.mean([d.mean() for _, _, _, d in snap])), "largest_fan_out": fan}
+    differ = 0
+    for (n0, p0, t0_, _), (n1, p1, t1_, _) in zip(trees["capped"], trees["uncapped"]):
+        for b in range(cfg.B):
+            same = n0[b] == n1[b] and np.array_equal(p0[b, :n0[b]], p1[b, :n1[b]]) and np.array_equal(t0_[b, :n0[b]], t1_[b, :n1[b]])
+            differ += 0 if same else 1
+    res["sequences"] = n_slots * cfg.B
+    res["sequences_whose_trees_differ"] = differ
+    return res
 
 
 def zipf_grid(T, torch, np, H, K=10, N=60, warm=20, runs=100):

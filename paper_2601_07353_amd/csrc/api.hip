@@ -202,22 +202,32 @@ int verify_layout(int B, int N_pad, int vocab, int dtype, VerifyLayout* V) {
   return TALON_OK;
 }
 
-// Workspace of talon_expand_literal: the scan's workspace for k = 1 and its outputs, the
-// per-sequence plan of a layer, and the survivors of every frontier row.
+// Workspace of talon_expand_literal: the scan's workspace and its outputs (laid out for the
+// most candidates per row the call ever asks the scan for), the per-sequence plan of a
+// layer, and the survivors of every frontier row.
+constexpr int kLiteralScanK = 16;
 struct LiteralLayout {
   ExpandLayout scan;
+  int k_max;   // candidates per row the layout has room for: kLiteralScanK, or 1 for very wide rows
   size_t off_token, off_logit, off_prob, off_edge, off_max, off_lse, off_plan, off_count, off_keys, total;
 };
 
 int literal_layout(int B, int N_pad, int vocab, int dtype, LiteralLayout* V) {
   int rc = expand_layout(B, N_pad, vocab, 1, dtype, &V->scan);
   if (rc) return rc;
+  V->k_max = 1;
+  const int ce = expand_chunk_elems(dtype);
+  if ((static_cast<long long>(vocab) + ce - 1) / ce * kLiteralScanK <= kMergeCap) {
+    V->k_max = kLiteralScanK;
+    if ((rc = expand_layout(B, N_pad, vocab, kLiteralScanK, dtype, &V->scan))) return rc;
+  }
   const size_t rows = static_cast<size_t>(B) * N_pad;
+  const size_t cands = rows * V->k_max;
   size_t o = V->scan.total;
-  V->off_token = o; o += align_up(rows * sizeof(int32_t), 256);
-  V->off_logit = o; o += align_up(rows * sizeof(float), 256);
-  V->off_prob = o;  o += align_up(rows * sizeof(float), 256);
-  V->off_edge = o;  o += align_up(rows * sizeof(double), 256);
+  V->off_token = o; o += align_up(cands * sizeof(int32_t), 256);
+  V->off_logit = o; o += align_up(cands * sizeof(float), 256);
+  V->off_prob = o;  o += align_up(cands * sizeof(float), 256);
+  V->off_edge = o;  o += align_up(cands * sizeof(double), 256);
   V->off_max = o;   o += align_up(rows * sizeof(float), 256);
   V->off_lse = o;   o += align_up(rows * sizeof(double), 256);
   V->off_plan = o;  o += align_up(static_cast<size_t>(B) * sizeof(LiteralPlan), 256);
@@ -431,8 +441,11 @@ int talon_expand_literal(const void* logits, int dtype, int64_t row_stride, int6
   if (rc) return rc;
   char* w = static_cast<char*>(workspace);
   ExpandLayout L;
+  // On top-K layers the scan ranks K_init candidates per row (the pool's K_init best hold no
+  // more of one row); otherwise only the row statistics are wanted.
+  const int k_scan = (init_layers > 0 && K_init >= 1 && K_init <= V.k_max) ? K_init : 1;
   // the scan's own checks (pointers, alignment, strides), its outputs in the workspace
-  rc = check_expand_args(logits, dtype, row_stride, seq_stride, row_mode, st, vocab, 1, w ? w + V.off_token : nullptr,
+  rc = check_expand_args(logits, dtype, row_stride, seq_stride, row_mode, st, vocab, k_scan, w ? w + V.off_token : nullptr,
                          w ? w + V.off_logit : nullptr, w ? w + V.off_prob : nullptr, w ? w + V.off_edge : nullptr,
                          w ? w + V.off_max : nullptr, w ? w + V.off_lse : nullptr, workspace, workspace_bytes, &L);
   if (rc) return rc;
@@ -445,7 +458,8 @@ int talon_expand_literal(const void* logits, int dtype, int64_t row_stride, int6
   if (init_layers < 0) { set_error("init_layers=%d must be >= 0", init_layers); return TALON_ERR_INVALID_ARG; }
   if (max_depth < 1) { set_error("max_depth=%d must be >= 1", max_depth); return TALON_ERR_INVALID_ARG; }
   if (layers < 1) { set_error("layers=%d must be >= 1", layers); return TALON_ERR_INVALID_ARG; }
-  const ExpandArgs ea = make_expand_args(logits, row_stride, seq_stride, row_mode, st, vocab, 1,
+  L = V.scan;   // offsets of the roomier layout; the scan strides its partial keys by k_scan
+  const ExpandArgs ea = make_expand_args(logits, row_stride, seq_stride, row_mode, st, vocab, k_scan,
                                          reinterpret_cast<int32_t*>(w + V.off_token), reinterpret_cast<float*>(w + V.off_logit),
                                          reinterpret_cast<float*>(w + V.off_prob), reinterpret_cast<double*>(w + V.off_edge),
                                          reinterpret_cast<float*>(w + V.off_max), reinterpret_cast<double*>(w + V.off_lse),
@@ -454,6 +468,8 @@ int talon_expand_literal(const void* logits, int dtype, int64_t row_stride, int6
   la.logits = logits; la.row_stride = row_stride; la.seq_stride = seq_stride; la.row_mode = row_mode; la.vocab = vocab;
   la.st = *st; la.log_mu = log(static_cast<double>(mu)); la.K_init = K_init; la.init_layers = init_layers;
   la.max_depth = max_depth;
+  la.k_scan = k_scan;
+  la.scan_token = reinterpret_cast<const int32_t*>(w + V.off_token);
   la.top_logit = reinterpret_cast<const float*>(w + V.off_logit);
   la.row_lse = reinterpret_cast<const double*>(w + V.off_lse);
   la.plan = reinterpret_cast<LiteralPlan*>(w + V.off_plan);
@@ -467,7 +483,7 @@ int talon_expand_literal(const void* logits, int dtype, int64_t row_stride, int6
   const int most = st->N > 1 ? st->N - 1 : 0;
   const int run = layers < most ? layers : most;
   for (int d = 0; d < run; ++d) {
-    rc = check_hip(launch_expand(ea, dtype, expand_grid(st, L.chunks, -1, 1, 1, 0), false, s), "scan launch");
+    rc = check_hip(launch_expand(ea, dtype, expand_grid(st, L.chunks, -1, k_scan, k_scan, 0), false, s), "scan launch");
     if (rc) return rc;
     rc = check_hip(launch_literal_layer(la, dtype, s), "literal layer launch");
     if (rc) return rc;

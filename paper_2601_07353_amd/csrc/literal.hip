@@ -29,19 +29,46 @@ __device__ __forceinline__ double key_to_f64(unsigned long long s) {
   return __longlong_as_double(static_cast<long long>(u));
 }
 
-// Adds one to s_hist[digit] for every lane with c set.  Keys of one row often share their
-// leading digits: when all lanes that count hit the same bin, one of them adds their number.
-__device__ __forceinline__ void hist_add(int* s_hist, bool c, int digit) {
-  const unsigned long long m = __ballot(c);
-  if (m == 0ull) return;
-  const int lead = __ffsll(static_cast<long long>(m)) - 1;
-  const int d0 = __shfl(digit, lead);
-  const unsigned long long same = __ballot(c && digit == d0);
-  if (same == m) {
-    if (static_cast<int>(threadIdx.x & 63) == lead) atomicAdd(&s_hist[d0], __popcll(m));
-  } else if (c) {
-    atomicAdd(&s_hist[digit], 1);
+// Histogram of 8-bit digits in LDS, fed one wavefront-wide call at a time.  Keys of one row
+// often share their leading digits: when all lanes that count hit the same bin, their number
+// is added by one lane, and runs of such calls on the same bin are added up in a register
+// first (flush() hands the rest over; call it before the histogram is read).
+struct WaveHist {
+  int* hist;
+  int pend_digit = -1;
+  int pend_count = 0;
+  __device__ __forceinline__ explicit WaveHist(int* h) : hist(h) {}
+  __device__ __forceinline__ void flush() {
+    if (pend_count > 0 && (threadIdx.x & 63) == 0) atomicAdd(&hist[pend_digit], pend_count);
+    pend_count = 0;
+    pend_digit = -1;
   }
+  __device__ __forceinline__ void add(bool c, int digit) {
+    const unsigned long long m = __ballot(c);
+    if (m == 0ull) return;
+    const int lead = __ffsll(static_cast<long long>(m)) - 1;
+    const int d0 = __builtin_amdgcn_readlane(digit, lead);
+    const unsigned long long same = __ballot(c && digit == d0);
+    if (same == m) {
+      if (d0 != pend_digit) { flush(); pend_digit = d0; }
+      pend_count += __popcll(m);
+    } else if (c) {
+      atomicAdd(&hist[digit], 1);
+    }
+  }
+};
+
+// One slot of a counter in LDS for every lane with c set (-1 for the others): one atomic per
+// wavefront, the lanes' slots in lane order.
+__device__ __forceinline__ int claim_slots(int* counter, bool c) {
+  const unsigned long long m = __ballot(c);
+  if (m == 0ull) return -1;
+  const int lane = threadIdx.x & 63;
+  const int lead = __ffsll(static_cast<long long>(m)) - 1;
+  int base = 0;
+  if (lane == lead) base = atomicAdd(counter, __popcll(m));
+  base = __shfl(base, lead);
+  return c ? base + __popcll(m & ((1ull << lane) - 1ull)) : -1;
 }
 
 // Walks the 256 bins from the largest digit down to the bin that holds the `remaining`-th
@@ -101,7 +128,7 @@ __global__ __launch_bounds__(kThreads) void literal_plan_kernel(LiteralArgs a) {
   unsigned long long key = 0ull;
   for (int j = tid; j < F; j += kThreads) {
     const size_t row = base + fb + j;
-    const double s = st.logp[row] + (static_cast<double>(a.top_logit[row]) - a.row_lse[row]);
+    const double s = st.logp[row] + (static_cast<double>(a.top_logit[row * a.k_scan]) - a.row_lse[row]);
     if (s == s) {
       unsigned long long ks = sortable_u64(s);
       if (ks == 0ull) ks = 1ull;
@@ -129,12 +156,29 @@ __device__ __forceinline__ float vec_elem(const uint4& v, int e) {
   }
 }
 
+constexpr int kHistCopies = 32;
+constexpr int kLdsKeys = 2048;   // keys of one histogram bin that the search finishes on in LDS
+constexpr int kVecAhead = 8;     // 16-byte loads a thread has in flight
+
 // One workgroup per frontier row.  EPL: logits per 16-byte vector (4 fp32, 8 bf16).
+//
+// The row is streamed once to count what passes the gate (and to keep it, if it fits: the
+// common case, one pass).  If more than `cap` pass, a radix select finds the cap-th largest
+// key: 8 bits per pass over the row, until the bin that holds the cut is small enough for
+// LDS; one more pass then writes the keys above that bin and gathers the bin, and the search
+// ends in LDS.  bf16 logits carry 16 significant bits, so the two low bytes of their images
+// are skipped.
 template <int EPL>
 __global__ __launch_bounds__(kThreads) void literal_collect_kernel(LiteralArgs a) {
+  // While the row is streamed every lane counts in its own copy of the histogram (copy =
+  // lane mod 32, one LDS bank each): logits of a row crowd into a few bins, and atomics of
+  // many lanes on one word would run one after the other.
+  __shared__ int s_rep[256 * kHistCopies];
   __shared__ int s_hist[256];
   __shared__ unsigned long long s_lo;
-  __shared__ int s_digit, s_want, s_count;
+  __shared__ int s_digit, s_want, s_count, s_nbin;
+  __shared__ int s_red[8];
+  __shared__ unsigned long long s_bin[kLdsKeys];
   const int b = blockIdx.y;
   const int j = blockIdx.x;
   const LiteralPlan p = a.plan[b];
@@ -149,9 +193,42 @@ __global__ __launch_bounds__(kThreads) void literal_collect_kernel(LiteralArgs a
   const int nvec = (a.vocab + EPL - 1) / EPL;
   unsigned long long* out = a.row_key + out_row * kLiteralRowCap;
 
-  s_hist[tid] = 0;
+  const int cap = p.limit;
+  if (p.d < a.init_layers && a.k_scan >= cap) {
+    // top-K layer: the pool's K_init best hold at most K_init tokens of one row, and the scan
+    // has already ranked that many (logit descending, token ascending; missing ones last)
+    unsigned long long key = 0ull;
+    bool have = false;
+    if (tid < cap) {
+      const int tok = a.scan_token[out_row * a.k_scan + tid];
+      have = tok >= 0;
+      key = (static_cast<unsigned long long>(sortable_u32(a.top_logit[out_row * a.k_scan + tid])) << 32) |
+            static_cast<unsigned long long>(0xFFFFFFFFu - static_cast<uint32_t>(tok));
+    }
+    if (have) out[tid] = key;
+    if (tid < 64) {   // cap <= 64 here: candidates are valid up to the first missing one
+      const unsigned long long vb = __ballot(have);
+      if (tid == 0) a.row_count[out_row] = vb == ~0ull ? 64 : __builtin_ctzll(~vb);
+    }
+    return;
+  }
+
+  const int copy = tid & (kHistCopies - 1);
+  auto clear_copies = [&]() {
+    for (int i = tid; i < 256 * kHistCopies; i += kThreads) s_rep[i] = 0;
+  };
+  auto sum_copies = [&]() {   // s_hist[bin] = sum of the copies; barriers before and after
+    __syncthreads();
+    int sum = 0;
+#pragma unroll 8
+    for (int r = 0; r < kHistCopies; ++r) sum += s_rep[tid * kHistCopies + ((r + tid) & (kHistCopies - 1))];
+    s_hist[tid] = sum;
+    __syncthreads();
+  };
+  clear_copies();
   if (tid == 0) {
     s_count = 0;
+    s_nbin = 0;
     // Inside a row the path score log p(v) + (logit - lse_v) rises with the logit, so the gate
     // is a bound on the logit: the smallest logit image whose score passes, by bisection with
     // the very expression the score is computed with.
@@ -170,83 +247,152 @@ __global__ __launch_bounds__(kThreads) void literal_collect_kernel(LiteralArgs a
   }
   __syncthreads();
   const unsigned long long lo = s_lo;
-  const int cap = p.limit;
+  const float x_lo = unsortable_f32(static_cast<uint32_t>(lo >> 32));   // logit >= x_lo: passes the gate
 
-  // f(valid, key) for every logit of the row; the same number of calls in every lane
-  auto for_each_key = [&](auto&& f) {
-    for (int base = 0; base < nvec; base += 4 * kThreads) {
-      uint4 raw[4];
+  // f(valid, key) for every logit of the row that is >= x_min, the same number of calls in
+  // every lane of a wavefront; vectors in which no lane holds such a logit are skipped whole
+  auto for_each_key = [&](float x_min, auto&& f) {
+    for (int base = 0; base < nvec; base += kVecAhead * kThreads) {
+      uint4 raw[kVecAhead];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < kVecAhead; ++u) {
         const int vi = base + u * kThreads + tid;
         raw[u] = vi < nvec ? row[vi] : make_uint4(0u, 0u, 0u, 0u);
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < kVecAhead; ++u) {
         const int t0 = (base + u * kThreads + tid) * EPL;
+        float x[EPL];
+        bool any = false;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+          x[e] = vec_elem<EPL>(raw[u], e);
+          any = any || (t0 + e < a.vocab && x[e] >= x_min);
+        }
+        if (__ballot(any) == 0ull) continue;
 #pragma unroll
         for (int e = 0; e < EPL; ++e) {
           const int token = t0 + e;
-          const unsigned long long key = (static_cast<unsigned long long>(sortable_u32(vec_elem<EPL>(raw[u], e))) << 32) |
+          const unsigned long long key = (static_cast<unsigned long long>(sortable_u32(x[e])) << 32) |
                                          static_cast<unsigned long long>(0xFFFFFFFFu - static_cast<uint32_t>(token));
-          f(token < a.vocab, key);
+          f(token < a.vocab && x[e] >= x_min, key);
         }
       }
     }
   };
 
   // first pass: count what passes the gate, keep it if it fits, histogram of the top digit
-  for_each_key([&](bool ok, unsigned long long key) {
-    const bool c = ok && key >= lo;
-    hist_add(s_hist, c, static_cast<int>(key >> 56));
-    if (c) {
-      const int slot = atomicAdd(&s_count, 1);
-      if (slot < kLiteralRowCap) out[slot] = key;
-    }
-  });
-  __syncthreads();
-  const int total = s_count;
+  // (slots are claimed only until the row has overflowed; after that a wavefront just counts)
+  {
+    bool overflow = false;
+    for_each_key(x_lo, [&](bool ok, unsigned long long key) {
+      const bool c = ok && key >= lo;
+      if (c) atomicAdd(&s_rep[static_cast<int>(key >> 56) * kHistCopies + copy], 1);
+      if (!overflow) {
+        const int slot = claim_slots(&s_count, c);
+        if (slot >= 0 && slot < kLiteralRowCap) out[slot] = key;
+        overflow = __ballot(slot >= kLiteralRowCap) != 0ull;
+      }
+    });
+  }
+  sum_copies();
+  const int total = block_sum_i32(s_hist[tid], s_red);
   if (total <= cap) {
     if (tid == 0) a.row_count[out_row] = total;
     return;
   }
 
-  // more than the layer can take: the cap-th largest key, 8 bits per pass
+  // more than the layer can take: the cap-th largest key
   unsigned long long prefix = 0ull;
   int remaining = cap;
+  int shift = 56;
+  bool in_lds = false, found = false;
   for (int pass = 0; pass < 8; ++pass) {
-    const int shift = 56 - 8 * pass;
+    shift = 56 - 8 * pass;
+    if (EPL == 8 && (pass == 2 || pass == 3)) {
+      // the low half of a bf16 logit's image is all zeros (positive) or all ones (negative)
+      if (!(prefix >> 63)) prefix |= 0xFFull << shift;
+      continue;
+    }
     if (pass > 0) {
-      s_hist[tid] = 0;
+      clear_copies();
       __syncthreads();
-      for_each_key([&](bool ok, unsigned long long key) {
+      for_each_key(x_lo, [&](bool ok, unsigned long long key) {
         const bool c = ok && key >= lo && ((key ^ prefix) >> (shift + 8)) == 0ull;
-        hist_add(s_hist, c, static_cast<int>(key >> shift) & 255);
+        if (c) atomicAdd(&s_rep[(static_cast<int>(key >> shift) & 255) * kHistCopies + copy], 1);
       });
+      sum_copies();
     }
     const int r = find_bin(s_hist, remaining, &s_digit, &s_want);
+    const int population = s_hist[r & 255];
     prefix |= static_cast<unsigned long long>(r & 255) << shift;
     remaining = s_want;
     __syncthreads();
-    if (r & 256) break;
+    if (r & 256) { found = true; break; }
+    if (population <= kLdsKeys) { in_lds = true; break; }
   }
-  const unsigned long long T = prefix > lo ? prefix : lo;
+
   if (tid == 0) s_count = 0;
   __syncthreads();
-  for_each_key([&](bool ok, unsigned long long key) {
-    if (ok && key >= T) {
+  if (found || !in_lds) {
+    // every key >= prefix (its lower digits zero) is kept
+    const unsigned long long T = prefix > lo ? prefix : lo;
+    for_each_key(x_lo, [&](bool ok, unsigned long long key) {
+      const int slot = claim_slots(&s_count, ok && key >= T);
+      if (slot >= 0 && slot < cap) out[slot] = key;
+    });
+    __syncthreads();
+    if (tid == 0) a.row_count[out_row] = s_count < cap ? s_count : cap;
+    return;
+  }
+
+  // keys above the bin are kept; the bin itself goes to LDS, where the search continues
+  for_each_key(x_lo, [&](bool ok, unsigned long long key) {
+    const bool c = ok && key >= lo;
+    const unsigned long long hi_part = key >> shift, bin = prefix >> shift;
+    const int slot = claim_slots(&s_count, c && hi_part > bin);
+    if (slot >= 0 && slot < cap) out[slot] = key;
+    const int slot2 = claim_slots(&s_nbin, c && hi_part == bin);
+    if (slot2 >= 0 && slot2 < kLdsKeys) s_bin[slot2] = key;
+  });
+  __syncthreads();
+  const int nbin = s_nbin < kLdsKeys ? s_nbin : kLdsKeys;
+  bool done = false;
+  for (int sh2 = shift - 8; sh2 >= 0 && !done; sh2 -= 8) {
+    s_hist[tid] = 0;
+    __syncthreads();
+    WaveHist wh(s_hist);
+    for (int base = 0; base < nbin; base += kThreads) {
+      const int i = base + tid;
+      const unsigned long long key = i < nbin ? s_bin[i] : 0ull;
+      const bool c = i < nbin && ((key ^ prefix) >> (sh2 + 8)) == 0ull;
+      wh.add(c, static_cast<int>(key >> sh2) & 255);
+    }
+    wh.flush();
+    const int r = find_bin(s_hist, remaining, &s_digit, &s_want);
+    prefix |= static_cast<unsigned long long>(r & 255) << sh2;
+    remaining = s_want;
+    __syncthreads();
+    done = (r & 256) != 0;
+  }
+  for (int i = tid; i < nbin; i += kThreads) {
+    const unsigned long long key = s_bin[i];
+    if (key >= prefix) {
       const int slot = atomicAdd(&s_count, 1);
       if (slot < cap) out[slot] = key;
     }
-  });
+  }
   __syncthreads();
   if (tid == 0) a.row_count[out_row] = s_count < cap ? s_count : cap;
 }
 
-// One workgroup per sequence.
+constexpr int kPoolLds = 4096;   // survivors of a layer that the budget check holds in LDS
+
+// One workgroup per sequence: the budget check over what the rows kept.
 __global__ __launch_bounds__(kThreads) void literal_select_kernel(LiteralArgs a) {
   __shared__ int s_hist[256];
   __shared__ int s_cnt[256];
+  __shared__ int s_off[256];
   __shared__ double s_lp[256];
   __shared__ double s_lse[256];
   __shared__ unsigned long long s_red_u64[8];
@@ -254,6 +400,8 @@ __global__ __launch_bounds__(kThreads) void literal_select_kernel(LiteralArgs a)
   __shared__ int s_digit, s_want, s_nkeep;
   __shared__ unsigned long long s_kkey[256];
   __shared__ int s_kj[256];
+  __shared__ unsigned long long s_pool[kPoolLds];
+  __shared__ unsigned char s_pool_j[kPoolLds];
   const talon_tree_state& st = a.st;
   const int b = blockIdx.x;
   const LiteralPlan p = a.plan[b];
@@ -261,6 +409,7 @@ __global__ __launch_bounds__(kThreads) void literal_select_kernel(LiteralArgs a)
   const int tid = threadIdx.x;
   const int F = p.F < 256 ? p.F : 256;
   const size_t base = static_cast<size_t>(b) * st.N_pad;
+  const unsigned long long* rows = a.row_key + (base + p.fb) * kLiteralRowCap;
   int c_own = 0;
   if (tid < F) {
     const size_t row = base + p.fb + tid;
@@ -270,18 +419,51 @@ __global__ __launch_bounds__(kThreads) void literal_select_kernel(LiteralArgs a)
   }
   s_cnt[tid] = c_own;
   if (tid == 0) s_nkeep = 0;
-  const int total = block_sum_i32(c_own, s_red_i32);
+  int total;
+  s_off[tid] = block_exclusive_scan_i32(c_own, s_red_i32, &total);
+  __syncthreads();
 
-  // candidate (row j, slot tid): its path score as a sortable key, and the order among equal
-  // scores (parent ascending, then token ascending = in-row rank ascending) as a second key
-  auto candidate = [&](int j, unsigned long long* k64, unsigned long long* hi, unsigned long long* lo2) {
-    const bool valid = tid < s_cnt[j];
-    const unsigned long long key = valid ? a.row_key[(base + p.fb + j) * kLiteralRowCap + tid] : 0ull;
-    const double score = s_lp[j] + (static_cast<double>(unsortable_f32(static_cast<uint32_t>(key >> 32))) - s_lse[j]);
-    *k64 = key;
-    *hi = sortable_u64(score);
-    *lo2 = ((static_cast<unsigned long long>(255 - j) << 32) | (key & 0xFFFFFFFFull)) << 24;
-    return valid;
+  // The pool in LDS, rows one after the other, when it fits (it does unless many rows are
+  // flat); otherwise every pass reads it from memory, row by row.
+  const bool dense = total <= kPoolLds;
+  if (dense) {
+    for (int j0 = 0; j0 < F; j0 += 4) {
+      unsigned long long k[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        k[u] = (j0 + u < F && tid < s_cnt[j0 + u]) ? rows[static_cast<size_t>(j0 + u) * kLiteralRowCap + tid] : 0ull;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (j0 + u < F && tid < s_cnt[j0 + u]) {
+          s_pool[s_off[j0 + u] + tid] = k[u];
+          s_pool_j[s_off[j0 + u] + tid] = static_cast<unsigned char>(j0 + u);
+        }
+      }
+    }
+    __syncthreads();
+  }
+  // f(valid, row j, key): the same number of calls in every thread
+  auto for_each = [&](auto&& f) {
+    if (dense) {
+      for (int i0 = 0; i0 < total; i0 += kThreads) {
+        const int i = i0 + tid;
+        const bool valid = i < total;
+        f(valid, valid ? static_cast<int>(s_pool_j[i]) : 0, valid ? s_pool[i] : 0ull);
+      }
+    } else {
+      for (int j = 0; j < F; ++j) {
+        const bool valid = tid < s_cnt[j];
+        f(valid, j, valid ? rows[static_cast<size_t>(j) * kLiteralRowCap + tid] : 0ull);
+      }
+    }
+  };
+  // path score of a candidate as a sortable key, and the order among equal scores (parent
+  // ascending, then token ascending = in-row rank ascending) as a second key
+  auto score_key = [&](int j, unsigned long long key) {
+    return sortable_u64(s_lp[j] + (static_cast<double>(unsortable_f32(static_cast<uint32_t>(key >> 32))) - s_lse[j]));
+  };
+  auto order_key = [&](int j, unsigned long long key) {
+    return ((static_cast<unsigned long long>(255 - j) << 32) | (key & 0xFFFFFFFFull)) << 24;
   };
 
   unsigned long long pre_hi = 0ull, pre_lo = 0ull, low = 0ull;
@@ -290,10 +472,13 @@ __global__ __launch_bounds__(kThreads) void literal_select_kernel(LiteralArgs a)
   if (cut) {
     // move the score keys to the range they span, so that their digits spread over the bins
     unsigned long long mx = 0ull, inv_mn = 0ull;
-    for (int j = 0; j < F; ++j) {
-      unsigned long long k64, hi, lo2;
-      if (candidate(j, &k64, &hi, &lo2)) { mx = hi > mx ? hi : mx; inv_mn = ~hi > inv_mn ? ~hi : inv_mn; }
-    }
+    for_each([&](bool valid, int j, unsigned long long key) {
+      if (valid) {
+        const unsigned long long hi = score_key(j, key);
+        mx = hi > mx ? hi : mx;
+        inv_mn = ~hi > inv_mn ? ~hi : inv_mn;
+      }
+    });
     mx = block_max_u64(mx, s_red_u64);
     low = ~block_max_u64(inv_mn, s_red_u64);
     sh = __clzll(static_cast<long long>(mx - low + 1ull));
@@ -303,10 +488,10 @@ __global__ __launch_bounds__(kThreads) void literal_select_kernel(LiteralArgs a)
       const int shift = first_key ? 56 - 8 * pass : 56 - 8 * (pass - 8);
       s_hist[tid] = 0;
       __syncthreads();
-      for (int j = 0; j < F; ++j) {
-        unsigned long long k64, hi, lo2;
-        const bool valid = candidate(j, &k64, &hi, &lo2);
-        hi = (hi - low + 1ull) << sh;
+      WaveHist wh(s_hist);
+      for_each([&](bool valid, int j, unsigned long long key) {
+        const unsigned long long hi = (score_key(j, key) - low + 1ull) << sh;
+        const unsigned long long lo2 = order_key(j, key);
         bool match;
         int digit;
         if (first_key) {
@@ -316,8 +501,9 @@ __global__ __launch_bounds__(kThreads) void literal_select_kernel(LiteralArgs a)
           match = hi == pre_hi && (pass == 8 || ((lo2 ^ pre_lo) >> (shift + 8)) == 0ull);
           digit = static_cast<int>(lo2 >> shift) & 255;
         }
-        hist_add(s_hist, valid && match, digit);
-      }
+        wh.add(valid && match, digit);
+      });
+      wh.flush();
       const int r = find_bin(s_hist, remaining, &s_digit, &s_want);
       if (first_key) pre_hi |= static_cast<unsigned long long>(r & 255) << shift;
       else pre_lo |= static_cast<unsigned long long>(r & 255) << shift;
@@ -328,20 +514,15 @@ __global__ __launch_bounds__(kThreads) void literal_select_kernel(LiteralArgs a)
   }
 
   // kept candidates, in any order
-  __syncthreads();
-  for (int j = 0; j < F; ++j) {
-    unsigned long long k64, hi, lo2;
-    const bool valid = candidate(j, &k64, &hi, &lo2);
+  for_each([&](bool valid, int j, unsigned long long key) {
     bool keep = valid;
-    if (cut) {
-      hi = (hi - low + 1ull) << sh;
-      keep = valid && (hi > pre_hi || (hi == pre_hi && lo2 >= pre_lo));
+    if (cut && valid) {
+      const unsigned long long hi = (score_key(j, key) - low + 1ull) << sh;
+      keep = hi > pre_hi || (hi == pre_hi && order_key(j, key) >= pre_lo);
     }
-    if (keep) {
-      const int slot = atomicAdd(&s_nkeep, 1);
-      if (slot < 256) { s_kkey[slot] = k64; s_kj[slot] = j; }
-    }
-  }
+    const int slot = claim_slots(&s_nkeep, keep);
+    if (slot >= 0 && slot < 256) { s_kkey[slot] = key; s_kj[slot] = j; }
+  });
   __syncthreads();
   const int n_keep = s_nkeep < p.limit ? s_nkeep : p.limit;
 

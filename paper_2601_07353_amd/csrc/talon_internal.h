@@ -98,7 +98,9 @@ struct LiteralArgs {
   talon_tree_state st;
   double log_mu;
   int K_init, init_layers, max_depth;
-  const float* top_logit;          // [B*N_pad] largest logit of a scanned row
+  int k_scan;                      // candidates per row the scan ranks (K_init on top-K layers, else 1)
+  const int32_t* scan_token;       // [B*N_pad][k_scan] the scan's candidates ...
+  const float* top_logit;          // [B*N_pad][k_scan] ... and their logits; the first is the row's largest
   const double* row_lse;           // [B*N_pad]
   LiteralPlan* plan;               // [B]
   int32_t* row_count;              // [B*N_pad] survivors kept of a row

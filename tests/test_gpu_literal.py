@@ -167,3 +167,35 @@ def test_budget_of_one_and_two():
     for N in (1, 2):
         cfg = small(name="lit-n%d" % N, V=2048, logits_dtype="bf16", K=4, N=N, Dmax=4)
         _compare_pool(cfg, H.build_pool(cfg, [cfg.seed]), need_margin=False)
+
+
+# ----------------------------------------------------------------------------- full sizes
+def _full_size(cfg_name, oracle_seqs):
+    """All sequences of a benchmark configuration through the uncapped call; the oracle builds the
+    stated sequences in full, every sequence is checked for the properties any tree must have."""
+    from oracle import talon_oracle as O
+    from tests.test_gpu_full_size import structural_checks
+    cfg = CONFIGS[cfg_name]
+    cap = cfg.N - 1
+    seeds = [cfg.seed] * cfg.B
+    for b in oracle_seqs:
+        seeds[b] = H.find_admissible_seed(cfg, b, cfg.seed, cap=cap)[0]
+    print("case", cfg.name, "uncapped, seeds", seeds, "oracle sequences", oracle_seqs, flush=True)
+    pool = H.build_pool(cfg, seeds)
+    gpu = H.run_gpu_literal(cfg, pool, cfg.K)
+    roots = H.root_tokens(cfg)
+    for b in range(cfg.B):
+        structural_checks(cfg, gpu, b)
+    for b in oracle_seqs:
+        t = H.oracle_tree(cfg, pool[b], roots[b], cap=cap)
+        assert t.margin > H.MARGIN_TOL
+        H.compare_tree(cfg, {k: v[b:b + 1] for k, v in gpu.items()}, [t], check_rows=False)
+        np.testing.assert_array_equal(gpu["mask"][b], O.mask_to_words(O.build_tree_mask(t.parent), cfg.N_pad))
+
+
+def test_c3_qwen3_8b_x4_full_size_uncapped():
+    _full_size("c3", [0, 1, 2, 3])
+
+
+def test_c5_stress_full_size_uncapped():
+    _full_size("c5", [3, 12])
