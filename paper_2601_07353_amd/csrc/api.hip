@@ -203,13 +203,13 @@ int verify_layout(int B, int N_pad, int vocab, int dtype, VerifyLayout* V) {
 }
 
 // Workspace of talon_expand_literal: the scan's workspace and its outputs (laid out for the
-// most candidates per row the call ever asks the scan for), the per-sequence plan of a
-// layer, and the survivors of every frontier row.
+// most candidates per row the call ever asks the scan for) and the survivors of every
+// frontier row.
 constexpr int kLiteralScanK = 16;
 struct LiteralLayout {
   ExpandLayout scan;
   int k_max;   // candidates per row the layout has room for: kLiteralScanK, or 1 for very wide rows
-  size_t off_token, off_logit, off_prob, off_edge, off_max, off_lse, off_plan, off_count, off_keys, total;
+  size_t off_token, off_logit, off_prob, off_edge, off_max, off_lse, off_count, off_keys, total;
 };
 
 int literal_layout(int B, int N_pad, int vocab, int dtype, LiteralLayout* V) {
@@ -230,7 +230,6 @@ int literal_layout(int B, int N_pad, int vocab, int dtype, LiteralLayout* V) {
   V->off_edge = o;  o += align_up(cands * sizeof(double), 256);
   V->off_max = o;   o += align_up(rows * sizeof(float), 256);
   V->off_lse = o;   o += align_up(rows * sizeof(double), 256);
-  V->off_plan = o;  o += align_up(static_cast<size_t>(B) * sizeof(LiteralPlan), 256);
   V->off_count = o; o += align_up(rows * sizeof(int32_t), 256);
   V->off_keys = o;  o += align_up(rows * kLiteralRowCap * sizeof(uint64_t), 256);
   V->total = o;
@@ -472,14 +471,13 @@ int talon_expand_literal(const void* logits, int dtype, int64_t row_stride, int6
   la.scan_token = reinterpret_cast<const int32_t*>(w + V.off_token);
   la.top_logit = reinterpret_cast<const float*>(w + V.off_logit);
   la.row_lse = reinterpret_cast<const double*>(w + V.off_lse);
-  la.plan = reinterpret_cast<LiteralPlan*>(w + V.off_plan);
   la.row_count = reinterpret_cast<int32_t*>(w + V.off_count);
   la.row_key = reinterpret_cast<unsigned long long*>(w + V.off_keys);
   hipStream_t s = static_cast<hipStream_t>(stream);
   // the scan's row tickets start at zero and every launch leaves them so
   rc = check_hip(launch_fill_zero(w + L.off_ticket, L.off_max - L.off_ticket, s), "ticket fill launch");
   if (rc) return rc;
-  // a tree of N nodes has at most N - 1 layers; a layer of finished sequences costs four empty launches
+  // a tree of N nodes has at most N - 1 layers; a layer of finished sequences costs three empty launches
   const int most = st->N > 1 ? st->N - 1 : 0;
   const int run = layers < most ? layers : most;
   for (int d = 0; d < run; ++d) {

@@ -6,10 +6,10 @@
 //
 // A layer never takes more than `limit` nodes (the remaining budget R_d, or min(K_init, R_d) on
 // a top-K layer), so a row can contribute at most `limit` of them, and inside a row the path
-// score rises with the logit.  Three kernels after the vocabulary scan (k = 1: row maximum and
-// log-sum-exp):
-//   plan     per sequence: anchor m_d = best path score of the pool (a row's best candidate is
-//            its largest logit), gate threshold log(mu) + m_d  (Eq. 4), limit
+// score rises with the logit.  Two kernels after the vocabulary scan (row maximum and
+// log-sum-exp; on top-K layers also the K_init best of every row):
+//   (plan    in both, per sequence: anchor m_d = best path score of the pool (a row's best
+//            candidate is its largest logit), gate threshold log(mu) + m_d  (Eq. 4), limit)
 //   collect  per frontier row: the tokens that pass the gate, at most `limit` of them, the
 //            best by (logit descending, token ascending) -- a radix select over the row when
 //            more pass
@@ -103,30 +103,29 @@ __device__ __forceinline__ int find_bin(const int* s_hist, int remaining, int* s
   return *s_digit;
 }
 
-__global__ __launch_bounds__(kThreads) void literal_plan_kernel(LiteralArgs a) {
-  __shared__ unsigned long long s_red[8];
+// What a layer does for sequence b, from the tree state and the scan's row statistics; computed
+// by every workgroup that works on the sequence (the same value in all of them and in all
+// threads; the tree state changes only in the select kernel, which is a later launch).
+// s_plan: one LiteralPlan in LDS.
+// NT: threads of the workgroup; s_red: NT / 64 values of LDS.
+template <int NT>
+__device__ __forceinline__ LiteralPlan make_plan(const LiteralArgs& a, int b, unsigned long long* s_red,
+                                                 LiteralPlan* s_plan) {
   const talon_tree_state& st = a.st;
-  const int b = blockIdx.x;
   const int tid = threadIdx.x;
   const uint32_t status = st.status[b];
   const int F = st.frontier_count[b];
-  LiteralPlan p;
-  p.thr = 0.0; p.active = 0; p.F = 0; p.fb = 0; p.n = 0; p.d = 0; p.limit = 0; p.status = status; p.pad = 0;
   const int n = st.n_nodes[b];
   const int R = st.N - n;
-  if ((status & kDoneMask) || F <= 0 || R <= 0) {
-    if (tid == 0) a.plan[b] = p;
-    return;
-  }
-  if (status & TALON_STATUS_BAD_ROW) {   // a row of this layer could not be normalised: stop here
-    if (tid == 0) { st.frontier_count[b] = 0; a.plan[b] = p; }
-    return;
-  }
+  LiteralPlan p;
+  p.thr = 0.0; p.active = 0; p.F = F; p.fb = 0; p.n = n; p.d = 0; p.limit = 0; p.status = status; p.pad = 0;
+  // finished, nothing to expand, or a row of this layer could not be normalised
+  if ((status & (kDoneMask | TALON_STATUS_BAD_ROW)) || F <= 0 || R <= 0) return p;
   const int fb = st.frontier_begin[b];
   const int d = st.depth_cur[b];
   const size_t base = static_cast<size_t>(b) * st.N_pad;
   unsigned long long key = 0ull;
-  for (int j = tid; j < F; j += kThreads) {
+  for (int j = tid; j < F; j += NT) {
     const size_t row = base + fb + j;
     const double s = st.logp[row] + (static_cast<double>(a.top_logit[row * a.k_scan]) - a.row_lse[row]);
     if (s == s) {
@@ -135,14 +134,20 @@ __global__ __launch_bounds__(kThreads) void literal_plan_kernel(LiteralArgs a) {
       key = ks > key ? ks : key;
     }
   }
-  key = block_max_u64(key, s_red);
+  key = wave_max_u64(key);
+  if ((tid & 63) == 0) s_red[tid >> 6] = key;
+  __syncthreads();
   if (tid == 0) {
+#pragma unroll
+    for (int w = 1; w < NT / 64; ++w) key = s_red[w] > key ? s_red[w] : key;
     const bool init = d < a.init_layers;
-    p.active = 1; p.F = F; p.fb = fb; p.n = n; p.d = d;
+    p.active = 1; p.fb = fb; p.d = d;
     p.limit = init ? (a.K_init < R ? a.K_init : R) : R;
     p.thr = (init || key == 0ull) ? -__builtin_huge_val() : a.log_mu + key_to_f64(key);
-    a.plan[b] = p;
+    *s_plan = p;
   }
+  __syncthreads();
+  return *s_plan;
 }
 
 template <int EPL>
@@ -156,9 +161,10 @@ __device__ __forceinline__ float vec_elem(const uint4& v, int e) {
   }
 }
 
+constexpr int kCollectThreads = 1024;   // a row is one workgroup's: many wavefronts, to have enough loads in flight
 constexpr int kHistCopies = 32;
 constexpr int kLdsKeys = 2048;   // keys of one histogram bin that the search finishes on in LDS
-constexpr int kVecAhead = 8;     // 16-byte loads a thread has in flight
+constexpr int kVecAhead = 4;     // 16-byte loads a thread has in flight
 
 // One workgroup per frontier row.  EPL: logits per 16-byte vector (4 fp32, 8 bf16).
 //
@@ -169,7 +175,8 @@ constexpr int kVecAhead = 8;     // 16-byte loads a thread has in flight
 // ends in LDS.  bf16 logits carry 16 significant bits, so the two low bytes of their images
 // are skipped.
 template <int EPL>
-__global__ __launch_bounds__(kThreads) void literal_collect_kernel(LiteralArgs a) {
+__global__ __launch_bounds__(kCollectThreads) void literal_collect_kernel(LiteralArgs a) {
+  constexpr int NT = kCollectThreads;
   // While the row is streamed every lane counts in its own copy of the histogram (copy =
   // lane mod 32, one LDS bank each): logits of a row crowd into a few bins, and atomics of
   // many lanes on one word would run one after the other.
@@ -179,10 +186,13 @@ __global__ __launch_bounds__(kThreads) void literal_collect_kernel(LiteralArgs a
   __shared__ int s_digit, s_want, s_count, s_nbin;
   __shared__ int s_red[8];
   __shared__ unsigned long long s_bin[kLdsKeys];
+  __shared__ unsigned long long s_red_plan[NT / 64];
+  __shared__ LiteralPlan s_plan;
   const int b = blockIdx.y;
   const int j = blockIdx.x;
-  const LiteralPlan p = a.plan[b];
-  if (!p.active || j >= p.F) return;
+  if (j >= a.st.frontier_count[b]) return;
+  const LiteralPlan p = make_plan<NT>(a, b, s_red_plan, &s_plan);
+  if (!p.active) return;
   const int tid = threadIdx.x;
   const int node = p.fb + j;
   const size_t out_row = static_cast<size_t>(b) * a.st.N_pad + node;
@@ -215,14 +225,16 @@ __global__ __launch_bounds__(kThreads) void literal_collect_kernel(LiteralArgs a
 
   const int copy = tid & (kHistCopies - 1);
   auto clear_copies = [&]() {
-    for (int i = tid; i < 256 * kHistCopies; i += kThreads) s_rep[i] = 0;
+    for (int i = tid; i < 256 * kHistCopies; i += NT) s_rep[i] = 0;
   };
   auto sum_copies = [&]() {   // s_hist[bin] = sum of the copies; barriers before and after
     __syncthreads();
-    int sum = 0;
+    if (tid < 256) {
+      int sum = 0;
 #pragma unroll 8
-    for (int r = 0; r < kHistCopies; ++r) sum += s_rep[tid * kHistCopies + ((r + tid) & (kHistCopies - 1))];
-    s_hist[tid] = sum;
+      for (int r = 0; r < kHistCopies; ++r) sum += s_rep[tid * kHistCopies + ((r + tid) & (kHistCopies - 1))];
+      s_hist[tid] = sum;
+    }
     __syncthreads();
   };
   clear_copies();
@@ -252,16 +264,16 @@ __global__ __launch_bounds__(kThreads) void literal_collect_kernel(LiteralArgs a
   // f(valid, key) for every logit of the row that is >= x_min, the same number of calls in
   // every lane of a wavefront; vectors in which no lane holds such a logit are skipped whole
   auto for_each_key = [&](float x_min, auto&& f) {
-    for (int base = 0; base < nvec; base += kVecAhead * kThreads) {
+    for (int base = 0; base < nvec; base += kVecAhead * NT) {
       uint4 raw[kVecAhead];
 #pragma unroll
       for (int u = 0; u < kVecAhead; ++u) {
-        const int vi = base + u * kThreads + tid;
+        const int vi = base + u * NT + tid;
         raw[u] = vi < nvec ? row[vi] : make_uint4(0u, 0u, 0u, 0u);
       }
 #pragma unroll
       for (int u = 0; u < kVecAhead; ++u) {
-        const int t0 = (base + u * kThreads + tid) * EPL;
+        const int t0 = (base + u * NT + tid) * EPL;
         float x[EPL];
         bool any = false;
 #pragma unroll
@@ -296,7 +308,12 @@ __global__ __launch_bounds__(kThreads) void literal_collect_kernel(LiteralArgs a
     });
   }
   sum_copies();
-  const int total = block_sum_i32(s_hist[tid], s_red);
+  {
+    const int v = wave_sum_i32(tid < 256 ? s_hist[tid] : 0);
+    if (tid < 256 && (tid & 63) == 0) s_red[tid >> 6] = v;
+    __syncthreads();
+  }
+  const int total = s_red[0] + s_red[1] + s_red[2] + s_red[3];
   if (total <= cap) {
     if (tid == 0) a.row_count[out_row] = total;
     return;
@@ -359,10 +376,10 @@ __global__ __launch_bounds__(kThreads) void literal_collect_kernel(LiteralArgs a
   const int nbin = s_nbin < kLdsKeys ? s_nbin : kLdsKeys;
   bool done = false;
   for (int sh2 = shift - 8; sh2 >= 0 && !done; sh2 -= 8) {
-    s_hist[tid] = 0;
+    if (tid < 256) s_hist[tid] = 0;
     __syncthreads();
     WaveHist wh(s_hist);
-    for (int base = 0; base < nbin; base += kThreads) {
+    for (int base = 0; base < nbin; base += NT) {
       const int i = base + tid;
       const unsigned long long key = i < nbin ? s_bin[i] : 0ull;
       const bool c = i < nbin && ((key ^ prefix) >> (sh2 + 8)) == 0ull;
@@ -375,7 +392,7 @@ __global__ __launch_bounds__(kThreads) void literal_collect_kernel(LiteralArgs a
     __syncthreads();
     done = (r & 256) != 0;
   }
-  for (int i = tid; i < nbin; i += kThreads) {
+  for (int i = tid; i < nbin; i += NT) {
     const unsigned long long key = s_bin[i];
     if (key >= prefix) {
       const int slot = atomicAdd(&s_count, 1);
@@ -402,11 +419,16 @@ __global__ __launch_bounds__(kThreads) void literal_select_kernel(LiteralArgs a)
   __shared__ int s_kj[256];
   __shared__ unsigned long long s_pool[kPoolLds];
   __shared__ unsigned char s_pool_j[kPoolLds];
+  __shared__ LiteralPlan s_plan;
   const talon_tree_state& st = a.st;
   const int b = blockIdx.x;
-  const LiteralPlan p = a.plan[b];
-  if (!p.active) return;
   const int tid = threadIdx.x;
+  const LiteralPlan p = make_plan<kThreads>(a, b, s_red_u64, &s_plan);
+  if (!p.active) {
+    // a row of this layer could not be normalised: the sequence stops here
+    if (tid == 0 && (p.status & TALON_STATUS_BAD_ROW) && !(p.status & kDoneMask) && p.F > 0) st.frontier_count[b] = 0;
+    return;
+  }
   const int F = p.F < 256 ? p.F : 256;
   const size_t base = static_cast<size_t>(b) * st.N_pad;
   const unsigned long long* rows = a.row_key + (base + p.fb) * kLiteralRowCap;
@@ -560,10 +582,9 @@ __global__ __launch_bounds__(kThreads) void literal_select_kernel(LiteralArgs a)
 }  // namespace
 
 hipError_t launch_literal_layer(const LiteralArgs& a, int dtype, hipStream_t s) {
-  hipLaunchKernelGGL(literal_plan_kernel, dim3(a.st.B), dim3(kThreads), 0, s, a);
   const dim3 grid(a.st.N > 1 ? a.st.N - 1 : 1, a.st.B);
-  if (dtype == TALON_DTYPE_F32) hipLaunchKernelGGL(literal_collect_kernel<4>, grid, dim3(kThreads), 0, s, a);
-  else hipLaunchKernelGGL(literal_collect_kernel<8>, grid, dim3(kThreads), 0, s, a);
+  if (dtype == TALON_DTYPE_F32) hipLaunchKernelGGL(literal_collect_kernel<4>, grid, dim3(kCollectThreads), 0, s, a);
+  else hipLaunchKernelGGL(literal_collect_kernel<8>, grid, dim3(kCollectThreads), 0, s, a);
   hipLaunchKernelGGL(literal_select_kernel, dim3(a.st.B), dim3(kThreads), 0, s, a);
   return hipGetLastError();
 }

@@ -85,7 +85,7 @@ struct ExpandArgs {
 
 // Uncapped ("paper-literal") layer of Alg. 2: the pool of a parent is its whole row.
 constexpr int kLiteralRowCap = 256;   // survivors of one row that can still be chosen: at most N - 1 <= 255
-struct LiteralPlan {   // per sequence, written by the plan kernel of a layer
+struct LiteralPlan {   // what a layer does for one sequence
   double thr;          // gate threshold on the path score, log(mu) + anchor (-inf on top-K layers)
   int32_t active, F, fb, n, d, limit;
   uint32_t status;
@@ -102,7 +102,6 @@ struct LiteralArgs {
   const int32_t* scan_token;       // [B*N_pad][k_scan] the scan's candidates ...
   const float* top_logit;          // [B*N_pad][k_scan] ... and their logits; the first is the row's largest
   const double* row_lse;           // [B*N_pad]
-  LiteralPlan* plan;               // [B]
   int32_t* row_count;              // [B*N_pad] survivors kept of a row
   unsigned long long* row_key;     // [B*N_pad][kLiteralRowCap] their keys (sortable logit << 32 | ~token)
 };
