@@ -189,11 +189,12 @@ __global__ __launch_bounds__(kCollectThreads) void literal_collect_kernel(Litera
   __shared__ unsigned long long s_red_plan[NT / 64];
   __shared__ LiteralPlan s_plan;
   const int b = blockIdx.y;
-  const int j = blockIdx.x;
-  if (j >= a.st.frontier_count[b]) return;
+  if (static_cast<int>(blockIdx.x) >= a.st.frontier_count[b]) return;
   const LiteralPlan p = make_plan<NT>(a, b, s_red_plan, &s_plan);
   if (!p.active) return;
   const int tid = threadIdx.x;
+  // the workgroups of a sequence take its frontier rows in turn
+  auto collect_row = [&](const int j) {
   const int node = p.fb + j;
   const size_t out_row = static_cast<size_t>(b) * a.st.N_pad + node;
   const int in_row = a.row_mode == TALON_ROWS_BY_FRONTIER ? j : node;
@@ -261,9 +262,11 @@ __global__ __launch_bounds__(kCollectThreads) void literal_collect_kernel(Litera
   const unsigned long long lo = s_lo;
   const float x_lo = unsortable_f32(static_cast<uint32_t>(lo >> 32));   // logit >= x_lo: passes the gate
 
-  // f(valid, key) for every logit of the row that is >= x_min, the same number of calls in
-  // every lane of a wavefront; vectors in which no lane holds such a logit are skipped whole
-  auto for_each_key = [&](float x_min, auto&& f) {
+  // f(passes, logit image, ~token) for every logit of the row, the same number of calls in every
+  // lane of a wavefront; vectors in which no lane holds a passing logit are skipped whole.
+  // (logit >= x_lo is the gate: the float order and the order of the images agree.)  The
+  // 64-bit key (image << 32 | ~token) is put together only where a key is stored.
+  auto for_each_key = [&](auto&& f) {
     for (int base = 0; base < nvec; base += kVecAhead * NT) {
       uint4 raw[kVecAhead];
 #pragma unroll
@@ -279,30 +282,26 @@ __global__ __launch_bounds__(kCollectThreads) void literal_collect_kernel(Litera
 #pragma unroll
         for (int e = 0; e < EPL; ++e) {
           x[e] = vec_elem<EPL>(raw[u], e);
-          any = any || (t0 + e < a.vocab && x[e] >= x_min);
+          any = any || (t0 + e < a.vocab && x[e] >= x_lo);
         }
         if (__ballot(any) == 0ull) continue;
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) {
-          const int token = t0 + e;
-          const unsigned long long key = (static_cast<unsigned long long>(sortable_u32(x[e])) << 32) |
-                                         static_cast<unsigned long long>(0xFFFFFFFFu - static_cast<uint32_t>(token));
-          f(token < a.vocab && x[e] >= x_min, key);
-        }
+        for (int e = 0; e < EPL; ++e)
+          f(t0 + e < a.vocab && x[e] >= x_lo, sortable_u32(x[e]), 0xFFFFFFFFu - static_cast<uint32_t>(t0 + e));
       }
     }
   };
+  auto key64 = [](uint32_t k32, uint32_t tk) { return (static_cast<unsigned long long>(k32) << 32) | tk; };
 
   // first pass: count what passes the gate, keep it if it fits, histogram of the top digit
   // (slots are claimed only until the row has overflowed; after that a wavefront just counts)
   {
     bool overflow = false;
-    for_each_key(x_lo, [&](bool ok, unsigned long long key) {
-      const bool c = ok && key >= lo;
-      if (c) atomicAdd(&s_rep[static_cast<int>(key >> 56) * kHistCopies + copy], 1);
+    for_each_key([&](bool c, uint32_t k32, uint32_t tk) {
+      if (c) atomicAdd(&s_rep[static_cast<int>(k32 >> 24) * kHistCopies + copy], 1);
       if (!overflow) {
         const int slot = claim_slots(&s_count, c);
-        if (slot >= 0 && slot < kLiteralRowCap) out[slot] = key;
+        if (slot >= 0 && slot < kLiteralRowCap) out[slot] = key64(k32, tk);
         overflow = __ballot(slot >= kLiteralRowCap) != 0ull;
       }
     });
@@ -334,10 +333,18 @@ __global__ __launch_bounds__(kCollectThreads) void literal_collect_kernel(Litera
     if (pass > 0) {
       clear_copies();
       __syncthreads();
-      for_each_key(x_lo, [&](bool ok, unsigned long long key) {
-        const bool c = ok && key >= lo && ((key ^ prefix) >> (shift + 8)) == 0ull;
-        if (c) atomicAdd(&s_rep[(static_cast<int>(key >> shift) & 255) * kHistCopies + copy], 1);
-      });
+      const uint32_t pre32 = static_cast<uint32_t>(prefix >> 32), pre_tk = static_cast<uint32_t>(prefix);
+      if (pass < 4) {        // a byte of the logit image
+        const int s32 = shift - 32;
+        for_each_key([&](bool ok, uint32_t k32, uint32_t) {
+          if (ok && ((k32 ^ pre32) >> (s32 + 8)) == 0u) atomicAdd(&s_rep[((k32 >> s32) & 255u) * kHistCopies + copy], 1);
+        });
+      } else {               // a byte of ~token, among equal logits
+        for_each_key([&](bool ok, uint32_t k32, uint32_t tk) {
+          if (ok && k32 == pre32 && (pass == 4 || ((tk ^ pre_tk) >> (shift + 8)) == 0u))
+            atomicAdd(&s_rep[((tk >> shift) & 255u) * kHistCopies + copy], 1);
+        });
+      }
       sum_copies();
     }
     const int r = find_bin(s_hist, remaining, &s_digit, &s_want);
@@ -354,9 +361,10 @@ __global__ __launch_bounds__(kCollectThreads) void literal_collect_kernel(Litera
   if (found || !in_lds) {
     // every key >= prefix (its lower digits zero) is kept
     const unsigned long long T = prefix > lo ? prefix : lo;
-    for_each_key(x_lo, [&](bool ok, unsigned long long key) {
-      const int slot = claim_slots(&s_count, ok && key >= T);
-      if (slot >= 0 && slot < cap) out[slot] = key;
+    const uint32_t T32 = static_cast<uint32_t>(T >> 32), T_tk = static_cast<uint32_t>(T);
+    for_each_key([&](bool ok, uint32_t k32, uint32_t tk) {
+      const int slot = claim_slots(&s_count, ok && (k32 > T32 || (k32 == T32 && tk >= T_tk)));
+      if (slot >= 0 && slot < cap) out[slot] = key64(k32, tk);
     });
     __syncthreads();
     if (tid == 0) a.row_count[out_row] = s_count < cap ? s_count : cap;
@@ -364,14 +372,27 @@ __global__ __launch_bounds__(kCollectThreads) void literal_collect_kernel(Litera
   }
 
   // keys above the bin are kept; the bin itself goes to LDS, where the search continues
-  for_each_key(x_lo, [&](bool ok, unsigned long long key) {
-    const bool c = ok && key >= lo;
-    const unsigned long long hi_part = key >> shift, bin = prefix >> shift;
-    const int slot = claim_slots(&s_count, c && hi_part > bin);
-    if (slot >= 0 && slot < cap) out[slot] = key;
-    const int slot2 = claim_slots(&s_nbin, c && hi_part == bin);
-    if (slot2 >= 0 && slot2 < kLdsKeys) s_bin[slot2] = key;
-  });
+  {
+    const uint32_t pre32 = static_cast<uint32_t>(prefix >> 32), pre_tk = static_cast<uint32_t>(prefix);
+    const bool logit_stage = shift >= 32;
+    const int s32 = logit_stage ? shift - 32 : 0;
+    for_each_key([&](bool ok, uint32_t k32, uint32_t tk) {
+      bool above, inbin;
+      if (logit_stage) {
+        const uint32_t hi_part = k32 >> s32, bin = pre32 >> s32;
+        above = hi_part > bin;
+        inbin = hi_part == bin;
+      } else {
+        const uint32_t hi_part = tk >> shift, bin = pre_tk >> shift;
+        above = k32 > pre32 || (k32 == pre32 && hi_part > bin);
+        inbin = k32 == pre32 && hi_part == bin;
+      }
+      const int slot = claim_slots(&s_count, ok && above);
+      if (slot >= 0 && slot < cap) out[slot] = key64(k32, tk);
+      const int slot2 = claim_slots(&s_nbin, ok && inbin);
+      if (slot2 >= 0 && slot2 < kLdsKeys) s_bin[slot2] = key64(k32, tk);
+    });
+  }
   __syncthreads();
   const int nbin = s_nbin < kLdsKeys ? s_nbin : kLdsKeys;
   bool done = false;
@@ -401,6 +422,11 @@ __global__ __launch_bounds__(kCollectThreads) void literal_collect_kernel(Litera
   }
   __syncthreads();
   if (tid == 0) a.row_count[out_row] = s_count < cap ? s_count : cap;
+  };
+  for (int j = blockIdx.x; j < p.F; j += gridDim.x) {
+    collect_row(j);
+    __syncthreads();   // the row's LDS is reused by the next one
+  }
 }
 
 constexpr int kPoolLds = 4096;   // survivors of a layer that the budget check holds in LDS
@@ -582,7 +608,12 @@ __global__ __launch_bounds__(kThreads) void literal_select_kernel(LiteralArgs a)
 }  // namespace
 
 hipError_t launch_literal_layer(const LiteralArgs& a, int dtype, hipStream_t s) {
-  const dim3 grid(a.st.N > 1 ? a.st.N - 1 : 1, a.st.B);
+  // rows of a sequence share workgroups when there are more rows than the device holds
+  // workgroups at once (two per compute unit): launches that find nothing to do stay short
+  int per_seq = 512 / a.st.B;
+  if (per_seq < 32) per_seq = 32;
+  const int most = a.st.N > 1 ? a.st.N - 1 : 1;
+  const dim3 grid(per_seq < most ? per_seq : most, a.st.B);
   if (dtype == TALON_DTYPE_F32) hipLaunchKernelGGL(literal_collect_kernel<4>, grid, dim3(kCollectThreads), 0, s, a);
   else hipLaunchKernelGGL(literal_collect_kernel<8>, grid, dim3(kCollectThreads), 0, s, a);
   hipLaunchKernelGGL(literal_select_kernel, dim3(a.st.B), dim3(kThreads), 0, s, a);
