@@ -199,3 +199,38 @@ def test_c3_qwen3_8b_x4_full_size_uncapped():
 
 def test_c5_stress_full_size_uncapped():
     _full_size("c5", [3, 12])
+
+
+def test_repeated_calls_on_one_workspace_agree():
+    """Survivors are collected in whatever order the lanes claim their slots; the tree must not
+    depend on it, nor on what an earlier call left in the workspace (a different, larger shape
+    first, then the same call twenty times)."""
+    import torch
+    import paper_2601_07353_amd as T
+    big = CASES["zipf-bf16-n256"]
+    cfg = CASES["qwen-bf16-n128"]
+    dt = T.TALON_DTYPE_BF16
+    ws = T.make_literal_workspace(big.B, big.N_pad, big.V, dt)
+    assert ws.numel() >= T.load_library().talon_literal_workspace_bytes(cfg.B, cfg.N_pad, cfg.V, dt)
+
+    def run(c, pool_dev):
+        st = T.TreeState(c.B, c.N)
+        T.talon_tree_init(st, torch.from_numpy(H.root_tokens(c)).cuda())
+        T.talon_expand_literal(pool_dev, st, c.Dmax, c.mu, c.K, 1, c.Dmax, ws)
+        torch.cuda.synchronize()
+        n = st.n_nodes.cpu().numpy()
+        return [n] + [getattr(st, f).cpu().numpy() for f in ("token", "parent", "depth", "prob", "logp", "status")]
+
+    run(big, H.to_device_logits(H.build_pool(big, [big.seed] * big.B)))
+    dev = H.to_device_logits(H.build_pool(cfg, [cfg.seed, cfg.seed + 100]))
+    first = run(cfg, dev)
+    assert all(int(v) == cfg.N for v in first[0])
+    for _ in range(20):
+        again = run(cfg, dev)
+        for x, y in zip(first, again):
+            n = first[0]
+            if x.ndim == 2:
+                for b in range(cfg.B):
+                    np.testing.assert_array_equal(x[b, :n[b]], y[b, :n[b]])
+            else:
+                np.testing.assert_array_equal(x, y)
