@@ -234,3 +234,39 @@ def test_repeated_calls_on_one_workspace_agree():
                     np.testing.assert_array_equal(x[b, :n[b]], y[b, :n[b]])
             else:
                 np.testing.assert_array_equal(x, y)
+
+
+def test_random_small_configurations():
+    """Thirty seeded random shapes (vocabulary 8 to 60001, both logit types, N 2-256, K_init 1-19
+    -- above 16 the top-K layers take the streaming route too --, 1-3 sequences, 0-2 top-K layers,
+    four thresholds and recipes, depth cap from 1), alternately in one call and one call per
+    layer.  Configurations whose oracle tree leaves no margin are skipped; most must run."""
+    from oracle import talon_oracle as O
+    from workloads import WorkloadConfig
+    rng = np.random.default_rng(20260107)
+    ran = 0
+    for it in range(30):
+        dtype = str(rng.choice(["f32", "bf16"]))
+        V = int(rng.choice([8, 63, 500, 4099, 20000, 60001]))
+        N = int(rng.integers(2, 257))
+        K = int(rng.integers(1, 20))
+        B = int(rng.integers(1, 4))
+        init_layers = int(rng.integers(0, 3))
+        mu = float(rng.choice([0.3, 0.03, 0.003, 1e-6]))
+        rec = [("gauss", 0.5, 4.0), ("gauss", 0.05, 0.3), ("gauss", 4.0, 8.0), ("zipf_mix", 1.2, 0.05)][int(rng.integers(0, 4))]
+        Dmax = int(rng.integers(1, 10))
+        if B * ((N + 63) // 64 * 64) * V > 60e6:
+            V = 4099
+        cfg = WorkloadConfig("literal-random-%d" % it, B=B, V=V, logits_dtype=dtype, K=K, N=N, Dmax=Dmax, mu=mu,
+                             Hq=4, Hkv=4, Dh=64, L=16, recipe=rec, seed=1000 + it)
+        pool = H.build_pool(cfg, [cfg.seed + 7 * b for b in range(B)])
+        roots = H.root_tokens(cfg)
+        trees = [H.oracle_tree(cfg, pool[b], roots[b], init_layers=init_layers, cap=max(N - 1, 1)) for b in range(B)]
+        if min(t.margin for t in trees) <= H.MARGIN_TOL:
+            continue
+        print("case", it, dtype, "V", V, "N", N, "K", K, "B", B, "init", init_layers, "mu", mu, rec, "Dmax", Dmax, flush=True)
+        gpu = H.run_gpu_literal(cfg, pool, K, init_layers=init_layers, layer_by_layer=bool(it % 2))
+        H.compare_tree(cfg, gpu, trees, check_rows=False)
+        H.compare_mask(cfg, gpu, [O.build_tree_mask(t.parent) for t in trees])
+        ran += 1
+    assert ran >= 24
