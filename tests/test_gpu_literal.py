@@ -270,3 +270,46 @@ def test_random_small_configurations():
         H.compare_mask(cfg, gpu, [O.build_tree_mask(t.parent) for t in trees])
         ran += 1
     assert ran >= 24
+
+
+def test_dense_frontier_batches_with_padded_rows():
+    """The layout a serving loop has: after every layer the draft model's logits exist for the
+    new frontier only, as a dense batch [B][frontier rows][padded row] (TALON_ROWS_BY_FRONTIER,
+    row stride larger than the vocabulary, values in the padding that would win any maximum).
+    One uncapped call per layer on a freshly gathered batch must build the oracle's tree."""
+    import torch
+    import paper_2601_07353_amd as T
+    from tests.test_gpu_parity import small
+    cfg = small(name="literal-dense", V=20011, logits_dtype="bf16", K=6, N=150, Dmax=9, B=3,
+                recipe=(("gauss", 4.0, 8.0), ("gauss", 0.5, 1.0), ("gauss", 2.0, 6.0)))
+    cap = cfg.N - 1
+    seeds = [H.find_admissible_seed(cfg, b, cfg.seed + 100 * b, cap=cap)[0] for b in range(cfg.B)]
+    pool = H.build_pool(cfg, seeds)
+    roots = H.root_tokens(cfg)
+    trees = [H.oracle_tree(cfg, pool[b], roots[b], cap=cap) for b in range(cfg.B)]
+    pool_dev = H.to_device_logits(pool)                      # [B][N_pad][V], only used to gather from
+    stride = (cfg.V + 8 + 63) // 64 * 64
+    st = T.TreeState(cfg.B, cfg.N)
+    ws = T.make_literal_workspace(cfg.B, st.N_pad, cfg.V, T.TALON_DTYPE_BF16)
+    T.talon_tree_init(st, torch.from_numpy(roots).cuda())
+    for _ in range(cfg.Dmax):
+        begin = st.frontier_begin.cpu().numpy()
+        count = st.frontier_count.cpu().numpy()
+        done = (st.status.cpu().numpy() & 3) != 0
+        if done.all():
+            break
+        fmax = max(1, int(count.max()))
+        dense = torch.full((cfg.B, fmax, stride), 30000.0, dtype=torch.bfloat16, device="cuda")
+        for b in range(cfg.B):
+            if not done[b]:
+                dense[b, :count[b], :cfg.V] = pool_dev[b, begin[b]:begin[b] + count[b]]
+        T.talon_expand_literal(dense, st, 1, cfg.mu, cfg.K, 1, cfg.Dmax, ws, row_mode=T.TALON_ROWS_BY_FRONTIER,
+                               vocab=cfg.V)
+        torch.cuda.synchronize()
+    n = st.n_nodes.cpu().numpy()
+    for b, t in enumerate(trees):
+        assert int(n[b]) == t.n
+        np.testing.assert_array_equal(st.token[b, :t.n].cpu().numpy(), np.asarray(t.token, dtype=np.int32))
+        np.testing.assert_array_equal(st.parent[b, :t.n].cpu().numpy(), np.asarray(t.parent, dtype=np.int32))
+        np.testing.assert_allclose(np.exp(st.logp[b, :t.n].cpu().numpy()), t.confidence(), rtol=H.PROB_RTOL, atol=0)
+    assert max(int(np.bincount(np.asarray(t.parent[1:])).max()) for t in trees) > cfg.K
