@@ -66,6 +66,7 @@ __device__ unsigned long long g_wg[1024][16];   // per-workgroup time stamps of 
 #endif
 __device__ unsigned long long g_tl[32][4];      // single-launch kernel: per-layer time stamps of workgroup 0
 #define TL_MARK(d, i) do { if (threadIdx.x == 0 && blockIdx.x == 0 && (d) < 32) g_tl[d][i] = wall_clock64(); } while (0)
+#define TL_ANY(d, i) do { if (threadIdx.x == 0 && (d) < 32) g_tl[d][i] = wall_clock64(); } while (0)
 #ifdef TALON_TIMELINE_ONLY
 #define WG_MARK_LOADED(i) do { } while (0)
 #else
@@ -74,6 +75,7 @@ __device__ unsigned long long g_tl[32][4];      // single-launch kernel: per-lay
 #else
 #define WG_MARK(i) do { } while (0)
 #define TL_MARK(d, i) do { } while (0)
+#define TL_ANY(d, i) do { } while (0)
 #define WG_MARK2(i) do { } while (0)
 #define WG_MARK_LOADED(i) do { } while (0)
 #define PHASE(i) do { } while (0)
@@ -785,6 +787,7 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
         }
         __syncthreads();
         if (s_last) {
+          TL_ANY(launch_idx, 2);
           // A launch that started the tree itself knows the sequence's status (nothing but a
           // row that cannot be normalised can have touched it), its size and its layer
           // without asking memory.
@@ -808,6 +811,7 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
             __syncthreads();
             if (tid == 0 && launch_idx + 1 < a.N_pad)
               st_<true, unsigned long long>(a.desc + ((launch_idx + 1) * a.B + b), next | kDescReady);
+            TL_ANY(launch_idx, 3);
           }   // (a launch of one layer leaves no descriptor: the next call starts from the public state)
         }
       }
