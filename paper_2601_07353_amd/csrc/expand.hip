@@ -419,6 +419,10 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
   // ---- chunks per row from the width of this layer
   const int blocks_per_row = a.chunks;
   int chunks = (a.target_items + total_rows - 1) / total_rows;
+  {   // ... and at least as many as give every workgroup of the grid an item in the first round
+    const int fill = static_cast<int>(gridDim.x) / total_rows;
+    chunks = fill > chunks ? fill : chunks;
+  }
   chunks = chunks < 1 ? 1 : (chunks > blocks_per_row ? blocks_per_row : chunks);
   const int bpc = (blocks_per_row + chunks - 1) / chunks;   // blocks per chunk
   chunks = (blocks_per_row + bpc - 1) / bpc;
