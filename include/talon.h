@@ -190,9 +190,11 @@ int talon_build_tree(const int32_t* root_token, const void* logits, int dtype, i
  * Strategy" and "Budget Check"): S_d holds every token of every frontier row, with no per-row
  * cap, for any budget N <= TALON_N_MAX.  The calls above cap a row at k <= TALON_K_MAX
  * candidates, which gives the same tree whenever k >= N - |T|; this is the general, slower
- * form: per layer one vocabulary scan for the row statistics, then per frontier row the
- * tokens that pass the gate (at most the remaining budget of them, found by a radix select
- * over the row when more pass), then per sequence the budget check over what the rows kept.
+ * form: per layer one vocabulary scan for the row statistics and the 16 best tokens of every
+ * row, then per frontier row the tokens that pass the gate (at most the remaining budget of
+ * them; rows of which fewer than 16 pass are settled by the scan, the others are read again,
+ * with a radix select over the row when more pass than can be taken), then per sequence the
+ * budget check over what the rows kept.
  * Runs `layers` >= 1 layers from the tree state as it stands (1: one layer between two draft
  * passes; >= max_depth: the whole loop); sequences that are finished are skipped.  Same tree
  * state, node order, ties and status bits as talon_expand_select_layer; no candidate

@@ -440,9 +440,10 @@ int talon_expand_literal(const void* logits, int dtype, int64_t row_stride, int6
   if (rc) return rc;
   char* w = static_cast<char*>(workspace);
   ExpandLayout L;
-  // On top-K layers the scan ranks K_init candidates per row (the pool's K_init best hold no
-  // more of one row); otherwise only the row statistics are wanted.
-  const int k_scan = (init_layers > 0 && K_init >= 1 && K_init <= V.k_max) ? K_init : 1;
+  // The scan ranks the 16 best tokens of every row where the workspace has room for them: on
+  // top-K layers with K_init <= 16 they are the row's survivors, and on gated layers they settle
+  // every row of which fewer than 16 tokens pass the gate; other rows are read a second time.
+  const int k_scan = V.k_max;
   // the scan's own checks (pointers, alignment, strides), its outputs in the workspace
   rc = check_expand_args(logits, dtype, row_stride, seq_stride, row_mode, st, vocab, k_scan, w ? w + V.off_token : nullptr,
                          w ? w + V.off_logit : nullptr, w ? w + V.off_prob : nullptr, w ? w + V.off_edge : nullptr,

@@ -238,7 +238,6 @@ __global__ __launch_bounds__(kCollectThreads) void literal_collect_kernel(Litera
     }
     __syncthreads();
   };
-  clear_copies();
   if (tid == 0) {
     s_count = 0;
     s_nbin = 0;
@@ -257,10 +256,36 @@ __global__ __launch_bounds__(kCollectThreads) void literal_collect_kernel(Litera
       res = l;
     }
     s_lo = static_cast<unsigned long long>(res) << 32;
+    s_digit = 0;
   }
   __syncthreads();
   const unsigned long long lo = s_lo;
   const float x_lo = unsortable_f32(static_cast<uint32_t>(lo >> 32));   // logit >= x_lo: passes the gate
+
+  // The scan has ranked the row's k_scan best tokens.  Those that pass the gate are the first
+  // of them; if not all pass, no other token of the row does, and the row is settled
+  // without reading it again (the rule for peaked rows, and for rows far below the anchor).
+  if (a.k_scan >= 2 && tid < 64) {
+    unsigned long long key = 0ull;
+    bool ok = false;
+    if (tid < a.k_scan) {
+      const int tok = a.scan_token[out_row * a.k_scan + tid];
+      key = (static_cast<unsigned long long>(sortable_u32(a.top_logit[out_row * a.k_scan + tid])) << 32) |
+            static_cast<unsigned long long>(0xFFFFFFFFu - static_cast<uint32_t>(tok));
+      ok = tok >= 0 && key >= lo;
+    }
+    const unsigned long long vb = __ballot(ok);
+    const int n_pass = vb == ~0ull ? 64 : __builtin_ctzll(~vb);   // the passing candidates come first
+    if (n_pass < a.k_scan) {
+      const int m = n_pass < cap ? n_pass : cap;
+      if (tid < m) out[tid] = key;
+      if (tid == 0) { a.row_count[out_row] = m; s_digit = 1; }
+    }
+  }
+  __syncthreads();
+  if (s_digit) return;
+  clear_copies();
+  __syncthreads();
 
   // f(passes, logit image, ~token) for every logit of the row, the same number of calls in every
   // lane of a wavefront; vectors in which no lane holds a passing logit are skipped whole.
