@@ -470,6 +470,8 @@ __global__ __launch_bounds__(kThreads) void literal_select_kernel(LiteralArgs a)
   __shared__ int s_kj[256];
   __shared__ unsigned long long s_pool[kPoolLds];
   __shared__ unsigned char s_pool_j[kPoolLds];
+  __shared__ unsigned long long s_fin_hi[kThreads], s_fin_lo[kThreads];
+  __shared__ int s_nfin;
   __shared__ LiteralPlan s_plan;
   const talon_tree_state& st = a.st;
   const int b = blockIdx.x;
@@ -578,11 +580,42 @@ __global__ __launch_bounds__(kThreads) void literal_select_kernel(LiteralArgs a)
       });
       wh.flush();
       const int r = find_bin(s_hist, remaining, &s_digit, &s_want);
+      const int population = s_hist[r & 255];
       if (first_key) pre_hi |= static_cast<unsigned long long>(r & 255) << shift;
       else pre_lo |= static_cast<unsigned long long>(r & 255) << shift;
       remaining = s_want;
       __syncthreads();
       if (r & 256) break;
+      if (population <= kThreads) {
+        // The bin fits one key per thread: rank its keys by counting and take the cut from
+        // there.  (Scores of bf16 rows tie in whole groups, and a cut inside such a group
+        // would otherwise walk every remaining digit of both keys.)
+        if (tid == 0) s_nfin = 0;
+        __syncthreads();
+        for_each([&](bool valid, int j, unsigned long long key) {
+          const unsigned long long hi = (score_key(j, key) - low + 1ull) << sh;
+          const unsigned long long lo2 = order_key(j, key);
+          const bool in_bin = valid && (first_key ? ((hi ^ pre_hi) >> shift) == 0ull
+                                                  : (hi == pre_hi && ((lo2 ^ pre_lo) >> shift) == 0ull));
+          const int slot = claim_slots(&s_nfin, in_bin);
+          if (slot >= 0 && slot < kThreads) { s_fin_hi[slot] = hi; s_fin_lo[slot] = lo2; }
+        });
+        __syncthreads();
+        const int nf = s_nfin < kThreads ? s_nfin : kThreads;
+        if (tid < nf) {
+          const unsigned long long mh = s_fin_hi[tid], ml = s_fin_lo[tid];
+          int rank = 0;
+          for (int i = 0; i < nf; ++i) {
+            const unsigned long long oh = s_fin_hi[i], ol = s_fin_lo[i];
+            rank += (oh > mh || (oh == mh && ol > ml)) ? 1 : 0;
+          }
+          if (rank == remaining - 1) { s_red_u64[0] = mh; s_red_u64[1] = ml; }   // keys are unique: one thread
+        }
+        __syncthreads();
+        pre_hi = s_red_u64[0];
+        pre_lo = s_red_u64[1];
+        break;
+      }
     }
   }
 
