@@ -10,8 +10,20 @@ from workloads import WorkloadConfig, attention_inputs, bf16_bits_to_f64, logits
 
 MARGIN_TOL = 1e-4   # smallest cross-parent score gap a seed must leave (log units)
 PROB_RTOL = 1e-5    # probabilities and path confidences, relative
-ATTN_ATOL = 2e-2    # tree-attention outputs, absolute (bf16 inputs, fp64 oracle)
+ATTN_ATOL = 2e-2    # tree-attention outputs, absolute (bf16 inputs, fp64 oracle): the stated bound
 LSE_ATOL = 2e-6     # row log-sum-exp, absolute
+# Beside the stated bound, one tied to the signal, so that at long prefixes (outputs of a few
+# hundredths) a lost tree key or a wrong mask bit cannot hide below 2e-2.  The kernel rounds the
+# softmax weights to bf16 before the P.V product and the result to bf16:
+#   output rounding      <= 2^-8 |out|   (half a unit in the last of 8 significant bits)
+#   weight rounding      each weight off by a relative delta_j, |delta_j| <= 2^-8, independent:
+#                        error = sum_j p_j delta_j v_j, standard deviation about
+#                        2^-8 / sqrt(3) * sqrt(sum_j p_j^2) for unit-variance values; with
+#                        N(0,1) scores sum_j p_j^2 is about e / keys, i.e. 3.7e-3 / sqrt(keys);
+#                        six standard deviations (millions of elements are compared)
+ATTN_OUT_RTOL = 2.0 ** -8
+ATTN_KEYS_ATOL = 2.2e-2      # divided by sqrt(number of keys the row attends to)
+ATTN_LSE_ATOL = 1e-4         # fp32 scores and denominators against fp64 (observed worst about 1e-5)
 
 
 def seeds_for(cfg: WorkloadConfig, seeds=None):
@@ -70,6 +82,19 @@ def find_admissible_seed(cfg: WorkloadConfig, b: int, base_seed: int, tol: float
         if t.margin > tol:
             return s, t
     raise RuntimeError("no admissible seed found for %s sequence %d" % (cfg.name, b))
+
+
+def admissible_pool(cfg: WorkloadConfig, make_pool, tries: int = 16, **tree_kw):
+    """First of make_pool(0), make_pool(1), ... whose oracle trees all leave every cross-parent
+    decision a margin > MARGIN_TOL.  Returns (pool, trees); fails the test if none qualifies, so
+    a case can never go untested in silence."""
+    roots = root_tokens(cfg)
+    for attempt in range(tries):
+        pool = make_pool(attempt)
+        trees = [oracle_tree(cfg, pool[b], roots[b], **tree_kw) for b in range(cfg.B)]
+        if min(t.margin for t in trees) > MARGIN_TOL:
+            return pool, trees
+    raise AssertionError("no admissible pool among %d tries for %s" % (tries, cfg.name))
 
 
 def run_oracle_step(cfg: WorkloadConfig, seeds=None, pool=None, attn=None, attn_nodes=None, attn_heads=None,
@@ -222,6 +247,7 @@ def run_gpu_step(cfg: WorkloadConfig, seeds=None, pool=None, attn=None, with_att
         torch.cuda.synchronize()
         res["attn_out"] = out.float().cpu().numpy()
         res["attn_lse"] = lse.cpu().numpy()
+        res["prefix_len"] = L
     return res
 
 
@@ -259,20 +285,37 @@ def compare_mask(cfg: WorkloadConfig, gpu: dict, masks):
         np.testing.assert_array_equal(gpu["mask"][b], O.mask_to_words(m, cfg.N_pad))
 
 
+def check_attention_rows(got_out, got_lse, want_out, want_lse, keys, where=()):
+    """Rows [n][Hq][Dh] of one sequence against the oracle's (NaN = not computed, skipped).
+    `keys`: keys each node attends to (a number, or one per node).  Two bounds on every element:
+    the stated 2e-2 absolute, and the signal-tied one derived above.  Returns the worst output
+    and LSE errors."""
+    sel = ~np.isnan(want_out)
+    assert sel.any(), where
+    err = np.abs(got_out - np.where(sel, want_out, 0.0))
+    err = np.where(sel, err, 0.0)
+    worst = float(err.max())
+    assert worst <= ATTN_ATOL, (where, worst)
+    keys = np.broadcast_to(np.asarray(keys, dtype=np.float64), want_out.shape[:1])
+    tol = ATTN_OUT_RTOL * np.abs(np.where(sel, want_out, 0.0)) + (ATTN_KEYS_ATOL / np.sqrt(keys))[:, None, None]
+    bad = err > tol
+    assert not bad.any(), (where, "signal-tied bound", float((err / tol).max()), np.argwhere(bad)[:4].tolist())
+    worst_lse = 0.0
+    if got_lse is not None:
+        sl = ~np.isnan(want_lse)
+        worst_lse = float(np.abs(got_lse[sl] - want_lse[sl]).max())
+        assert worst_lse <= ATTN_LSE_ATOL, (where, worst_lse)
+    return worst, worst_lse
+
+
 def compare_attention(cfg: WorkloadConfig, gpu: dict, ref: dict):
     worst = 0.0
     for b in range(cfg.B):
         want = ref["attn_out"][b]
         n = want.shape[0]
-        got = gpu["attn_out"][b, :n]
-        sel = ~np.isnan(want)
-        assert sel.any()
-        err = np.abs(got[sel] - want[sel]).max()
-        worst = max(worst, float(err))
-        assert err <= ATTN_ATOL, (b, err)
-        wl = ref["attn_lse"][b]
-        sl = ~np.isnan(wl)
-        assert np.abs(gpu["attn_lse"][b, :n][sl] - wl[sl]).max() <= 2e-3
+        keys = ref["keys"][b] if "keys" in ref else gpu["prefix_len"] + ref["mask"][b].sum(axis=1)
+        w, _ = check_attention_rows(gpu["attn_out"][b, :n], gpu["attn_lse"][b, :n], want, ref["attn_lse"][b], keys, (b,))
+        worst = max(worst, w)
         # rows beyond n_nodes must be untouched (the harness pre-fills the output with zeros)
         assert not gpu["attn_out"][b, n:].any()
     return worst

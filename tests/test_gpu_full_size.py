@@ -1,9 +1,11 @@
 """GPU parity at the full sizes of the benchmark configurations, in the launch configuration
 bench.py times (one talon_build_tree call: init, loop and mask; one talon_tree_attention call).
 
-Where the oracle cannot finish the whole configuration in seconds, it checks a stated sample
-(some sequences in full for the expansion, sampled (node, head) pairs for attention) and the
-remaining outputs are checked through properties that hold at any size."""
+Expansion: every sequence of every configuration is built by the oracle and compared bit for bit
+(c5: all sixteen trees).  Tree attention: every (node, head) pair at c3 and c4; at c5, where the
+oracle's fp64 loops would take minutes, a stated sample: all nodes x 2 heads x 2 sequences plus
+256 random (sequence, head, node) triples.  Every output also goes through the properties that
+hold at any size."""
 import numpy as np
 import pytest
 
@@ -43,61 +45,92 @@ def structural_checks(cfg, gpu, b):
     assert not words[n:].any()
 
 
-def sampled_attention_check(cfg, gpu, b, tree, mask, x, nodes, heads):
+class Decoded:
+    """fp64 copies of one sequence's attention inputs (decoded once, used for many oracle calls)."""
+
+    def __init__(self, x, n):
+        self.q = bf16_bits_to_f64(x["q"][:n])
+        self.kp, self.vp = bf16_bits_to_f64(x["k_prefix"]), bf16_bits_to_f64(x["v_prefix"])
+        self.kt, self.vt = bf16_bits_to_f64(x["k_tree"][:n]), bf16_bits_to_f64(x["v_tree"][:n])
+
+
+def attention_check(cfg, gpu, b, mask, dec, nodes=None, heads=None):
+    """Oracle attention of sequence b on the given nodes and heads (None: all of them) against the
+    GPU's rows, through the harness's bounds.  Returns (worst output error, worst LSE error)."""
     from oracle import talon_oracle as O
-    n = tree.n
-    out, lse = O.tree_attention(bf16_bits_to_f64(x["q"][:n]), bf16_bits_to_f64(x["k_prefix"]),
-                                bf16_bits_to_f64(x["v_prefix"]), bf16_bits_to_f64(x["k_tree"][:n]),
-                                bf16_bits_to_f64(x["v_tree"][:n]), mask, nodes=nodes, heads=heads)
-    worst = 0.0
-    for i in nodes:
-        for h in heads:
-            err = float(np.abs(gpu["attn_out"][b, i, h] - out[i, h]).max())
-            worst = max(worst, err)
-            assert err <= H.ATTN_ATOL, (b, i, h, err)
-            assert abs(float(gpu["attn_lse"][b, i, h]) - lse[i, h]) <= 2e-3
-    return worst
+    out, lse = O.tree_attention(dec.q, dec.kp, dec.vp, dec.kt, dec.vt, mask, nodes=nodes, heads=heads)
+    n = out.shape[0]
+    return H.check_attention_rows(gpu["attn_out"][b, :n], gpu["attn_lse"][b, :n], out, lse,
+                                  cfg.L + mask.sum(axis=1), (b,))
 
 
-def spread(n, count):
-    return sorted(set([0, n - 1] + [int(v) for v in np.linspace(0, n - 1, count)]))
-
-
-def run_full(cfg_name, oracle_seqs, n_nodes_sample, heads):
+def run_config(cfg_name):
+    """GPU step on admissible seeds for every sequence; every tree and mask against the oracle."""
     from oracle import talon_oracle as O
     cfg = CONFIGS[cfg_name]
-    seeds = [cfg.seed] * cfg.B
-    for b in oracle_seqs:
-        seeds[b] = H.find_admissible_seed(cfg, b, cfg.seed)[0]
-    print("case", cfg.name, "seeds", seeds, "oracle sequences", oracle_seqs, flush=True)
+    found = [H.find_admissible_seed(cfg, b, cfg.seed) for b in range(cfg.B)]
+    seeds = [s for s, _ in found]
+    trees = [t for _, t in found]
+    print("case", cfg.name, "seeds", seeds, flush=True)
     pool = H.build_pool(cfg, seeds)
     attn = [attention_inputs(cfg, seeds[b], b) for b in range(cfg.B)]
     gpu = H.run_gpu_step(cfg, seeds, pool=pool, attn=attn)
-    roots = H.root_tokens(cfg)
+    del pool
+    masks = []
     for b in range(cfg.B):
         structural_checks(cfg, gpu, b)
-    worst = 0.0
-    for b in oracle_seqs:
-        t = H.oracle_tree(cfg, pool[b], roots[b])
-        assert t.margin > H.MARGIN_TOL
-        sub = {k: v[b:b + 1] for k, v in gpu.items()}
-        H.compare_tree(cfg, sub, [t])
-        m = O.build_tree_mask(t.parent)
-        np.testing.assert_array_equal(gpu["mask"][b], O.mask_to_words(m, cfg.N_pad))
-        worst = max(worst, sampled_attention_check(cfg, gpu, b, t, m, attn[b], spread(t.n, n_nodes_sample), heads))
-    # rows of nodes beyond n_nodes are untouched in every sequence
-    for b in range(cfg.B):
+        assert trees[b].margin > H.MARGIN_TOL
+        H.compare_tree(cfg, {k: v[b:b + 1] for k, v in gpu.items()}, [trees[b]])
+        masks.append(O.build_tree_mask(trees[b].parent))
+        np.testing.assert_array_equal(gpu["mask"][b], O.mask_to_words(masks[b], cfg.N_pad))
+        # rows of nodes beyond n_nodes are untouched
         assert not gpu["attn_out"][b, int(gpu["n_nodes"][b]):].any()
-    print(cfg.name, "sampled attention worst abs err", worst, flush=True)
+    return cfg, gpu, trees, masks, attn
+
+
+def run_full(cfg_name):
+    cfg, gpu, trees, masks, attn = run_config(cfg_name)
+    worst = (0.0, 0.0)
+    for b in range(cfg.B):
+        w = attention_check(cfg, gpu, b, masks[b], Decoded(attn[b], trees[b].n))
+        worst = (max(worst[0], w[0]), max(worst[1], w[1]))
+    print(cfg.name, "attention over all (node, head) pairs: worst abs err", worst[0], "worst LSE err", worst[1], flush=True)
 
 
 def test_c3_qwen3_8b_x4_full_size():
-    run_full("c3", oracle_seqs=[0, 1, 2, 3], n_nodes_sample=8, heads=[0, 5, 17, 31])
+    run_full("c3")
 
 
 def test_c4_70b_shaped_full_size():
-    run_full("c4", oracle_seqs=[0], n_nodes_sample=8, heads=[0, 7, 8, 33, 63])
+    run_full("c4")
 
 
-def test_c5_stress_full_size():
-    run_full("c5", oracle_seqs=[3, 12], n_nodes_sample=5, heads=[2, 29])
+@pytest.fixture(scope="module")
+def c5_run():
+    return run_config("c5")     # sixteen trees and masks against the oracle
+
+
+def test_c5_stress_full_size_all_trees(c5_run):
+    cfg, gpu, trees, _, _ = c5_run
+    assert len(trees) == 16 and all(t.n == int(gpu["n_nodes"][b]) for b, t in enumerate(trees))
+
+
+def test_c5_stress_full_size_attention_sample(c5_run):
+    """All nodes x heads {2, 29} x sequences {3, 12}, then 256 random (sequence, head, node) triples."""
+    cfg, gpu, trees, masks, attn = c5_run
+    worst = [0.0, 0.0]
+
+    def note(w):
+        worst[0], worst[1] = max(worst[0], w[0]), max(worst[1], w[1])
+
+    for b in (3, 12):
+        note(attention_check(cfg, gpu, b, masks[b], Decoded(attn[b], trees[b].n), heads=[2, 29]))
+    rng = np.random.default_rng(20260107)
+    triples = [(int(rng.integers(cfg.B)), int(rng.integers(cfg.Hq)), 0) for _ in range(256)]
+    triples = sorted((b, h, int(rng.integers(trees[b].n))) for b, h, _ in triples)
+    dec, dec_b = None, -1
+    for b, h, i in triples:
+        if b != dec_b:
+            dec, dec_b = Decoded(attn[b], trees[b].n), b
+        note(attention_check(cfg, gpu, b, masks[b], dec, nodes=[i], heads=[h]))
+    print(cfg.name, "sampled attention worst abs err", worst[0], "worst LSE err", worst[1], flush=True)

@@ -152,6 +152,87 @@ def test_select_budget_vs_bruteforce_layer(seed):
         assert got == want
 
 
+# ---------------------------------------------------------------- decision margin
+def _random_layer(rng):
+    """A random pool: F parents with path confidences and rows close enough together that
+    cross-parent comparisons are tight."""
+    V = int(rng.integers(4, 9))
+    cap = int(rng.integers(1, V + 1))
+    F = int(rng.integers(1, 6))
+    parents = list(range(20, 20 + F))
+    logp = {v: math.log(rng.uniform(0.2, 1.0)) for v in parents}
+    spread = float(rng.choice([0.05, 0.5, 3.0]))
+    rows = {v: rng.normal(size=V) * spread for v in parents}
+    return parents, logp, rows, cap
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_margin_is_the_all_pairs_minimum(seed):
+    """The margin the oracle reports (and the test harness selects seeds by) against its
+    definition written out: over every (kept, dropped) pair of candidates of DIFFERENT parents
+    the smallest score gap at the top-K / budget cut, and over every candidate other than the
+    anchor the distance to the gate threshold.  The oracle's own routine prunes and exits early;
+    this one looks at all pairs."""
+    rng = np.random.default_rng(7000 + seed)
+    parents, logp, rows, cap = _random_layer(rng)
+    mu = float(rng.choice([0.03, 0.3, 0.8, 1.0]))
+    R = int(rng.integers(1, 12))
+    K = int(rng.integers(1, 6))
+    for layer in (0, 1):
+        pool = O.expand_layer(parents, logp, lambda v: rows[v], cap)
+        sel = O.select_budget(pool, layer, R, K, mu, init_layers=1)
+        cands = [(float(r.score[j]), r.node, j) for r in pool for j in range(len(r.token))]
+        ordered = sorted(cands, key=lambda u: (-u[0], u[1], u[2]))
+
+        def all_pairs(kept, dropped):
+            gaps = [abs(a[0] - b[0]) for a in kept for b in dropped if a[1] != b[1]]
+            return min(gaps) if gaps else math.inf
+
+        want = math.inf
+        if layer == 0:
+            survivors = ordered[:K]
+            want = min(want, all_pairs(survivors, ordered[K:]))
+        else:
+            anchor = ordered[0][0]
+            thr = math.log(mu) + anchor
+            survivors = [u for u in ordered if u[0] >= thr]
+            for u in ordered:
+                if u[0] != anchor:
+                    want = min(want, abs(u[0] - thr))
+        if len(survivors) > R:
+            want = min(want, all_pairs(survivors[:R], survivors[R:]))
+        # the routine may answer early with the gap between the lowest kept and the highest
+        # dropped score when that gap exceeds 1: a lower bound of the all-pairs minimum
+        if sel.margin > 1.0 and want > 1.0:
+            assert sel.margin <= want
+        else:
+            assert sel.margin == want, (layer, sel.margin, want)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_margin_means_what_the_harness_needs(seed):
+    """What the margin promises: if every row's log-sum-exp is off by less than half the margin
+    (each row by its own amount, as another arithmetic's rounding would be), the layer keeps
+    exactly the same candidates.  (That the margin is not smaller than it has to be is the
+    equality with the all-pairs minimum above.)"""
+    rng = np.random.default_rng(9000 + seed)
+    parents, logp, rows, cap = _random_layer(rng)
+    mu = float(rng.choice([0.03, 0.3, 0.8]))
+    R = int(rng.integers(1, 12))
+    K = int(rng.integers(1, 6))
+    for layer in (0, 1):
+        pool = O.expand_layer(parents, logp, lambda v: rows[v], cap)
+        sel = O.select_budget(pool, layer, R, K, mu, init_layers=1)
+        if not math.isfinite(sel.margin) or sel.margin < 1e-9:
+            continue
+        for trial in range(10):
+            shift = {v: rng.uniform(-0.49, 0.49) * min(sel.margin, 10.0) for v in parents}
+            moved = [O.RowResult(node=r.node, row_max=r.row_max, row_lse=r.row_lse - shift[r.node], token=r.token,
+                                 logit=r.logit, edge_logp=r.edge_logp + shift[r.node], prob=r.prob,
+                                 score=r.score + shift[r.node]) for r in pool]
+            assert O.select_budget(moved, layer, R, K, mu, init_layers=1).kept == sel.kept
+
+
 # ---------------------------------------------------------------- brute force: whole tree
 def enumerate_trees(V, max_nodes, max_depth):
     """Every prefix-closed set of token paths (tuples) with <= max_nodes paths, depth <= max_depth."""
