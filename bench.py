@@ -36,6 +36,7 @@ def parse_args():
     ap.add_argument("--slots", type=int, default=0, help="rotating input sets (0 = enough to exceed 512 MB)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-c3", action="store_true", help="leave the Qwen3-8B x4 block out of the default line")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run plain device copies of 1 GiB (reads 1 GiB, writes 1 GiB each): the "
                          "reference that scales the FETCH_SIZE / WRITE_SIZE counters of a --pmc run")
@@ -70,9 +71,10 @@ def parse_args():
 
 
 class Slot:
-    """One set of inputs (logits pool, Q/K/V) on the device."""
+    """One set of inputs (logits pool, Q/K/V) on the device, with the tree state and mask its
+    steps write (so that what every slot's last step produced can be checked after timing)."""
 
-    def __init__(self, cfg, seed, torch, H):
+    def __init__(self, cfg, seed, torch, H, T=None):
         import numpy as np
         from workloads import attention_inputs
         seeds = [seed] * cfg.B
@@ -86,6 +88,28 @@ class Slot:
         self.kt = H.bf16_to_device(np.stack([x["k_tree"] for x in xs]))
         self.vt = H.bf16_to_device(np.stack([x["v_tree"] for x in xs]))
         self.graph = None
+        self.graph_layers = None
+        if T is not None:
+            self.st = T.TreeState(cfg.B, cfg.N)
+            self.mask = torch.zeros(cfg.B, self.st.N_pad, self.st.N_pad // 64, dtype=torch.int64, device="cuda")
+        self.n_expected = None
+
+
+def check_slots(T, slots, used, where):
+    """Every slot's last step must have ended normally and built the tree its warm-up built: a
+    launch that gave up its bounded wait (ABORTED) or met a bad row must not be timed as a step."""
+    bad = T.TALON_STATUS_ABORTED | T.TALON_STATUS_BAD_ROW
+    for i in sorted(set(used)):
+        s = slots[i]
+        status = s.st.status.cpu().numpy()
+        n = s.st.n_nodes.cpu().numpy()
+        if (status & bad).any() or not ((status & 3) != 0).all():
+            print("bench.py: %s: slot %d ended with status %s" % (where, i, status.tolist()), file=sys.stderr)
+            sys.exit(3)
+        if s.n_expected is not None and n.tolist() != s.n_expected:
+            print("bench.py: %s: slot %d built trees of %s nodes, warm-up built %s" %
+                  (where, i, n.tolist(), s.n_expected), file=sys.stderr)
+            sys.exit(3)
 
 
 def main():
@@ -95,13 +119,21 @@ def main():
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
+    from workloads import CONFIGS
+    cfg = CONFIGS[args.config.lower()]
+    plain = not (args.copy_calibration or args.attainable or args.zipf_grid or args.scan_grid or args.sweep
+                 or args.literal)
+    # The oracle's timing runs first, in forked worker processes, before this process touches
+    # the GPU (a process that has initialised the GPU must not be forked into workers).
+    cpu = None
+    if plain and not args.no_cpu_baseline:
+        cpu = cpu_baseline(cfg, args.cpu_seconds)
+
     import numpy as np
     import torch
     import paper_2601_07353_amd as T
-    from tests import harness as H
-    from workloads import CONFIGS
+    import workloads as H
 
-    cfg = CONFIGS[args.config.lower()]
     T.load_library()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -131,49 +163,90 @@ def main():
         print(json.dumps({"literal": literal_timing(T, torch, np, H, cfg, args.steps, args.slots or 2)}))
         return
 
+    r = run_workload(T, torch, np, H, cfg, args, args.steps, args.warmup)
+    result = {
+        "metric": "tree expand+verify steps/s", "value": r["steps_per_s"], "unit": "steps/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": r["ms_per_step"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if cfg.logits_dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "config": r["config"],
+        "roofline": r["roofline"],
+        "kernels": r["kernels"],
+        "latency": r["latency"],
+        "per_layer_launches": r["per_layer_launches"],
+    }
+    for key in ("accept", "layers"):
+        if key in r:
+            result[key] = r[key]
+    # The second 8B-shaped configuration (Qwen3-8B x4: wide layers, where the bandwidth and
+    # matrix-core fractions mean something) rides along on the default line.
+    if cfg.name == CONFIGS["c2"].name and not args.no_c3:
+        c3 = run_workload(T, torch, np, H, CONFIGS["c3"], args, min(args.steps, 100), min(args.warmup, 10), extras=False)
+        result["c3"] = {"workload": c3["config"]["workload"], "steps_per_s": c3["steps_per_s"],
+                        "ms_per_step": c3["ms_per_step"], "steps": c3["steps"], "config": c3["config"],
+                        "expand_tree_kernel": c3["kernels"]["expand_tree_kernel"],
+                        "tree_attention": c3["kernels"]["tree_attention"],
+                        "per_layer_launches": c3["per_layer_launches"]}
+    if cpu is not None:
+        result["cpu_baseline"] = cpu
+    print(json.dumps(result))
+
+
+def run_workload(T, torch, np, H, cfg, args, steps, warmup, extras=True):
+    """Times `steps` whole steps of one configuration; returns the figures of the bench line."""
+    dev = torch.device("cuda:0")
     elem = cfg.elem_bytes
     pool_bytes = cfg.B * cfg.N_pad * cfg.V * elem
     kv_bytes = 2 * cfg.B * cfg.L * cfg.Hkv * cfg.Dh * 2
     n_slots = args.slots or max(2, min(32, int(np.ceil(512e6 / (pool_bytes + kv_bytes)))))
-    slots = [Slot(cfg, cfg.seed + 1000 * i, torch, H) for i in range(n_slots)]
+    slots = [Slot(cfg, cfg.seed + 1000 * i, torch, H, T) for i in range(n_slots)]
 
     cap = args.cap or cfg.K
-    st = T.TreeState(cfg.B, cfg.N)
-    cand = T.Candidates(cfg.B, st.N_pad, cap)
+    N_pad = slots[0].st.N_pad
+    cand = T.Candidates(cfg.B, N_pad, cap)
     dt = T.TALON_DTYPE_F32 if cfg.logits_dtype == "f32" else T.TALON_DTYPE_BF16
-    ws_expand = T.make_expand_workspace(cfg.B, st.N_pad, cfg.V, cap, dt)
+    ws_expand = T.make_expand_workspace(cfg.B, N_pad, cfg.V, cap, dt)
     roots = torch.from_numpy(H.root_tokens(cfg)).cuda()
-    mask = torch.zeros(cfg.B, st.N_pad, st.N_pad // 64, dtype=torch.int64, device=dev)
-    out = torch.zeros(cfg.B, st.N_pad, cfg.Hq, cfg.Dh, dtype=torch.bfloat16, device=dev)
+    out = torch.zeros(cfg.B, N_pad, cfg.Hq, cfg.Dh, dtype=torch.bfloat16, device=dev)
     plen = torch.full((cfg.B,), cfg.L, dtype=torch.int32, device=dev)
-    nb = T.talon_tree_attention_workspace_bytes(cfg.B, st.N_pad, cfg.Hq, cfg.Hkv, cfg.Dh, cfg.L)
+    nb = T.talon_tree_attention_workspace_bytes(cfg.B, N_pad, cfg.Hq, cfg.Hkv, cfg.Dh, cfg.L)
     ws_attn = torch.empty(max(nb, 256), dtype=torch.uint8, device=dev)
+    depth_cap = min(cfg.Dmax, cfg.N - 1)
 
     def expand(s):   # tree init, the whole loop of Alg. 2 and the ancestor mask: one launch
-        T.talon_build_tree(roots, s.logits, st, cap, cfg.mu, cfg.K, 1, cfg.Dmax, cand, ws_expand, mask=mask)
+        T.talon_build_tree(roots, s.logits, s.st, cap, cfg.mu, cfg.K, 1, cfg.Dmax, cand, ws_expand, mask=s.mask)
 
     def attention(s):
-        T.talon_tree_attention(s.q, s.kp, s.vp, s.kt, s.vt, mask, st.n_nodes, plen, cfg.L, out, None, ws_attn)
+        T.talon_tree_attention(s.q, s.kp, s.vp, s.kt, s.vt, s.mask, s.st.n_nodes, plen, cfg.L, out, None, ws_attn)
 
     def step(s):
         expand(s)
         attention(s)
 
+    def step_per_layer(s):   # what a serving loop can call between draft passes: one launch per layer
+        T.talon_tree_init(s.st, roots)
+        for d in range(depth_cap):
+            T.talon_expand_select_layer(s.logits, s.st, cap, cfg.mu, cfg.K, 1, cfg.Dmax, cand, ws_expand, layer=d)
+        T.talon_build_tree_mask(s.st, s.mask)
+        attention(s)
+
     # ---- warmup (also records the per-slot work: rows scanned, attention FLOPs)
     rows_scanned, attn_flops, n_nodes_mean = [], [], []
-    for i in range(max(args.warmup, n_slots)):
+    for i in range(max(warmup, n_slots)):
         s = slots[i % n_slots]
         step(s)
         if i < n_slots:
             torch.cuda.synchronize()
-            n = st.n_nodes.cpu().numpy().astype(np.int64)
-            fc = st.frontier_count.cpu().numpy().astype(np.int64)
-            depth = st.depth.cpu().numpy()
+            n = s.st.n_nodes.cpu().numpy().astype(np.int64)
+            fc = s.st.frontier_count.cpu().numpy().astype(np.int64)
+            depth = s.st.depth.cpu().numpy()
+            s.n_expected = n.tolist()
             rows_scanned.append(int((n - fc).sum()))
             keys = sum(int((cfg.L + depth[b, :n[b]] + 1).sum()) for b in range(cfg.B))
             attn_flops.append(4.0 * cfg.Hq * cfg.Dh * keys)
             n_nodes_mean.append(float(n.mean()))
     torch.cuda.synchronize()
+    check_slots(T, slots, range(n_slots), "warm-up")
 
     use_graph = not args.no_graph
     if use_graph:
@@ -187,45 +260,75 @@ def main():
         torch.cuda.synchronize()
 
     # ---- timed region: exactly K steps
+    used = [i % n_slots for i in range(steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        s = slots[i % n_slots]
+    for i in used:
+        s = slots[i]
         if use_graph:
             s.graph.replay()
         else:
             step(s)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    steps_per_s = args.steps / (t1 - t0)
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    steps_per_s = steps / (t1 - t0)
+    check_slots(T, slots, used, "timed region")
+
+    # ---- the same steps with one launch per layer (tree init, Dmax fused scan + selection
+    # launches, mask, attention), as one HIP graph per slot
+    per_layer = None
+    if use_graph:
+        for s in slots:
+            step_per_layer(s)
+        torch.cuda.synchronize()
+        check_slots(T, slots, range(n_slots), "per-layer launches, eager")
+        for s in slots:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                step_per_layer(s)
+            s.graph_layers = g
+        for s in slots:
+            s.graph_layers.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in used:
+            slots[i].graph_layers.replay()
+        torch.cuda.synchronize()
+        dt_s = time.perf_counter() - t0
+        check_slots(T, slots, used, "per-layer launches")
+        per_layer = {"ms_per_step": dt_s * 1e3 / steps, "steps_per_s": steps / dt_s,
+                     "launches_per_step": 2 + 2 * depth_cap + (2 if nb > 256 else 1),
+                     "what": "talon_tree_init + %d x talon_expand_select_layer (two launches each) + "
+                             "talon_build_tree_mask + talon_tree_attention, one HIP graph per step" % depth_cap}
 
     # ---- kernel timing region: the same K steps launched eagerly, with HIP events (on the
     # launch stream) around the expansion launch (one per step: the kernel walks all layers;
     # recorded by the library's measurement hook inside talon_build_tree) and around the
     # tree-attention call.
     layers = 1
-    ev_attn = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    ev_attn = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
     T.talon_profile_scan_launches(True)
-    for i in range(args.steps):
-        s = slots[i % n_slots]
+    for k_, i in enumerate(used):
+        s = slots[i]
         expand(s)
-        e0, e1 = ev_attn[i]
+        e0, e1 = ev_attn[k_]
         e0.record(); attention(s); e1.record()
     torch.cuda.synchronize()
-    scan_us, n_rec = T.talon_profile_read(args.steps * layers)
+    scan_us, n_rec = T.talon_profile_read(steps * layers)
     T.talon_profile_scan_launches(False)
-    assert n_rec == args.steps * layers, (n_rec, args.steps, layers)
-    scan_ms_step = float(np.sum(scan_us)) * 1e-3 / args.steps
+    assert n_rec == steps * layers, (n_rec, steps, layers)
+    check_slots(T, slots, used, "kernel timing region")
+    scan_ms_step = float(np.sum(scan_us)) * 1e-3 / steps
     scan_ms_launch = scan_ms_step / layers
     attn_all = [e0.elapsed_time(e1) for e0, e1 in ev_attn]
     attn_ms = float(np.mean(attn_all))
     # one step at a time (a graph replay between two events, the device idle before it): the
     # latency a single request sees, as mean and median beside the back-to-back rate above
     lat = []
-    if use_graph:
-        for i in range(min(args.steps, 100)):
-            s = slots[i % n_slots]
+    if use_graph and extras:
+        for i in used[:100]:
+            s = slots[i]
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             torch.cuda.synchronize()
             e0.record(); s.graph.replay(); e1.record()
@@ -236,57 +339,50 @@ def main():
                "single_step_us_mean": float(np.mean(lat)) if lat else None,
                "single_step_us_p50": float(np.median(lat)) if lat else None}
 
-    used = [i % n_slots for i in range(args.steps)]
     mean_rows = float(np.mean([rows_scanned[u] for u in used]))
     mean_flops = float(np.mean([attn_flops[u] for u in used]))
     scan_bytes = mean_rows * cfg.V * elem
     attn_bytes = (2.0 * cfg.B * cfg.L * cfg.Hkv * cfg.Dh * 2 +
                   2.0 * float(np.mean(n_nodes_mean)) * cfg.B * (cfg.Hq + cfg.Hkv) * cfg.Dh * 2)
 
+    scan_gbps = scan_bytes / (scan_ms_step * 1e-3) / 1e9
+    attn_tflops = mean_flops / (attn_ms * 1e-3) / 1e12
     kernels = {
         "expand_tree_kernel": {"launches_per_step": layers, "ms_per_step": scan_ms_step, "ms_per_launch": scan_ms_launch,
-                          "rows_scanned_per_step": mean_rows, "bytes_per_step": scan_bytes,
-                          "GBps": scan_bytes / (scan_ms_step * 1e-3) / 1e9},
+                               "rows_scanned_per_step": mean_rows, "bytes_per_step": scan_bytes,
+                               "GBps": scan_gbps, "frac_of_hbm_peak": scan_gbps / HBM_PEAK_GBS},
         "tree_attention": {"ms": attn_ms, "flops": mean_flops, "bytes": attn_bytes,
-                           "TFLOPs": mean_flops / (attn_ms * 1e-3) / 1e12},
+                           "TFLOPs": attn_tflops, "frac_of_mfma_peak": attn_tflops / MFMA_BF16_PEAK_TFLOPS},
     }
     traffic = read_traffic(cfg.name)
+    traffic_source = ("profiles/hbm_traffic_%s.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, "
+                      "scaled by a plain 1 GiB copy; a committed summary, not counted in this run" % cfg.name)
     if scan_ms_step >= attn_ms:
         # dominant kernel of the step: the vocab scan (HBM-bound: every logit is read once)
         ach = scan_bytes / layers / (scan_ms_launch * 1e-3) / 1e9
         roofline = {"kernel": "expand_tree_kernel", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": traffic.get("expand_tree_kernel"),
+                    "traffic_source": traffic_source,
                     "launches_per_step": layers, "avg_launch_us": scan_ms_launch * 1e3,
                     "algorithmic_bytes_per_launch": scan_bytes / layers}
     else:
         ach = mean_flops / (attn_ms * 1e-3) / 1e12
         roofline = {"kernel": "tree_attention_kernel", "bound": "mfma", "achieved": ach,
                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
-                    "traffic": traffic.get("tree_attention_kernel"), "avg_launch_us": attn_ms * 1e3,
-                    "algorithmic_flops_per_launch": mean_flops}
+                    "traffic": traffic.get("tree_attention_kernel"), "traffic_source": traffic_source,
+                    "avg_launch_us": attn_ms * 1e3, "algorithmic_flops_per_launch": mean_flops}
 
-    result = {
-        "metric": "tree expand+verify steps/s", "value": steps_per_s, "unit": "steps/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if cfg.logits_dtype == "bf16" else "f32",
-        "data": "synthetic",
-        "config": {"workload": cfg.name, "B": cfg.B, "vocab": cfg.V, "K": cfg.K, "N": cfg.N, "Dmax": cfg.Dmax,
-                   "mu": cfg.mu, "row_cap": cap, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "Dh": cfg.Dh, "prefix_len": cfg.L,
-                   "input_slots": n_slots, "hip_graph": use_graph},
-        "roofline": roofline,
-        "kernels": kernels,
-        "latency": latency,
-    }
-
-    if args.accept:
-        result["accept"] = accept_outcome(T, torch, np, cfg, slots, st, args.steps, elem)
-
-    if args.layerwise:
-        result["layers"] = layerwise(T, torch, np, cfg, slots, st, cand, ws_expand, roots, args.steps, elem)
-
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cfg, args.cpu_seconds, H)
-    print(json.dumps(result))
+    r = {"steps_per_s": steps_per_s, "ms_per_step": ms_per_step, "steps": steps,
+         "config": {"workload": cfg.name, "B": cfg.B, "vocab": cfg.V, "K": cfg.K, "N": cfg.N, "Dmax": cfg.Dmax,
+                    "mu": cfg.mu, "row_cap": cap, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "Dh": cfg.Dh, "prefix_len": cfg.L,
+                    "input_slots": n_slots, "hip_graph": use_graph},
+         "roofline": roofline, "kernels": kernels, "latency": latency, "per_layer_launches": per_layer}
+    st = slots[(steps - 1) % n_slots].st
+    if args.accept and extras:
+        r["accept"] = accept_outcome(T, torch, np, cfg, slots, st, steps, elem)
+    if args.layerwise and extras:
+        r["layers"] = layerwise(T, torch, np, cfg, slots, st, cand, ws_expand, roots, steps, elem)
+    return r
 
 
 def accept_outcome(T, torch, np, cfg, slots, st, steps, elem):
@@ -628,25 +724,74 @@ def read_traffic(workload):
     return out
 
 
-def cpu_baseline(cfg, budget_s, H):
-    """The CPU oracle, as it stands, timed on this host on whole steps of the same workload."""
+def _oracle_steps(job):
+    """Worker: whole oracle steps (Alg. 2 tree, mask, tree attention over all nodes and heads) of
+    one configuration on fresh seeded inputs, one thread; input generation is not timed.
+    Returns (steps done, seconds spent in the oracle)."""
+    cfg_name, first_seed, budget_s, max_steps = job
     from threadpoolctl import threadpool_limits
-    n_done, t_total, seed = 0, 0.0, cfg.seed
+    from oracle import talon_oracle as O
+    from workloads import CONFIGS, attention_inputs, bf16_bits_to_f64, build_pool, root_tokens, storage_to_f64
+    cfg = next(c for c in CONFIGS.values() if c.name == cfg_name)
+    import numpy as np
+    mu = float(np.float32(cfg.mu))
+    n_done, busy = 0, 0.0
     with threadpool_limits(limits=1):
-        while True:
-            seeds = [seed + 1000 * n_done] * cfg.B
-            pool = H.build_pool(cfg, seeds)           # input generation is not timed
-            from workloads import attention_inputs
+        while n_done < max_steps and busy < budget_s:
+            seeds = [first_seed + 1000 * n_done] * cfg.B
+            pool = build_pool(cfg, seeds)
             attn = [attention_inputs(cfg, seeds[b], b) for b in range(cfg.B)]
+            roots = root_tokens(cfg)
             t0 = time.perf_counter()
-            H.run_oracle_step(cfg, seeds, pool=pool, attn=attn)
-            t_total += time.perf_counter() - t0
+            for b in range(cfg.B):
+                rows = {}
+
+                def row_of(i, b=b, rows=rows):
+                    if i not in rows:
+                        rows[i] = storage_to_f64(pool[b, i])
+                    return rows[i]
+
+                t = O.build_tree(row_of, int(roots[b]), N=cfg.N, K=cfg.K, mu=mu, cap=cfg.K, Dmax=cfg.Dmax, init_layers=1)
+                m = O.build_tree_mask(t.parent)
+                x, n = attn[b], t.n
+                O.tree_attention(bf16_bits_to_f64(x["q"][:n]), bf16_bits_to_f64(x["k_prefix"]),
+                                 bf16_bits_to_f64(x["v_prefix"]), bf16_bits_to_f64(x["k_tree"][:n]),
+                                 bf16_bits_to_f64(x["v_tree"][:n]), m)
+            busy += time.perf_counter() - t0
             n_done += 1
-            if t_total >= budget_s or n_done >= 50:
-                break
-    return {"value": n_done / t_total, "unit": "steps/s", "cores": 1, "kind": "oracle",
-            "sample": "%d whole steps of %s (expansion + mask + attention over all nodes and heads), "
-                      "numpy fp64, BLAS pinned to one thread" % (n_done, cfg.name)}
+    return n_done, busy
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(cfg, budget_s):
+    """The CPU oracle, as it stands, timed on this host on whole steps of the same workload:
+    one thread, then one single-threaded worker process per core (independent steps side by
+    side: the whole-job rate of the host).  Must run before this process initialises the GPU."""
+    import multiprocessing as mp
+    nproc = os.cpu_count() or 1
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = nproc
+    cores = max(1, min(usable, 16))     # one GPU's share of the host
+    one_n, one_busy = _oracle_steps((cfg.name, cfg.seed, budget_s / 2.0, 50))
+    with mp.get_context("fork").Pool(cores) as pool:
+        res = pool.map(_oracle_steps, [(cfg.name, cfg.seed + 100000 * (w + 1), budget_s / 2.0, 50) for w in range(cores)])
+    rate_all = sum(n / busy for n, busy in res)
+    return {"value": rate_all, "unit": "steps/s", "cores": cores, "kind": "oracle",
+            "single_thread_value": one_n / one_busy, "nproc": nproc, "cpu_model": cpu_model(),
+            "sample": "%d whole steps of %s on one thread, then %d steps on %d single-threaded worker processes side by "
+                      "side (expansion + mask + attention over all nodes and heads; numpy fp64, BLAS pinned to one "
+                      "thread per process; input generation not timed)" % (one_n, cfg.name, sum(n for n, _ in res), cores)}
 
 
 if __name__ == "__main__":

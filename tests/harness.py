@@ -6,7 +6,8 @@ import math
 
 import numpy as np
 
-from workloads import WorkloadConfig, attention_inputs, bf16_bits_to_f64, logits_row, storage_to_f64
+from workloads import (WorkloadConfig, attention_inputs, bf16_bits_to_f64, bf16_to_device, build_pool,  # noqa: F401
+                       logits_row, root_tokens, storage_to_f64, to_device_logits)
 
 MARGIN_TOL = 1e-4   # smallest cross-parent score gap a seed must leave (log units)
 PROB_RTOL = 1e-5    # probabilities and path confidences, relative
@@ -23,7 +24,7 @@ LSE_ATOL = 2e-6     # row log-sum-exp, absolute
 #                        six standard deviations (millions of elements are compared)
 ATTN_OUT_RTOL = 2.0 ** -8
 ATTN_KEYS_ATOL = 2.2e-2      # divided by sqrt(number of keys the row attends to)
-ATTN_LSE_ATOL = 1e-4         # fp32 scores and denominators against fp64 (observed worst about 1e-5)
+ATTN_LSE_ATOL = 2e-5         # fp32 scores and denominators against fp64 (observed worst 1.6e-6)
 
 
 def seeds_for(cfg: WorkloadConfig, seeds=None):
@@ -32,19 +33,6 @@ def seeds_for(cfg: WorkloadConfig, seeds=None):
     if isinstance(seeds, int):
         return [seeds] * cfg.B
     return list(seeds)
-
-
-def build_pool(cfg: WorkloadConfig, seeds) -> np.ndarray:
-    dt = np.float32 if cfg.logits_dtype == "f32" else np.uint16
-    pool = np.zeros((cfg.B, cfg.N_pad, cfg.V), dtype=dt)
-    for b in range(cfg.B):
-        for i in range(cfg.N):
-            pool[b, i] = logits_row(cfg, seeds[b], b, i)
-    return pool
-
-
-def root_tokens(cfg: WorkloadConfig) -> np.ndarray:
-    return (np.arange(cfg.B, dtype=np.int32) * 7 + 11) % cfg.V
 
 
 # --------------------------------------------------------------------------- oracle side
@@ -121,28 +109,6 @@ def run_oracle_step(cfg: WorkloadConfig, seeds=None, pool=None, attn=None, attn_
 
 
 # --------------------------------------------------------------------------- GPU side
-def to_device_logits(pool: np.ndarray):
-    """Pool on the device, rows padded to a multiple of 8 elements (the ABI wants 16-byte row strides);
-    the returned view keeps the true vocabulary width."""
-    import torch
-    V = pool.shape[2]
-    V_pad = (V + 7) // 8 * 8
-    if V_pad != V:
-        padded = np.zeros(pool.shape[:2] + (V_pad,), dtype=pool.dtype)
-        padded[:, :, :V] = pool
-        pool = padded
-    if pool.dtype == np.uint16:
-        dev = torch.from_numpy(pool.view(np.int16)).cuda().view(torch.bfloat16)
-    else:
-        dev = torch.from_numpy(pool).cuda()
-    return dev[:, :, :V]
-
-
-def bf16_to_device(bits: np.ndarray):
-    import torch
-    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
-
-
 def run_gpu_expand(cfg: WorkloadConfig, pool_dev, init_layers=1, mu=None, K_init=None, layerwise=False):
     """Whole expansion loop on the GPU.  Default: talon_build_tree (init, loop and mask in two
     launches; the mask is returned).  layerwise="tree": talon_tree_init + talon_expand_tree;
@@ -247,7 +213,7 @@ def run_gpu_step(cfg: WorkloadConfig, seeds=None, pool=None, attn=None, with_att
         torch.cuda.synchronize()
         res["attn_out"] = out.float().cpu().numpy()
         res["attn_lse"] = lse.cpu().numpy()
-        res["prefix_len"] = L
+        res["prefix_len"] = np.full(cfg.B, L, dtype=np.int64)
     return res
 
 
@@ -313,7 +279,7 @@ def compare_attention(cfg: WorkloadConfig, gpu: dict, ref: dict):
     for b in range(cfg.B):
         want = ref["attn_out"][b]
         n = want.shape[0]
-        keys = ref["keys"][b] if "keys" in ref else gpu["prefix_len"] + ref["mask"][b].sum(axis=1)
+        keys = int(gpu["prefix_len"][b]) + ref["mask"][b].sum(axis=1)
         w, _ = check_attention_rows(gpu["attn_out"][b, :n], gpu["attn_lse"][b, :n], want, ref["attn_lse"][b], keys, (b,))
         worst = max(worst, w)
         # rows beyond n_nodes must be untouched (the harness pre-fills the output with zeros)

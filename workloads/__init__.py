@@ -7,6 +7,7 @@ path's tests draw their inputs from here so that the two sides see identical
 bytes.
 """
 from .configs import CONFIGS, WorkloadConfig, get_config  # noqa: F401
+from .staging import bf16_to_device, build_pool, root_tokens, to_device_logits  # noqa: F401
 from .generators import (  # noqa: F401
     attention_inputs,
     bf16_bits_to_f64,
