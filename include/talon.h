@@ -331,6 +331,33 @@ int talon_tree_attention(const void* q, const void* k_prefix, const void* v_pref
                          int64_t kv_stride_h, float scale, void* out, float* out_lse,
                          void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * talon_tree_attention for callers that cannot allocate device memory or pass a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the
+ * same call, the same kernels and the same results, with the split-KV partial results kept in
+ * a device array that is part of the library itself (talon_static_scratch_bytes() = 16 MiB per
+ * GPU, held from the moment the library is loaded on that GPU until the process ends).  The
+ * call allocates nothing and frees nothing.
+ *   - Shapes whose partial results need more than that (talon_tree_attention_workspace_bytes
+ *     says how much) are refused with TALON_ERR_WORKSPACE; nothing is launched then.
+ *   - The array's device address is looked up on the first call on a device;
+ *     talon_static_scratch_init() does the same lookup ahead of time (call it once per device,
+ *     with that device current, before capturing a graph).
+ *   - Every call on a GPU shares that GPU's array: calls that overlap in time on one GPU (two
+ *     streams, two host threads) race and give wrong results.  Calls on one stream are safe.
+ *     Nothing in the array has to be zero: a call never reads what an earlier one left.
+ * Arguments and all other errors: as talon_tree_attention.
+ */
+size_t talon_static_scratch_bytes(void);
+int talon_static_scratch_init(void);
+int talon_tree_attention_static(const void* q, const void* k_prefix, const void* v_prefix,
+                                const void* k_tree, const void* v_tree, const uint64_t* mask,
+                                const int32_t* n_nodes, const int32_t* prefix_len, int32_t B,
+                                int32_t N_pad, int32_t Hq, int32_t Hkv, int32_t Dh,
+                                int32_t max_prefix_len, int64_t kv_stride_b, int64_t kv_stride_t,
+                                int64_t kv_stride_h, float scale, void* out, float* out_lse,
+                                void* stream);
+
 #ifdef __cplusplus
 }
 #endif

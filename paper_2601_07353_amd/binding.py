@@ -39,6 +39,7 @@ EXPORTS = [
     "talon_literal_workspace_bytes", "talon_expand_literal",
     "talon_greedy_accept", "talon_compact_kv", "talon_prune_tree",
     "talon_build_tree_mask", "talon_tree_attention_workspace_bytes", "talon_tree_attention",
+    "talon_static_scratch_bytes", "talon_static_scratch_init", "talon_tree_attention_static",
 ]
 
 
@@ -105,6 +106,11 @@ def load_library() -> ctypes.CDLL:
     lib.talon_tree_attention_workspace_bytes.argtypes = [c_int32] * 6
     lib.talon_tree_attention.argtypes = [P, P, P, P, P, P, P, P, c_int32, c_int32, c_int32, c_int32, c_int32, c_int32,
                                          c_int64, c_int64, c_int64, c_float, P, P, P, c_size_t, P]
+    lib.talon_static_scratch_bytes.restype = c_size_t
+    lib.talon_static_scratch_bytes.argtypes = []
+    lib.talon_static_scratch_init.argtypes = []
+    lib.talon_tree_attention_static.argtypes = [P, P, P, P, P, P, P, P, c_int32, c_int32, c_int32, c_int32, c_int32,
+                                                c_int32, c_int64, c_int64, c_int64, c_float, P, P, P]
     for name in EXPORTS:
         fn = getattr(lib, name)
         if fn.restype is c_int:
@@ -274,8 +280,23 @@ def talon_tree_attention_workspace_bytes(B, N_pad, Hq, Hkv, Dh, max_prefix_len) 
     return load_library().talon_tree_attention_workspace_bytes(B, N_pad, Hq, Hkv, Dh, max_prefix_len)
 
 
+def talon_static_scratch_bytes() -> int:
+    return load_library().talon_static_scratch_bytes()
+
+
+def talon_static_scratch_init():
+    _check(load_library().talon_static_scratch_init())
+
+
+def talon_tree_attention_static(q, k_prefix, v_prefix, k_tree, v_tree, mask, n_nodes, prefix_len, max_prefix_len, out,
+                                out_lse=None, scale=0.0, stream=None):
+    """talon_tree_attention without a workspace argument (the library's own scratch array)."""
+    return talon_tree_attention(q, k_prefix, v_prefix, k_tree, v_tree, mask, n_nodes, prefix_len, max_prefix_len,
+                                out, out_lse, None, scale, stream, _static=True)
+
+
 def talon_tree_attention(q, k_prefix, v_prefix, k_tree, v_tree, mask, n_nodes, prefix_len, max_prefix_len, out,
-                         out_lse=None, workspace=None, scale=0.0, stream=None):
+                         out_lse=None, workspace=None, scale=0.0, stream=None, _static=False):
     """q/k_tree/v_tree [B][N_pad][H][Dh] bf16 dense; k_prefix/v_prefix [B][L][Hkv][Dh] views (any strides
     with a contiguous Dh run); mask [B][N_pad][N_pad/64] int64."""
     B, N_pad, Hq, Dh = q.shape
@@ -291,6 +312,12 @@ def talon_tree_attention(q, k_prefix, v_prefix, k_tree, v_tree, mask, n_nodes, p
         sb, st_, sh = k_prefix.stride(0), k_prefix.stride(1), k_prefix.stride(2)
     else:
         sb = st_ = sh = Dh
+    if _static:
+        _check(load_library().talon_tree_attention_static(
+            _ptr(q), _ptr(k_prefix), _ptr(v_prefix), _ptr(k_tree), _ptr(v_tree), _ptr(mask), _ptr(n_nodes),
+            _ptr(prefix_len), B, N_pad, Hq, Hkv, Dh, max_prefix_len, sb, st_, sh, c_float(scale), _ptr(out),
+            _ptr(out_lse), _stream(stream)))
+        return
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load_library().talon_tree_attention(
         _ptr(q), _ptr(k_prefix), _ptr(v_prefix), _ptr(k_tree), _ptr(v_tree), _ptr(mask), _ptr(n_nodes),

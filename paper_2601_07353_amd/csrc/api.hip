@@ -8,6 +8,7 @@
 
 #include "talon_internal.h"
 
+#include <mutex>
 #include <vector>
 
 namespace talon {
@@ -240,6 +241,37 @@ int literal_layout(int B, int N_pad, int vocab, int dtype, LiteralLayout* V) {
 }  // namespace talon
 
 using namespace talon;
+
+// ---- scratch of the entry point that takes no workspace (talon_tree_attention_static).
+// One array per GPU, part of the library's code object: it exists from the moment the library
+// is loaded on a device until the process ends.  In host code the array's name is only a
+// handle: its device address is looked up once per device and that address is what kernels get.
+constexpr size_t kStaticScratchBytes = static_cast<size_t>(16) << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+// Device address of `scratch` on the current device (looked up on the first call per device).
+int static_scratch_address(void** out) {
+  int dev = -1;
+  int rc = check_hip(hipGetDevice(&dev), "hipGetDevice");
+  if (rc) return rc;
+  if (dev < 0 || dev >= kMaxDevices) { set_error("device index %d outside [0, %d)", dev, kMaxDevices); return TALON_ERR_UNSUPPORTED; }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    rc = check_hip(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)");
+    if (rc) return rc;
+    if (!p) { set_error("hipGetSymbolAddress returned a null address"); return TALON_ERR_RUNTIME; }
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return TALON_OK;
+}
+}  // namespace
 
 extern "C" {
 
@@ -653,12 +685,12 @@ size_t talon_tree_attention_workspace_bytes(int32_t B, int32_t N_pad, int32_t Hq
   return total;
 }
 
-int talon_tree_attention(const void* q, const void* k_prefix, const void* v_prefix, const void* k_tree,
-                         const void* v_tree, const uint64_t* mask, const int32_t* n_nodes,
-                         const int32_t* prefix_len, int32_t B, int32_t N_pad, int32_t Hq, int32_t Hkv, int32_t Dh,
-                         int32_t max_prefix_len, int64_t kv_stride_b, int64_t kv_stride_t, int64_t kv_stride_h,
-                         float scale, void* out, float* out_lse, void* workspace, size_t workspace_bytes,
-                         void* stream) {
+static int tree_attention_call(const void* q, const void* k_prefix, const void* v_prefix, const void* k_tree,
+                               const void* v_tree, const uint64_t* mask, const int32_t* n_nodes,
+                               const int32_t* prefix_len, int32_t B, int32_t N_pad, int32_t Hq, int32_t Hkv, int32_t Dh,
+                               int32_t max_prefix_len, int64_t kv_stride_b, int64_t kv_stride_t, int64_t kv_stride_h,
+                               float scale, void* out, float* out_lse, void* workspace, size_t workspace_bytes,
+                               bool static_scratch, void* stream) {
   AttnArgs a;
   size_t off_m, off_l, total;
   int rc = attention_layout(B, N_pad, Hq, Hkv, Dh, max_prefix_len, &a.splits, &a.tiles_per_split, &a.rows_pad, &off_m,
@@ -684,6 +716,17 @@ int talon_tree_attention(const void* q, const void* k_prefix, const void* v_pref
   }
   if (out_lse && (reinterpret_cast<uintptr_t>(out_lse) & 3u)) { set_error("out_lse is misaligned"); return TALON_ERR_INVALID_ARG; }
   if (!(scale >= 0.f) || isinf(scale)) { set_error("scale=%g must be finite and >= 0 (0 selects 1/sqrt(Dh))", (double)scale); return TALON_ERR_INVALID_ARG; }
+  if (static_scratch) {
+    // the split-KV partial results go to the library's own device array: size first (a host
+    // check), then the array's address on the current device
+    if (a.splits > 1 && total > kStaticScratchBytes) {
+      set_error("this shape needs %zu bytes of split-KV scratch; the call without a workspace holds at most %zu "
+                "(use talon_tree_attention with a caller-provided workspace)", total, kStaticScratchBytes);
+      return TALON_ERR_WORKSPACE;
+    }
+    if ((rc = static_scratch_address(&workspace))) return rc;
+    workspace_bytes = kStaticScratchBytes;
+  }
   if (a.splits > 1) {
     if (!workspace || !aligned16(workspace)) { set_error("workspace is NULL or not 16-byte aligned"); return TALON_ERR_INVALID_ARG; }
     if (workspace_bytes < total) { set_error("workspace of %zu bytes is smaller than the %zu needed", workspace_bytes, total); return TALON_ERR_WORKSPACE; }
@@ -705,6 +748,34 @@ int talon_tree_attention(const void* q, const void* k_prefix, const void* v_pref
   a.part_m = reinterpret_cast<float*>(w + off_m);
   a.part_l = reinterpret_cast<float*>(w + off_l);
   return check_hip(launch_attention(a, static_cast<hipStream_t>(stream)), "tree attention launch");
+}
+
+int talon_tree_attention(const void* q, const void* k_prefix, const void* v_prefix, const void* k_tree,
+                         const void* v_tree, const uint64_t* mask, const int32_t* n_nodes,
+                         const int32_t* prefix_len, int32_t B, int32_t N_pad, int32_t Hq, int32_t Hkv, int32_t Dh,
+                         int32_t max_prefix_len, int64_t kv_stride_b, int64_t kv_stride_t, int64_t kv_stride_h,
+                         float scale, void* out, float* out_lse, void* workspace, size_t workspace_bytes,
+                         void* stream) {
+  return tree_attention_call(q, k_prefix, v_prefix, k_tree, v_tree, mask, n_nodes, prefix_len, B, N_pad, Hq, Hkv, Dh,
+                             max_prefix_len, kv_stride_b, kv_stride_t, kv_stride_h, scale, out, out_lse, workspace,
+                             workspace_bytes, false, stream);
+}
+
+size_t talon_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int talon_static_scratch_init(void) {
+  void* p = nullptr;
+  return static_scratch_address(&p);
+}
+
+int talon_tree_attention_static(const void* q, const void* k_prefix, const void* v_prefix, const void* k_tree,
+                                const void* v_tree, const uint64_t* mask, const int32_t* n_nodes,
+                                const int32_t* prefix_len, int32_t B, int32_t N_pad, int32_t Hq, int32_t Hkv,
+                                int32_t Dh, int32_t max_prefix_len, int64_t kv_stride_b, int64_t kv_stride_t,
+                                int64_t kv_stride_h, float scale, void* out, float* out_lse, void* stream) {
+  return tree_attention_call(q, k_prefix, v_prefix, k_tree, v_tree, mask, n_nodes, prefix_len, B, N_pad, Hq, Hkv, Dh,
+                             max_prefix_len, kv_stride_b, kv_stride_t, kv_stride_h, scale, out, out_lse, nullptr, 0,
+                             true, stream);
 }
 
 }  // extern "C"
