@@ -5,7 +5,12 @@
  *
  * Conventions
  *   - Every pointer is a DEVICE pointer unless it is marked "host".  The caller owns every
- *     buffer; the library allocates nothing and keeps no state between calls.
+ *     buffer and the library allocates no device memory.  State it keeps between calls, all of
+ *     it host-side and per process: the measurement hook's HIP events (created on demand while
+ *     the hook is enabled), the wait bound of talon_set_spin_limit_us, two cached launch facts
+ *     (how many workgroups of the single-launch kernel the device holds at once; that the
+ *     attention kernel's LDS size has been raised), and the device address of the scratch
+ *     array of talon_tree_attention_static.  None of it depends on the arguments of a call.
  *   - Calls only enqueue work on `stream` (a hipStream_t passed as void*; NULL = the null
  *     stream) and return at once.  Nothing synchronises with the host.
  *   - Every call returns TALON_OK or a negative TALON_ERR_* code; all argument checks run on
@@ -170,6 +175,16 @@ int talon_expand_tree(const void* logits, int dtype, int64_t row_stride, int64_t
                       void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Bound of the wait between two layers inside talon_expand_tree / talon_build_tree, in
+ * microseconds (default 200000).  A launch whose workgroups cannot all be resident (the device
+ * is shared with other work) ends after this long with TALON_STATUS_ABORTED on every sequence
+ * instead of hanging; the caller then re-runs the step layer by layer with
+ * talon_tree_init + talon_expand_select_layer on the same workspace.  0 makes every wait give
+ * up at once (used by tests of that path).  Process-wide; applies to calls made afterwards.
+ */
+int talon_set_spin_limit_us(int64_t microseconds);
+
+/*
  * Alg. 2 from its first line to its last, and the tree's attention mask, in one launch:
  * T = {x_t} as talon_tree_init sets it (root_token: device, [B]), the whole loop as
  * talon_expand_tree runs it, and, if `mask` is not NULL, the ancestor mask of
@@ -184,6 +199,26 @@ int talon_build_tree(const int32_t* root_token, const void* logits, int dtype, i
                      int32_t* cand_token, float* cand_logit, float* cand_prob,
                      double* cand_edge_logp, float* row_max, double* row_lse, uint64_t* mask,
                      void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * talon_build_tree with the recovery from a launch that gave up (TALON_STATUS_ABORTED: the
+ * device could not hold the whole grid at once, e.g. because other work was running on it).
+ * Runs talon_build_tree, WAITS for `stream` (the only call of this library that synchronises
+ * with the host: not for use under graph capture), reads status[b] and, if any sequence is
+ * marked ABORTED, builds the same trees again on the same buffers and workspace with one launch
+ * per layer: talon_tree_init, min(max_depth, N-1) x talon_expand_select_layer, and the mask.
+ * The result is the tree talon_build_tree builds.  *fell_back (host, optional) is set to 1 if
+ * the layer-by-layer path ran, else 0.  Arguments and errors as talon_build_tree, plus
+ * TALON_ERR_RUNTIME if the copy or the wait fails.
+ */
+int talon_build_tree_checked(const int32_t* root_token, const void* logits, int dtype,
+                             int64_t row_stride, int64_t seq_stride, int row_mode,
+                             const talon_tree_state* st, int32_t vocab, int32_t k, float mu,
+                             int32_t K_init, int32_t init_layers, int32_t max_depth,
+                             int32_t* cand_token, float* cand_logit, float* cand_prob,
+                             double* cand_edge_logp, float* row_max, double* row_lse,
+                             uint64_t* mask, void* workspace, size_t workspace_bytes, void* stream,
+                             int32_t* fell_back);
 
 /*
  * Alg. 2 with the candidate pool exactly as the listing writes it (Sec. 5.2, "Hybrid Expansion

@@ -35,7 +35,7 @@ TALON_ROWS_BY_FRONTIER = 1
 EXPORTS = [
     "talon_last_error_string", "talon_tree_init", "talon_expand_workspace_bytes",
     "talon_expand_workspace_init", "talon_expand_layer", "talon_select_budget", "talon_expand_select_layer",
-    "talon_expand_tree", "talon_build_tree", "talon_profile_scan_launches", "talon_profile_read", "talon_probe_read", "talon_probe_mfma", "talon_verify_workspace_bytes", "talon_target_argmax",
+    "talon_expand_tree", "talon_build_tree", "talon_build_tree_checked", "talon_set_spin_limit_us", "talon_profile_scan_launches", "talon_profile_read", "talon_probe_read", "talon_probe_mfma", "talon_verify_workspace_bytes", "talon_target_argmax",
     "talon_literal_workspace_bytes", "talon_expand_literal",
     "talon_greedy_accept", "talon_compact_kv", "talon_prune_tree",
     "talon_build_tree_mask", "talon_tree_attention_workspace_bytes", "talon_tree_attention",
@@ -86,6 +86,8 @@ def load_library() -> ctypes.CDLL:
                                               P, c_size_t, P]
     lib.talon_build_tree.argtypes = [P, P, c_int, c_int64, c_int64, c_int, POINTER(_CTreeState), c_int32, c_int32,
                                      c_float, c_int32, c_int32, c_int32, P, P, P, P, P, P, P, P, c_size_t, P]
+    lib.talon_build_tree_checked.argtypes = lib.talon_build_tree.argtypes + [POINTER(c_int32)]
+    lib.talon_set_spin_limit_us.argtypes = [c_int64]
     lib.talon_profile_scan_launches.argtypes = [c_int]
     lib.talon_profile_read.argtypes = [POINTER(c_float), c_int32, POINTER(c_int32)]
     lib.talon_literal_workspace_bytes.restype = c_size_t
@@ -247,6 +249,25 @@ def talon_build_tree(root_token, logits, st: TreeState, k, mu, K_init, init_laye
         V if vocab is None else vocab, k, c_float(mu), K_init, init_layers, max_depth, _ptr(cand.token),
         _ptr(cand.logit), _ptr(cand.prob), _ptr(cand.edge_logp), _ptr(cand.row_max), _ptr(cand.row_lse), _ptr(mask),
         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def talon_build_tree_checked(root_token, logits, st: TreeState, k, mu, K_init, init_layers, max_depth,
+                             cand: Candidates, workspace, mask=None, row_mode=TALON_ROWS_BY_NODE, vocab=None,
+                             stream=None) -> bool:
+    """talon_build_tree, then the layer-by-layer rebuild if the launch gave up.  Waits for the stream.
+    Returns whether the layer-by-layer path ran."""
+    dt, row_stride, seq_stride, V = _logits_meta(logits)
+    fell = c_int32(0)
+    _check(load_library().talon_build_tree_checked(
+        _ptr(root_token), _ptr(logits), dt, row_stride, seq_stride, row_mode, ctypes.byref(st.c),
+        V if vocab is None else vocab, k, c_float(mu), K_init, init_layers, max_depth, _ptr(cand.token),
+        _ptr(cand.logit), _ptr(cand.prob), _ptr(cand.edge_logp), _ptr(cand.row_max), _ptr(cand.row_lse), _ptr(mask),
+        _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream), ctypes.byref(fell)))
+    return bool(fell.value)
+
+
+def talon_set_spin_limit_us(microseconds: int):
+    _check(load_library().talon_set_spin_limit_us(microseconds))
 
 
 def talon_profile_scan_launches(enable: bool):

@@ -7,7 +7,11 @@
 #include <string.h>
 
 #include "talon_internal.h"
+#ifdef TALON_TUNING
+#include "tuning.h"
+#endif
 
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -117,16 +121,13 @@ int check_select_args(const talon_tree_state* st, int32_t k, const void* cand_to
   return TALON_OK;
 }
 
-// Items a scan launch aims for (tuning knob; TALON_EXPAND_TARGET_ITEMS overrides it).
-int expand_target_items() {
-  static int v = 0;
-  if (v == 0) {
-    const char* e = getenv("TALON_EXPAND_TARGET_ITEMS");
-    v = e ? atoi(e) : 512;
-    if (v < 1) v = 512;
-  }
-  return v;
-}
+// Launch heuristics.  Tuning builds (-DTALON_TUNING) can override them from the environment;
+// the default build compiles the constants in.
+#ifndef TALON_TUNING
+constexpr int tuned_int(const char*, int dflt) { return dflt; }
+#endif
+// (row, chunk) items a scan launch aims for when it cuts rows into chunks (from a sweep over c2, c3, c5)
+int expand_target_items() { return tuned_int("TALON_EXPAND_TARGET_ITEMS", 512); }
 
 ExpandArgs make_expand_args(const void* logits, int64_t row_stride, int64_t seq_stride, int row_mode,
                             const talon_tree_state* st, int32_t vocab, int32_t k, int32_t* cand_token,
@@ -343,17 +344,21 @@ hipError_t profile_record(hipStream_t s) {
 // Fused launches of `layers` consecutive layers starting from the public tree state.
 // Resident workgroups of the single-launch kernel, per element type, queried once.
 int tree_grid_limit(int dtype) {
-  static int cached[2] = {-1, -1};
-  int& c = cached[dtype == TALON_DTYPE_F32 ? 0 : 1];
-  if (c < 0) c = expand_tree_max_grid(dtype);
-  return c;
+  static std::atomic<int> cached[2] = {{-1}, {-1}};
+  std::atomic<int>& c = cached[dtype == TALON_DTYPE_F32 ? 0 : 1];
+  int v = c.load(std::memory_order_relaxed);
+  if (v < 0) {
+    v = expand_tree_max_grid(dtype);
+    c.store(v, std::memory_order_relaxed);
+  }
+  return v;
 }
 
 // Bound of the wait between two layers of the single-launch kernel, in ticks of the 100 MHz
-// wall clock (default 0.2 s; TALON_SPIN_LIMIT_US overrides it).
+// wall clock (default 0.2 s; talon_set_spin_limit_us changes it).
+std::atomic<long long> g_spin_limit_us{200000};
 unsigned long long spin_limit_ticks() {
-  const char* e = getenv("TALON_SPIN_LIMIT_US");
-  const long long us = e ? atoll(e) : 200000;
+  const long long us = g_spin_limit_us.load(std::memory_order_relaxed);
   return static_cast<unsigned long long>(us < 0 ? 0 : us) * 100ull;
 }
 
@@ -455,6 +460,45 @@ int talon_build_tree(const int32_t* root_token, const void* logits, int dtype, i
                           row_max, row_lse, workspace, workspace_bytes, stream);
 }
 
+int talon_build_tree_checked(const int32_t* root_token, const void* logits, int dtype, int64_t row_stride,
+                             int64_t seq_stride, int row_mode, const talon_tree_state* st, int32_t vocab, int32_t k,
+                             float mu, int32_t K_init, int32_t init_layers, int32_t max_depth, int32_t* cand_token,
+                             float* cand_logit, float* cand_prob, double* cand_edge_logp, float* row_max,
+                             double* row_lse, uint64_t* mask, void* workspace, size_t workspace_bytes, void* stream,
+                             int32_t* fell_back) {
+  if (fell_back) *fell_back = 0;
+  int rc = talon_build_tree(root_token, logits, dtype, row_stride, seq_stride, row_mode, st, vocab, k, mu, K_init,
+                            init_layers, max_depth, cand_token, cand_logit, cand_prob, cand_edge_logp, row_max, row_lse,
+                            mask, workspace, workspace_bytes, stream);
+  if (rc) return rc;
+  // the outcome of the single launch: did any workgroup give up its wait between two layers?
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  std::vector<uint32_t> status(static_cast<size_t>(st->B));
+  rc = check_hip(hipMemcpyAsync(status.data(), st->status, status.size() * sizeof(uint32_t), hipMemcpyDeviceToHost, s),
+                 "status copy");
+  if (rc) return rc;
+  rc = check_hip(hipStreamSynchronize(s), "stream synchronize");
+  if (rc) return rc;
+  bool aborted = false;
+  for (uint32_t v : status) aborted = aborted || (v & TALON_STATUS_ABORTED) != 0;
+  if (!aborted) return TALON_OK;
+  // The launch that gave up has put the workspace back in order (its last workgroup clears
+  // every ticket and descriptor): build the same trees again, one launch per layer, which
+  // needs no two workgroups to be resident together.
+  if (fell_back) *fell_back = 1;
+  rc = talon_tree_init(st, root_token, stream);
+  if (rc) return rc;
+  const int layers = max_depth < st->N - 1 ? max_depth : st->N - 1;
+  for (int d = 0; d < layers; ++d) {
+    rc = talon_expand_select_layer(logits, dtype, row_stride, seq_stride, row_mode, d, st, vocab, k, mu, K_init, init_layers,
+                                   max_depth, cand_token, cand_logit, cand_prob, cand_edge_logp, row_max, row_lse,
+                                   workspace, workspace_bytes, stream);
+    if (rc) return rc;
+  }
+  if (mask) rc = talon_build_tree_mask(st, mask, stream);
+  return rc;
+}
+
 size_t talon_literal_workspace_bytes(int32_t B, int32_t N_pad, int32_t vocab, int dtype) {
   LiteralLayout V;
   if (literal_layout(B, N_pad, vocab, dtype, &V)) return 0;
@@ -519,6 +563,12 @@ int talon_expand_literal(const void* logits, int dtype, int64_t row_stride, int6
     rc = check_hip(launch_literal_layer(la, dtype, s), "literal layer launch");
     if (rc) return rc;
   }
+  return TALON_OK;
+}
+
+int talon_set_spin_limit_us(int64_t microseconds) {
+  if (microseconds < 0) { set_error("spin limit of %lld us is negative", (long long)microseconds); return TALON_ERR_INVALID_ARG; }
+  g_spin_limit_us.store(microseconds, std::memory_order_relaxed);
   return TALON_OK;
 }
 
@@ -670,7 +720,7 @@ static int attention_layout(int32_t B, int32_t N_pad, int32_t Hq, int32_t Hkv, i
   if (Hq / Hkv > 16) { set_error("Hq/Hkv=%d above 16 is not supported", Hq / Hkv); return TALON_ERR_UNSUPPORTED; }
   attention_plan(B, N_pad, Hq, Hkv, Dh, max_prefix_len, splits, tps, rows_pad);
   const size_t prow = static_cast<size_t>(B) * Hkv * (*splits) * (*rows_pad);
-  *off_m = prow * Dh * sizeof(float);
+  *off_m = prow * Dh * sizeof(uint16_t);   // bf16 partial outputs, then fp32 maxima and denominators
   *off_l = *off_m + prow * sizeof(float);
   *total = *off_l + prow * sizeof(float);
   if (*splits == 1) *total = 256;  // nothing is staged, keep a token size
@@ -744,7 +794,7 @@ static int tree_attention_call(const void* q, const void* k_prefix, const void* 
   a.out = static_cast<uint16_t*>(out);
   a.out_lse = out_lse;
   char* w = static_cast<char*>(workspace);
-  a.part_o = reinterpret_cast<float*>(w);
+  a.part_o = reinterpret_cast<uint16_t*>(w);
   a.part_m = reinterpret_cast<float*>(w + off_m);
   a.part_l = reinterpret_cast<float*>(w + off_l);
   return check_hip(launch_attention(a, static_cast<hipStream_t>(stream)), "tree attention launch");

@@ -27,6 +27,9 @@
 
 #include "device_utils.h"
 #include "talon_internal.h"
+#ifdef TALON_TUNING
+#include "tuning.h"
+#endif
 
 namespace talon {
 
@@ -131,9 +134,9 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void tree_attention_kerne
   const int t_end = (t_begin + a.tiles_per_split < T) ? t_begin + a.tiles_per_split : T;
   const int words = a.N_pad / 64;
 
-  // ---- this lane's queries (one per row block) and their Q^T operands
+  // ---- this lane's queries (one per row block): which node and head each is
   const int wrow0 = row0 + wave * 32 * RB;
-  bf16x8 bq[RB][DSTEPS];
+  bf16x8 bq[RB][DSTEPS];   // Q^T operands, loaded in the prologue below
   int node_rb[RB];
   bool valid_rb[RB];
   size_t orow_rb[RB];  // (b*N_pad + node)*Hq + head
@@ -146,30 +149,6 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void tree_attention_kerne
     node_rb[rb] = node;
     valid_rb[rb] = valid;
     orow_rb[rb] = (static_cast<size_t>(b) * a.N_pad + node) * a.Hq + g * G + j;
-    const uint16_t* qp = a.q + orow_rb[rb] * DH + 8 * h;
-#pragma unroll
-    for (int ds = 0; ds < DSTEPS; ++ds) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (valid) v = *reinterpret_cast<const uint4*>(qp + 16 * ds);
-      bq[rb][ds] = as_bf16x8(v);
-    }
-  }
-
-  // Make the compiler wait for the query loads here, in straight-line code: otherwise it
-  // places its wait for them at their first use inside the loop, where it would also wait
-  // for every tile load in flight (see global_to_lds_16).
-  {
-    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    static_assert(RB == 1 && (DSTEPS == 8 || DSTEPS == 4), "one statement names every query fragment");
-    u32x4 qv[DSTEPS];
-#pragma unroll
-    for (int ds = 0; ds < DSTEPS; ++ds) qv[ds] = __builtin_bit_cast(u32x4, bq[0][ds]);
-    if constexpr (DSTEPS == 8)
-      asm volatile("" : "+v"(qv[0]), "+v"(qv[1]), "+v"(qv[2]), "+v"(qv[3]), "+v"(qv[4]), "+v"(qv[5]), "+v"(qv[6]), "+v"(qv[7]));
-    else
-      asm volatile("" : "+v"(qv[0]), "+v"(qv[1]), "+v"(qv[2]), "+v"(qv[3]));
-#pragma unroll
-    for (int ds = 0; ds < DSTEPS; ++ds) bq[0][ds] = __builtin_bit_cast(bf16x8, qv[ds]);
   }
 
   float m_run[RB], l_run[RB];
@@ -433,8 +412,27 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void tree_attention_kerne
     tile_landed();
   };
 
-  // The ancestor words of this workgroup's rows go to LDS once: inside the loop the only
-  // global loads are then the tile loads above, whose waits are all explicit.
+  // Prologue.  Three kinds of loads start the workgroup: the first K/V tiles (global to LDS),
+  // this lane's queries (registers) and the ancestor words of the workgroup's rows (LDS, so that
+  // inside the loop the only global loads are the tile loads, whose waits are all explicit).
+  // They are issued back to back, tiles first, and waited for together: one memory round trip
+  // instead of three.
+  if (nt > 0) {
+    load_k(t_begin, 0);
+    load_v(t_begin, 0);
+    if (nt > 1) load_k(t_begin + 1, 1);
+  }
+  // ---- this lane's queries (loaded here, after the tile loads have been issued)
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    const uint16_t* qp = a.q + orow_rb[rb] * DH + 8 * h;
+#pragma unroll
+    for (int ds = 0; ds < DSTEPS; ++ds) {
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (valid_rb[rb]) v = *reinterpret_cast<const uint4*>(qp + 16 * ds);
+      bq[rb][ds] = as_bf16x8(v);
+    }
+  }
   for (int idx = tid; idx < 32 * NW * RB * words; idx += kWgThreads) {
     const int r = idx / words;
     const int rho = row0 + r;
@@ -442,11 +440,25 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void tree_attention_kerne
     if (rho < rows) wv = a.mask[(static_cast<size_t>(b) * a.N_pad + rho / G) * words + (idx - r * words)];
     s_mask[idx] = wv;
   }
+  // Make the compiler wait for the query loads here, in straight-line code: otherwise it
+  // places its wait for them at their first use inside the loop, where it would also wait
+  // for every tile load in flight (see global_to_lds_16).
+  {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    static_assert(RB == 1 && (DSTEPS == 8 || DSTEPS == 4), "one statement names every query fragment");
+    u32x4 qv[DSTEPS];
+#pragma unroll
+    for (int ds = 0; ds < DSTEPS; ++ds) qv[ds] = __builtin_bit_cast(u32x4, bq[0][ds]);
+    if constexpr (DSTEPS == 8)
+      asm volatile("" : "+v"(qv[0]), "+v"(qv[1]), "+v"(qv[2]), "+v"(qv[3]), "+v"(qv[4]), "+v"(qv[5]), "+v"(qv[6]), "+v"(qv[7]));
+    else
+      asm volatile("" : "+v"(qv[0]), "+v"(qv[1]), "+v"(qv[2]), "+v"(qv[3]));
+#pragma unroll
+    for (int ds = 0; ds < DSTEPS; ++ds) bq[0][ds] = __builtin_bit_cast(bf16x8, qv[ds]);
+  }
+
   floatx16 s_a[2][RB], s_b[2][RB];
   if (nt > 0) {
-    load_k(t_begin, 0);
-    load_v(t_begin, 0);
-    if (nt > 1) load_k(t_begin + 1, 1);
     tile_landed();
     qk(stage_k(0), s_a);
     mask_scores(t_begin, s_a);
@@ -477,10 +489,17 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void tree_attention_kerne
       const auto sw = __builtin_amdgcn_permlane32_swap(li, li, false, false);
       l_tot = __int_as_float(static_cast<int>(sw[0])) + __int_as_float(static_cast<int>(sw[1]));
     }
-    if (!valid_rb[rb]) continue;
+    // Where this lane's row goes is worked out again here, from a lane index the compiler cannot
+    // trace back: otherwise it keeps the output addresses alive (or spills them) across the loop.
+    int l32_e = l32;
+    asm volatile("" : "+v"(l32_e));
+    const int rho_e = wrow0 + 32 * rb + l32_e;
+    if (rho_e >= rows) continue;
+    const int node_e = rho_e / G;
+    const size_t orow_e = (static_cast<size_t>(b) * a.N_pad + node_e) * a.Hq + g * G + (rho_e - node_e * G);
     if (a.splits == 1) {
       const float inv = 1.f / l_tot;
-      uint16_t* op = a.out + orow_rb[rb] * DH;
+      uint16_t* op = a.out + orow_e * DH;
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
 #pragma unroll
@@ -491,21 +510,26 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void tree_attention_kerne
           *reinterpret_cast<bf16x4*>(op + 32 * db + 8 * q4 + 4 * h) = v;
         }
       }
-      if (a.out_lse && h == 0) a.out_lse[orow_rb[rb]] = (m_run[rb] + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
+      if (a.out_lse && h == 0) a.out_lse[orow_e] = (m_run[rb] + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
     } else {
-      // Partial O^T of a (KV head, split) is laid out in slabs of 8 head-dim values:
-      // [DH / 8][rows_pad][8], so that the 64 lanes of a store (32 rows x 2 halves of a slab
-      // entry) cover 1 KiB of consecutive addresses; row-major would give 32-byte pieces.
-      const int rho = wrow0 + 32 * rb + l32;
+      // Partial O^T of a (KV head, split), normalised by the split's own denominator and rounded
+      // to bf16 (half the bytes of the round trip through memory; the rounding, 2^-9 relative
+      // per split, is below that of the final bf16 output), laid out in slabs of 8 head-dim
+      // values: [DH / 8][rows_pad][8], so that the 64 lanes of a store (32 rows x 2 halves of a
+      // slab entry) cover 512 consecutive bytes; row-major would give 8-byte pieces.
+      const int rho = rho_e;
       const size_t pblock = (static_cast<size_t>(bg) * a.splits + split) * a.rows_pad;
       const size_t prow = pblock + rho;
-      float* po = a.part_o + pblock * DH + static_cast<size_t>(rho) * 8 + 4 * h;
+      uint16_t* po = a.part_o + pblock * DH + static_cast<size_t>(rho) * 8 + 4 * h;
+      const float inv_l = l_tot > 0.f ? 1.f / l_tot : 0.f;
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
-          float4 v = make_float4(o[db][rb][4 * q4], o[db][rb][4 * q4 + 1], o[db][rb][4 * q4 + 2], o[db][rb][4 * q4 + 3]);
-          *reinterpret_cast<float4*>(po + static_cast<size_t>(4 * db + q4) * a.rows_pad * 8) = v;
+          bf16x4 v;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = static_cast<__bf16>(o[db][rb][4 * q4 + e] * inv_l);
+          *reinterpret_cast<bf16x4*>(po + static_cast<size_t>(4 * db + q4) * a.rows_pad * 8) = v;
         }
       }
       if (h == 0) {
@@ -516,7 +540,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void tree_attention_kerne
   }
 }
 
-// Merge of the split-KV partial results: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
+// Merge of the split-KV partial results (O_s normalised by its own l_s):
+// out = sum_s 2^(m_s - M) l_s O_s / sum_s 2^(m_s - M) l_s.
 // One thread per (packed row, 4 head-dim values).  A workgroup takes 256 / (DH / 4) rows.  It
 // reads the partial results in their slab order (thread = (slab, row, half): consecutive
 // threads, consecutive addresses) and turns its results through LDS to write whole output
@@ -556,11 +581,12 @@ __global__ __launch_bounds__(kThreads) void tree_attention_combine_kernel(AttnAr
     const size_t pr = base + static_cast<size_t>(s) * a.rows_pad;
     const float ms = a.part_m[pr];
     const float ls = a.part_l[pr];
-    const float4 v = *reinterpret_cast<const float4*>(
+    const bf16x4 v = *reinterpret_cast<const bf16x4*>(
         a.part_o + (block0 + static_cast<size_t>(s) * a.rows_pad) * DH + in_block);
-    const float w = ms == kNegInfF ? 0.f : __builtin_amdgcn_exp2f(ms - M);   // an empty split stores zeros
-    den += w * ls;
-    acc.x += w * v.x; acc.y += w * v.y; acc.z += w * v.z; acc.w += w * v.w;
+    const float w = ms == kNegInfF ? 0.f : __builtin_amdgcn_exp2f(ms - M) * ls;   // an empty split: weight 0
+    den += w;
+    acc.x += w * static_cast<float>(v[0]); acc.y += w * static_cast<float>(v[1]);
+    acc.z += w * static_cast<float>(v[2]); acc.w += w * static_cast<float>(v[3]);
   }
   const float inv = 1.f / den;
   bf16x4 v;
@@ -591,13 +617,11 @@ hipError_t launch_one(const AttnArgs& a_in, hipStream_t s) {
   a.row_tiles = (a.N_pad * a.G + 32 * NW - 1) / (32 * NW);
   a.total_items = a.row_tiles * a.splits * a.B * a.Hkv;
   auto kern = tree_attention_kernel<DH, NW>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       Smem<DH>::BYTES);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  // (initialisation of a function-local static is thread-safe: two host threads making their
+  // first call together set the attribute once)
+  static const hipError_t attr_result = hipFuncSetAttribute(
+      reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, Smem<DH>::BYTES);
+  if (attr_result != hipSuccess) return attr_result;
   hipLaunchKernelGGL(kern, dim3(8 * ((a.total_items + 7) / 8)), dim3(64 * NW), Smem<DH>::BYTES, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -619,26 +643,20 @@ hipError_t launch_one(const AttnArgs& a_in, hipStream_t s) {
 // the grid aims at filling 256 compute units; but a split must keep enough key tiles to
 // amortise its fixed work (query load, first tile, the partial result it writes and the
 // merge reads back).
+#ifndef TALON_TUNING
+constexpr int tuned_int(const char*, int dflt) { return dflt; }
+#endif
+
 int attention_waves(int rows) {
-  static int forced = -1;   // tuning knob: TALON_ATTN_WAVES = 4 or 8
-  if (forced < 0) {
-    const char* e = getenv("TALON_ATTN_WAVES");
-    forced = e ? atoi(e) : 0;
-    if (forced != 4 && forced != 8) forced = 0;
-  }
-  if (forced) return forced;
+  const int forced = tuned_int("TALON_ATTN_WAVES", 0);   // tuning builds: 4 or 8
+  if (forced == 4 || forced == 8) return forced;
   return rows >= 512 ? 8 : 4;
 }
 
 void attention_plan(int B, int N_pad, int Hq, int Hkv, int Dh, int max_prefix_len, int* splits,
                     int* tiles_per_split, int* rows_pad) {
   (void)Dh;
-  static int min_tiles = 0;   // tuning knob: TALON_ATTN_MIN_TILES
-  if (min_tiles == 0) {
-    const char* e = getenv("TALON_ATTN_MIN_TILES");
-    min_tiles = e ? atoi(e) : 4;
-    if (min_tiles < 1) min_tiles = 4;
-  }
+  const int min_tiles = tuned_int("TALON_ATTN_MIN_TILES", 4);   // key tiles a split must keep
   const int G = Hq / Hkv;
   const int rows = N_pad * G;
   const int waves = attention_waves(rows);

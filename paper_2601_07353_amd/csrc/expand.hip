@@ -39,6 +39,15 @@
 // softmax statistics.
 #include "select_device.h"
 
+// Time-stamp marks exist only in tuning builds (-DTALON_TUNING pulls in tuning.h).
+#ifdef TALON_TUNING
+#define TALON_TUNING_MARKS
+#include "tuning.h"
+#else
+#define TL_MARK(d, i) do { } while (0)
+#define TL_ANY(d, i) do { } while (0)
+#endif
+
 namespace talon {
 
 namespace {
@@ -48,39 +57,6 @@ constexpr int kHitTrigger = 64;                  // buffered vectors that trigge
 constexpr int kHitCap = kHitTrigger + 64;        // a tile adds at most 64 vectors
 constexpr int kSubBatch = 32;                    // vectors expanded per ranking round (two lanes per vector)
 constexpr int kSubKeys = kSubBatch * 8 + TALON_K_MAX + 16;  // keys ranked per round (<= 8 logits per vector) + zero padding
-
-// Phase timestamps (100 MHz wall clock) of workgroup 0; compiled only into tuning builds
-// with -DTALON_PHASE_TIMING.
-#ifdef TALON_PHASE_TIMING
-__device__ unsigned long long g_phase[16];
-#define PHASE(i) do { if (threadIdx.x == 0 && blockIdx.x == 0) g_phase[i] = wall_clock64(); } while (0)
-__device__ unsigned long long g_wg[1024][16];   // per-workgroup time stamps of its first item
-#ifdef TALON_TIMELINE_ONLY   // only the per-layer marks of the single-launch kernel: nothing that perturbs it
-#define PHASE_MAX(i) do { } while (0)
-#define WG_MARK(i) do { } while (0)
-#define WG_MARK2(i) do { } while (0)
-#else
-#define PHASE_MAX(i) do { if (threadIdx.x == 0) atomicMax(&g_phase[i], wall_clock64()); } while (0)
-#define WG_MARK(i) do { if (threadIdx.x == 0 && item == blockIdx.x && blockIdx.x < 1024) g_wg[blockIdx.x][i] = wall_clock64(); } while (0)
-#define WG_MARK2(i) do { if (threadIdx.x == 0 && blockIdx.x < 1024) g_wg[blockIdx.x][i] = wall_clock64(); } while (0)
-#endif
-__device__ unsigned long long g_tl[32][4];      // single-launch kernel: per-layer time stamps of workgroup 0
-#define TL_MARK(d, i) do { if (threadIdx.x == 0 && blockIdx.x == 0 && (d) < 32) g_tl[d][i] = wall_clock64(); } while (0)
-#define TL_ANY(d, i) do { if (threadIdx.x == 0 && (d) < 32) g_tl[d][i] = wall_clock64(); } while (0)
-#ifdef TALON_TIMELINE_ONLY
-#define WG_MARK_LOADED(i) do { } while (0)
-#else
-#define WG_MARK_LOADED(i) do { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); WG_MARK(i); } while (0)
-#endif
-#else
-#define WG_MARK(i) do { } while (0)
-#define TL_MARK(d, i) do { } while (0)
-#define TL_ANY(d, i) do { } while (0)
-#define WG_MARK2(i) do { } while (0)
-#define WG_MARK_LOADED(i) do { } while (0)
-#define PHASE(i) do { } while (0)
-#define PHASE_MAX(i) do { } while (0)
-#endif
 
 // One 16-byte vector of a logits row, with -inf in the lanes past the end of the row.
 template <int EPL>
@@ -219,7 +195,11 @@ constexpr int kCandCap = 512;   // keys of a row merge that can still be among t
 template <bool FUSED>
 __device__ __forceinline__ bool write_row(const ExpandArgs& a, int b, int out_row, const unsigned long long* keys,
                                           int lists, float m, double sum, unsigned long long* s_cand, int* s_nc) {
-  const int tid = threadIdx.x;
+  // (thread index taken afresh, through an empty asm statement: addresses derived from it are
+  // then computed here, at their use, instead of being kept alive or spilled across the
+  // caller's streaming loop)
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
   const int k = a.k;
   const double lse = static_cast<double>(m) + log_of_sum(sum);
   const size_t ob = static_cast<size_t>(out_row) * k;
@@ -287,7 +267,6 @@ __device__ __forceinline__ bool write_row(const ExpandArgs& a, int b, int out_ro
       }
     }
   }
-  WG_MARK2(11);
   const int valid = a.vocab < k ? a.vocab : k;
   if (tid >= valid && tid < k) {
     a.cand_logit[ob + tid] = kNegInf;
@@ -360,7 +339,6 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  PHASE(0);
 
   // ---- frontier sizes of all sequences -> item map (identical in every workgroup)
   __shared__ int s_gave_up;
@@ -410,8 +388,6 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
       if (s_gave_up) return -1;
     }
   }
-  PHASE(1);
-  PHASE_MAX(10);
   const int total_rows = s_prefix[a.B];
   if (total_rows == 0) return 0;
   const int k = a.k;
@@ -503,28 +479,44 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
     // Streaming state machine.  A step is a group of 4 tiles.  Tiles whose hits do not fit the
     // buffer are deferred, together with all later tiles of the group, to the single slow
     // section below, which cuts the buffer and then re-reads them.
-    PHASE(2);
-    WG_MARK(0);
+    // One group of 4 tiles of this thread: plain vector loads where the group lies wholly inside
+    // the row, guarded loads (-inf past the end) at the ragged end.
+    auto load_group = [&](int t, uint4 (&r)[kScanTiles]) {
+      if (t + kScanTiles <= full_tiles) {
+#pragma unroll
+        for (int q = 0; q < kScanTiles; ++q)
+          r[q] = *reinterpret_cast<const uint4*>(lane_ptr + (t + q) * kTileBytes);
+      } else {
+#pragma unroll
+        for (int q = 0; q < kScanTiles; ++q)
+          r[q] = load_vec<EPL>(row, ((t + q) * kThreads + tid) * EPL, a.vocab);
+      }
+    };
     int tb = t0;
     bool done = false;
+    // With the selection in the launch the kernel runs three workgroups per compute unit and has
+    // registers to spare: the loads of the next group are issued before the current one is
+    // processed, so that a chunk of several blocks does not pay the memory latency per block.
+    // The scan-only launch runs four workgroups per compute unit on 128 registers and relies on
+    // those for the overlap.
+    constexpr bool PREFETCH = FUSED;
+    uint4 raw_next[kScanTiles];
+    if constexpr (PREFETCH) {
+      if (tb < t1) load_group(tb, raw_next);
+    }
     while (!done) {
       uint32_t deferred = 0;   // bit q: tile def_base + q still has to be buffered
       int def_base = tb;
       bool force = false;
       if (tb < t1) {
-        // No software prefetch: many resident wavefronts, each with 4 loads in flight, hide
-        // the latency, and the loop stays small in registers.
         uint4 raw[kScanTiles];
-        if (tb + kScanTiles <= full_tiles) {
+        if constexpr (PREFETCH) {
 #pragma unroll
-          for (int q = 0; q < kScanTiles; ++q)
-            raw[q] = *reinterpret_cast<const uint4*>(lane_ptr + (tb + q) * kTileBytes);
+          for (int q = 0; q < kScanTiles; ++q) raw[q] = raw_next[q];
+          if (tb + kScanTiles < t1) load_group(tb + kScanTiles, raw_next);
         } else {
-#pragma unroll
-          for (int q = 0; q < kScanTiles; ++q)
-            raw[q] = load_vec<EPL>(row, ((tb + q) * kThreads + tid) * EPL, a.vocab);
+          load_group(tb, raw);
         }
-        WG_MARK_LOADED(5);
         // lane maxima of the 4 tiles first; the running max moves at most once per group
         float vmax4[kScanTiles];
 #pragma unroll
@@ -560,9 +552,7 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
           for (int e = 0; e < EPL; ++e) acc += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e], kLog2e, -c));
         }
         s_l += static_cast<double>(acc * __builtin_amdgcn_exp2f(-c_err));
-        WG_MARK(6);
         if (tb == t0) { first_threshold(gmax); force = true; }
-        WG_MARK(7);
 #pragma unroll
         for (int q = 0; q < kScanTiles; ++q)
           if (deferred != 0u || !buffer_hits(raw[q], vmax4[q], tb + q)) deferred |= 1u << q;
@@ -572,7 +562,6 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
         done = true;
       }
 
-      WG_MARK(8);
       if (force || deferred != 0u || cnt > kHitTrigger) {
         // ---- slow section: cut the buffer to the k best; then buffer the deferred tiles
         while (true) {
@@ -620,7 +609,6 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
             if (tcnt >= k) tau = fmaxf(tau, key_logit(topw[k - 1]));
           }
           cnt = 0;
-          WG_MARK(9);
           if (tcnt >= k) tau = float_above(key_logit(topw[k - 1]));
           if (deferred == 0u) break;
 #pragma unroll 1
@@ -639,9 +627,6 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
         }
       }
     }
-    PHASE(3);
-    PHASE_MAX(15);
-    WG_MARK(1);
 
     // ---- wavefront statistics
     {
@@ -654,7 +639,6 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
       if (lane >= tcnt) topw[lane] = 0ull;   // unused slots of the list: zero keys
     }
     __syncthreads();
-    PHASE(4);
 
     // ---- merge the four lists (each <= k keys, zero keys in the unused slots) into the
     // chunk's k best, sorted.  Lane 16w+i of every wavefront holds key i of list w; wavefront v
@@ -684,8 +668,6 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
     for (int w = 0; w < 4; ++w)
       if (s_wmax[w] != kNegInf) csum += s_wsum[w] * static_cast<double>(__expf(s_wmax[w] - cm));
     __syncthreads();
-    PHASE(5);
-    WG_MARK(2);
 
     bool row_written = false;   // this workgroup has just written a whole row's outputs
     bool row_bad = false;       // ... and the row could not be normalised
@@ -731,9 +713,6 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
         s_last = (old == chunks - 1) ? 1 : 0;
       }
       __syncthreads();
-      PHASE(6);
-      PHASE_MAX(14);
-      WG_MARK(3);
       if (s_last) {
         const float* pm = a.part_max + static_cast<size_t>(out_row) * blocks_per_row;
         const double* ps = a.part_sum + static_cast<size_t>(out_row) * blocks_per_row;
@@ -759,13 +738,8 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
         }
         sum = wave_sum_f64(sum);
         __syncthreads();   // s_keys is staged
-        WG_MARK2(10);
-        PHASE(7);
-        PHASE_MAX(12);
         start_tree();
         row_bad = write_row<FUSED>(a, b, out_row, s_keys, chunks, m, sum, s_cand, &s_nc);
-        PHASE_MAX(13);
-        WG_MARK2(12);
         if (tid == 0) store_agent(a.ticket + out_row, 0);  // leave the workspace clean for the next layer
         row_written = true;
       }
@@ -821,11 +795,7 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
       }
     }
     __syncthreads();  // s_keys / s_top / s_w* are reused by the next item
-    PHASE(8);
-    WG_MARK(4);
-    PHASE_MAX(11);
   }
-  PHASE(9);
   return total_rows;
 }
 
@@ -1006,22 +976,6 @@ hipError_t launch_expand(const ExpandArgs& a, int dtype, int grid, bool fused, h
   }
   return hipGetLastError();
 }
-
-#ifdef TALON_PHASE_TIMING
-extern "C" int talon_debug_read_phases(unsigned long long* host16) {
-  return static_cast<int>(hipMemcpyFromSymbol(host16, HIP_SYMBOL(g_phase), sizeof(unsigned long long) * 16));
-}
-extern "C" int talon_debug_read_wg(unsigned long long* host) {
-  return static_cast<int>(hipMemcpyFromSymbol(host, HIP_SYMBOL(g_wg), sizeof(unsigned long long) * 1024 * 16));
-}
-extern "C" int talon_debug_read_timeline(unsigned long long* host) {
-  return static_cast<int>(hipMemcpyFromSymbol(host, HIP_SYMBOL(g_tl), sizeof(unsigned long long) * 32 * 4));
-}
-extern "C" int talon_debug_clear_phases() {
-  unsigned long long z[16] = {0};
-  return static_cast<int>(hipMemcpyToSymbol(HIP_SYMBOL(g_phase), z, sizeof(z)));
-}
-#endif
 
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
   const size_t n = bytes / 4;

@@ -66,7 +66,11 @@ __device__ __forceinline__ unsigned long long select_sequence(const SelectArgs& 
                                                               uint32_t status, const SelectLds& lds,
                                                               int n_known = -1, int d_known = -1) {
   const talon_tree_state& st = a.st;
-  const int tid = threadIdx.x;
+  // (the thread index is taken afresh, through an empty asm statement: a caller that inlines this
+  // into a long kernel would otherwise keep the per-thread addresses computed from it alive, or
+  // spilled, across all of its own code)
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
   unsigned long long* s_key = lds.key;
   int* s_hist = lds.hist;
   unsigned long long* s_red_u64 = lds.red_u64;

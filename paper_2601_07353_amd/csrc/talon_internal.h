@@ -123,7 +123,7 @@ struct AttnArgs {
   float* out_lse;
   int splits;            // KV splits per (sequence, kv head, row tile)
   int tiles_per_split;   // key tiles of kAttnKeyTile per split
-  float* part_o;         // [B][Hkv][splits][rows_pad][Dh]  unnormalised partial outputs
+  uint16_t* part_o;      // [B][Hkv][splits][Dh/8][rows_pad][8] bf16: each split's output, normalised by its own denominator
   float* part_m;         // [B][Hkv][splits][rows_pad]      running max (base-2 units)
   float* part_l;         // [B][Hkv][splits][rows_pad]      running denominator
   int rows_pad;          // N_pad * G rounded up to the row tile

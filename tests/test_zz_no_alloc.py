@@ -52,15 +52,15 @@ def test_static_scratch_attention_matches_the_workspace_call_twice_in_a_row():
     import paper_2601_07353_amd as T
     T.talon_static_scratch_init()
     rng = np.random.default_rng(20260107)
-    _case(rng, 1, [60], 32, 8, 128, [2048])            # the Llama-3-8B-shaped call: 7 splits, 7.4 MB of partials
+    _case(rng, 1, [60], 32, 8, 128, [2048])            # the Llama-3-8B-shaped call: 7 splits, 3.8 MB of partials
     _case(rng, 2, [37, 20], 8, 2, 64, [700, 333])      # smaller, ragged, other head size: same array
 
 
 def test_static_scratch_refuses_what_does_not_fit():
-    """Host-side check: the 70B-shaped call needs more than the array holds; nothing is launched."""
+    """Host-side check: two 70B-shaped sequences need more than the array holds; nothing is launched."""
     import torch
     import paper_2601_07353_amd as T
-    B, N_pad, Hq, Hkv, Dh, L = 1, 64, 64, 8, 128, 8192
+    B, N_pad, Hq, Hkv, Dh, L = 2, 64, 64, 8, 128, 8192
     assert T.talon_tree_attention_workspace_bytes(B, N_pad, Hq, Hkv, Dh, L) > T.talon_static_scratch_bytes()
     z = lambda *shape: torch.zeros(*shape, dtype=torch.bfloat16, device="cuda")
     n = torch.ones(B, dtype=torch.int32, device="cuda")
