@@ -385,13 +385,14 @@ int run_fused_layers(bool single_launch, const int32_t* root_token, uint64_t* ma
     if (mask) return check_hip(launch_mask(*st, mask, s), "mask launch");
     return TALON_OK;
   }
-  // The single launch starts fresh trees itself; continuing trees in a single launch takes its
-  // first frontier from the public tree state in a small launch of its own.  Every launch form
-  // leaves the workspace's tickets and descriptors as it found them (zero).
+  // The single launch starts fresh trees itself and leaves its counters clean; every other
+  // mode takes its first frontier from a snapshot of the public tree state made by a small
+  // launch of its own (the selections of a launch rewrite the public state while workgroups of
+  // the same launch may still be starting, and every workgroup must see the same item map).
   const bool starts_trees = root_token != nullptr;   // talon_build_tree only: single launch, first layer 0
   if (starts_trees) ea.root_token = root_token;
-  else if (single_launch && (rc = check_hip(launch_fused_init(*st, ea, s), "fused init launch"))) return rc;
-  if (!single_launch) {   // one layer, one launch: the kernel reads its frontier from the public tree state
+  else if ((rc = check_hip(launch_fused_init(*st, ea, s), "fused init launch"))) return rc;
+  if (!single_launch) {   // one layer, one launch
     ea.launch_idx = 0;
     if (g_profile.enabled && (rc = check_hip(profile_record(s), "profile event"))) return rc;
     rc = check_hip(launch_expand(ea, dtype, expand_grid(st, L.chunks, first_layer, k, K_init, init_layers), true, s), "expand launch");

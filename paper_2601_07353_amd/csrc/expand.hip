@@ -351,10 +351,13 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
       if (TREE && a.root_token && launch_idx == 0) {   // fresh trees: the frontier is the root
         s_begin[tid] = 0;
         c = 1;
-      } else if constexpr (TREE) {   // {begin, count} in one 8-byte load
+      } else if constexpr (FUSED) {   // {begin, count} in one 8-byte load
+        // (also in a launch of one layer: its selections rewrite the public tree state while
+        // workgroups may still be starting, so the frontier is read from a snapshot taken by a
+        // small launch before this one; every workgroup must see the same item map)
         const unsigned long long* dp = a.desc + (launch_idx * a.B + tid);
         unsigned long long d2 = ld<TREE, unsigned long long>(dp);
-        {
+        if constexpr (TREE) {
           // the selection of the layer before stores this word when all it wrote has been
           // performed: wait for it (bounded)
           if (!(d2 & kDescReady)) {
@@ -368,8 +371,7 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
         }
         s_begin[tid] = static_cast<int>(static_cast<uint32_t>(d2));
         c = static_cast<int>(static_cast<uint32_t>(d2 >> 32) & 0x7FFFFFFFu);
-      } else {  // one layer per launch: the frontier is the public tree state's (the loads are
-                // issued together; the select below is register-only)
+      } else {  // the loads are issued together; the select below is register-only
         const uint32_t stat = a.status[tid];
         const int fc = a.frontier_count[tid];
         s_begin[tid] = a.frontier_begin[tid];

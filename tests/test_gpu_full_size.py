@@ -75,7 +75,6 @@ def run_config(cfg_name):
     pool = H.build_pool(cfg, seeds)
     attn = [attention_inputs(cfg, seeds[b], b) for b in range(cfg.B)]
     gpu = H.run_gpu_step(cfg, seeds, pool=pool, attn=attn)
-    del pool
     masks = []
     for b in range(cfg.B):
         structural_checks(cfg, gpu, b)
@@ -85,11 +84,11 @@ def run_config(cfg_name):
         np.testing.assert_array_equal(gpu["mask"][b], O.mask_to_words(masks[b], cfg.N_pad))
         # rows of nodes beyond n_nodes are untouched
         assert not gpu["attn_out"][b, int(gpu["n_nodes"][b]):].any()
-    return cfg, gpu, trees, masks, attn
+    return cfg, gpu, trees, masks, attn, pool
 
 
 def run_full(cfg_name):
-    cfg, gpu, trees, masks, attn = run_config(cfg_name)
+    cfg, gpu, trees, masks, attn, _ = run_config(cfg_name)
     worst = (0.0, 0.0)
     for b in range(cfg.B):
         w = attention_check(cfg, gpu, b, masks[b], Decoded(attn[b], trees[b].n))
@@ -111,13 +110,24 @@ def c5_run():
 
 
 def test_c5_stress_full_size_all_trees(c5_run):
-    cfg, gpu, trees, _, _ = c5_run
+    cfg, gpu, trees, _, _, _ = c5_run
     assert len(trees) == 16 and all(t.n == int(gpu["n_nodes"][b]) for b, t in enumerate(trees))
+
+
+def test_c5_stress_per_layer_launches(c5_run):
+    """The same sixteen trees through one fused launch per layer (talon_expand_select_layer).  At
+    this size a launch has more workgroups than the device starts at once and its selections
+    finish while others are still starting: every workgroup must still see the frontier the
+    launch began with (it reads a snapshot, not the public state the selections rewrite)."""
+    cfg, _, trees, masks, _, pool = c5_run
+    gpu = H.run_gpu_step(cfg, pool=pool, with_attention=False, layerwise="fused")
+    H.compare_tree(cfg, gpu, trees, check_rows=False)
+    H.compare_mask(cfg, gpu, masks)
 
 
 def test_c5_stress_full_size_attention_sample(c5_run):
     """All nodes x heads {2, 29} x sequences {3, 12}, then 256 random (sequence, head, node) triples."""
-    cfg, gpu, trees, masks, attn = c5_run
+    cfg, gpu, trees, masks, attn, _ = c5_run
     worst = [0.0, 0.0]
 
     def note(w):
