@@ -370,7 +370,7 @@ int talon_tree_attention(const void* q, const void* k_prefix, const void* v_pref
  * talon_tree_attention for callers that cannot allocate device memory or pass a workspace
  * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the
  * same call, the same kernels and the same results, with the split-KV partial results kept in
- * a device array that is part of the library itself (talon_static_scratch_bytes() = 16 MiB per
+ * a device array that is part of the library itself (talon_static_scratch_bytes() = 32 MiB per
  * GPU, held from the moment the library is loaded on that GPU until the process ends).  The
  * call allocates nothing and frees nothing.
  *   - Shapes whose partial results need more than that (talon_tree_attention_workspace_bytes

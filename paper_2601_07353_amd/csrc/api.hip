@@ -247,7 +247,7 @@ using namespace talon;
 // One array per GPU, part of the library's code object: it exists from the moment the library
 // is loaded on a device until the process ends.  In host code the array's name is only a
 // handle: its device address is looked up once per device and that address is what kernels get.
-constexpr size_t kStaticScratchBytes = static_cast<size_t>(16) << 20;
+constexpr size_t kStaticScratchBytes = static_cast<size_t>(32) << 20;
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {

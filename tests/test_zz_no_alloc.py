@@ -57,15 +57,16 @@ def test_static_scratch_attention_matches_the_workspace_call_twice_in_a_row():
 
 
 def test_static_scratch_refuses_what_does_not_fit():
-    """Host-side check: two 70B-shaped sequences need more than the array holds; nothing is launched."""
+    """Host-side check: a shape whose partial results need a little more than the array holds (the launch plan
+    keeps them near twice the chip's workgroup slots, so few shapes do); nothing is launched."""
     import torch
     import paper_2601_07353_amd as T
-    B, N_pad, Hq, Hkv, Dh, L = 2, 64, 64, 8, 128, 8192
+    B, N_pad, Hq, Hkv, Dh, L = 21, 192, 16, 8, 128, 8192
     assert T.talon_tree_attention_workspace_bytes(B, N_pad, Hq, Hkv, Dh, L) > T.talon_static_scratch_bytes()
     z = lambda *shape: torch.zeros(*shape, dtype=torch.bfloat16, device="cuda")
     n = torch.ones(B, dtype=torch.int32, device="cuda")
     plen = torch.full((B,), L, dtype=torch.int32, device="cuda")
-    mask = torch.zeros(B, N_pad, 1, dtype=torch.int64, device="cuda")
+    mask = torch.zeros(B, N_pad, N_pad // 64, dtype=torch.int64, device="cuda")
     with pytest.raises(T.TalonError) as e:
         T.talon_tree_attention_static(z(B, N_pad, Hq, Dh), z(B, L, Hkv, Dh), z(B, L, Hkv, Dh), z(B, N_pad, Hkv, Dh),
                                       z(B, N_pad, Hkv, Dh), mask, n, plen, L, z(B, N_pad, Hq, Dh))
