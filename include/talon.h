@@ -234,6 +234,11 @@ int talon_build_tree_checked(const int32_t* root_token, const void* logits, int 
  * passes; >= max_depth: the whole loop); sequences that are finished are skipped.  Same tree
  * state, node order, ties and status bits as talon_expand_select_layer; no candidate
  * arrays are written.
+ * Trees of at most 64 nodes (N_pad = 64) take a shortcut where the workspace allows it: a row can
+ * get at most N - 1 <= 63 children, so the capped loop with k = N - 1 cuts nothing and builds
+ * the same tree in one launch (the launch talon_expand_tree makes).  With `layers` > 1 that
+ * launch's workgroups wait for each other between layers and can give up as described at
+ * talon_build_tree (TALON_STATUS_ABORTED on every sequence); calls with `layers` = 1 never wait.
  *   `workspace`: talon_literal_workspace_bytes bytes of device memory, no initialisation
  *   needed; it must not be shared with a call running at the same time.
  *   Errors: as talon_expand_layer and talon_select_budget (k does not apply).

@@ -139,9 +139,9 @@ def _stream(stream):
 class TreeState:
     """Device buffers of the token tree T (structure of arrays) plus the C struct that names them."""
 
-    def __init__(self, B: int, N: int, device="cuda"):
+    def __init__(self, B: int, N: int, device="cuda", N_pad: int | None = None):
         self.B, self.N = B, N
-        self.N_pad = (N + 63) // 64 * 64
+        self.N_pad = (N + 63) // 64 * 64 if N_pad is None else N_pad   # a multiple of 64, at least N
         i32 = dict(dtype=torch.int32, device=device)
         self.token = torch.zeros(B, self.N_pad, **i32)
         self.parent = torch.full((B, self.N_pad), -1, **i32)

@@ -212,7 +212,13 @@ struct LiteralLayout {
   ExpandLayout scan;
   int k_max;   // candidates per row the layout has room for: kLiteralScanK, or 1 for very wide rows
   size_t off_token, off_logit, off_prob, off_edge, off_max, off_lse, off_count, off_keys, total;
+  // Trees of at most 64 nodes: a row can never get more than N - 1 <= 63 children, so a per-row
+  // cap of N - 1 is no cap at all and the capped single-launch loop builds the uncapped tree.
+  // Its workspace and candidate arrays (for k = 63) lie over the same bytes as the layout above.
+  bool capped_loop_fits;
+  size_t c_workspace, c_token, c_logit, c_prob, c_edge, c_max, c_lse;
 };
+constexpr int kCappedLoopK = 63;
 
 int literal_layout(int B, int N_pad, int vocab, int dtype, LiteralLayout* V) {
   int rc = expand_layout(B, N_pad, vocab, 1, dtype, &V->scan);
@@ -235,6 +241,21 @@ int literal_layout(int B, int N_pad, int vocab, int dtype, LiteralLayout* V) {
   V->off_count = o; o += align_up(rows * sizeof(int32_t), 256);
   V->off_keys = o;  o += align_up(rows * kLiteralRowCap * sizeof(uint64_t), 256);
   V->total = o;
+  V->capped_loop_fits = false;
+  ExpandLayout C;
+  if (N_pad == 64 && expand_layout(B, N_pad, vocab, kCappedLoopK, dtype, &C) == TALON_OK) {
+    V->capped_loop_fits = true;
+    const size_t cc = rows * kCappedLoopK;
+    size_t c = C.total;
+    V->c_workspace = C.total;
+    V->c_token = c; c += align_up(cc * sizeof(int32_t), 256);
+    V->c_logit = c; c += align_up(cc * sizeof(float), 256);
+    V->c_prob = c;  c += align_up(cc * sizeof(float), 256);
+    V->c_edge = c;  c += align_up(cc * sizeof(double), 256);
+    V->c_max = c;   c += align_up(rows * sizeof(float), 256);
+    V->c_lse = c;   c += align_up(rows * sizeof(double), 256);
+    V->total = c > V->total ? c : V->total;
+  }
   return TALON_OK;
 }
 
@@ -536,6 +557,26 @@ int talon_expand_literal(const void* logits, int dtype, int64_t row_stride, int6
   if (init_layers < 0) { set_error("init_layers=%d must be >= 0", init_layers); return TALON_ERR_INVALID_ARG; }
   if (max_depth < 1) { set_error("max_depth=%d must be >= 1", max_depth); return TALON_ERR_INVALID_ARG; }
   if (layers < 1) { set_error("layers=%d must be >= 1", layers); return TALON_ERR_INVALID_ARG; }
+  if (V.capped_loop_fits && st->N >= 2) {
+    // At most 64 nodes: with a per-row cap of N - 1 (the whole row, if the vocabulary is smaller)
+    // no row is ever cut short, so the capped loop in its single launch builds the same tree
+    // (Alg. 2 with the pool as printed; a row's children enter in rank order, so a child
+    // beyond rank N - 1 could only be chosen after N - 1 siblings, which the budget forbids).
+    // The same argument bounds K_init.  The launch wants its counters zero.
+    const int k = st->N - 1 < vocab ? st->N - 1 : vocab;
+    const int most_layers = layers < st->N - 1 ? layers : st->N - 1;
+    ExpandLayout C;
+    rc = expand_layout(st->B, st->N_pad, vocab, k, dtype, &C);
+    if (rc) return rc;
+    hipStream_t cs = static_cast<hipStream_t>(stream);
+    rc = check_hip(launch_fill_zero(w, C.off_max, cs), "counter fill launch");
+    if (rc) return rc;
+    return run_fused_layers(true, nullptr, nullptr, logits, dtype, row_stride, seq_stride, row_mode, 0, most_layers, st, vocab, k,
+                            mu, K_init < k ? K_init : k, init_layers, max_depth, reinterpret_cast<int32_t*>(w + V.c_token),
+                            reinterpret_cast<float*>(w + V.c_logit), reinterpret_cast<float*>(w + V.c_prob),
+                            reinterpret_cast<double*>(w + V.c_edge), reinterpret_cast<float*>(w + V.c_max),
+                            reinterpret_cast<double*>(w + V.c_lse), workspace, V.c_workspace, stream);
+  }
   L = V.scan;   // offsets of the roomier layout; the scan strides its partial keys by k_scan
   const ExpandArgs ea = make_expand_args(logits, row_stride, seq_stride, row_mode, st, vocab, k_scan,
                                          reinterpret_cast<int32_t*>(w + V.off_token), reinterpret_cast<float*>(w + V.off_logit),

@@ -145,13 +145,15 @@ def run_gpu_expand(cfg: WorkloadConfig, pool_dev, init_layers=1, mu=None, K_init
 
 
 def run_gpu_literal(cfg: WorkloadConfig, pool: np.ndarray, K_init: int, init_layers: int = 1, mu=None,
-                    layer_by_layer: bool = False, row_mode_frontier: bool = False):
+                    layer_by_layer: bool = False, row_mode_frontier: bool = False, roomy_state: bool = False):
     """Alg. 2 with the uncapped pool through talon_expand_literal: talon_tree_init, the loop (one
-    call, or one call per layer), talon_build_tree_mask."""
+    call, or one call per layer), talon_build_tree_mask.  Trees of at most 64 nodes take the call's
+    shortcut through the capped loop; with roomy_state the tree state is padded to 128 nodes, which
+    keeps such a tree on the general path (results are cut back to cfg.N_pad columns)."""
     import torch
     import paper_2601_07353_amd as T
     pool_dev = to_device_logits(pool)
-    st = T.TreeState(cfg.B, cfg.N)
+    st = T.TreeState(cfg.B, cfg.N, N_pad=max(128, cfg.N_pad) if roomy_state else None)
     dt = T.TALON_DTYPE_F32 if cfg.logits_dtype == "f32" else T.TALON_DTYPE_BF16
     ws = T.make_literal_workspace(cfg.B, st.N_pad, cfg.V, dt)
     ws.fill_(0xA5)   # the call must not depend on what the workspace holds
@@ -166,12 +168,16 @@ def run_gpu_literal(cfg: WorkloadConfig, pool: np.ndarray, K_init: int, init_lay
     mask = torch.zeros(cfg.B, st.N_pad, st.N_pad // 64, dtype=torch.int64, device="cuda")
     T.talon_build_tree_mask(st, mask)
     torch.cuda.synchronize()
+    P, W = cfg.N_pad, cfg.N_pad // 64
+    words = mask.cpu().numpy().view(np.uint64)
+    assert not words[:, P:].any() and not words[:, :, W:].any()      # nothing beyond the tree's own padding
+    cut = lambda t: t.cpu().numpy()[:, :P]
     return {
-        "token": st.token.cpu().numpy(), "parent": st.parent.cpu().numpy(), "depth": st.depth.cpu().numpy(),
-        "prob": st.prob.cpu().numpy(), "logp": st.logp.cpu().numpy(), "n_nodes": st.n_nodes.cpu().numpy(),
+        "token": cut(st.token), "parent": cut(st.parent), "depth": cut(st.depth),
+        "prob": cut(st.prob), "logp": cut(st.logp), "n_nodes": st.n_nodes.cpu().numpy(),
         "status": st.status.cpu().numpy(), "depth_cur": st.depth_cur.cpu().numpy(),
         "frontier_begin": st.frontier_begin.cpu().numpy(), "frontier_count": st.frontier_count.cpu().numpy(),
-        "mask": mask.cpu().numpy().view(np.uint64),
+        "mask": np.ascontiguousarray(words[:, :P, :W]),
     }
 
 

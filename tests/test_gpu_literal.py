@@ -44,9 +44,10 @@ def _case(cfg, init_layers=1, layer_by_layer=False):
         t = H.oracle_tree(cfg, pool[b], roots[b], init_layers=init_layers, cap=cap)
         trees.append(t)
         masks.append(O.build_tree_mask(t.parent))
-    gpu = H.run_gpu_literal(cfg, pool, cfg.K, init_layers=init_layers, layer_by_layer=layer_by_layer)
-    H.compare_tree(cfg, gpu, trees, check_rows=False)
-    H.compare_mask(cfg, gpu, masks)
+    for roomy in ((False, True) if cfg.N_pad == 64 else (False,)):
+        gpu = H.run_gpu_literal(cfg, pool, cfg.K, init_layers=init_layers, layer_by_layer=layer_by_layer, roomy_state=roomy)
+        H.compare_tree(cfg, gpu, trees, check_rows=False)
+        H.compare_mask(cfg, gpu, masks)
     return trees
 
 
@@ -92,9 +93,11 @@ def _compare_pool(cfg, make_pool, need_margin=True, **kw):
     else:
         pool = make_pool(0)
         trees = [H.oracle_tree(cfg, pool[b], roots[b], cap=max(cfg.N - 1, 1), **kw) for b in range(cfg.B)]
-    gpu = H.run_gpu_literal(cfg, pool, cfg.K, **kw)
-    H.compare_tree(cfg, gpu, trees, check_rows=False)
-    H.compare_mask(cfg, gpu, [O.build_tree_mask(t.parent) for t in trees])
+    # trees of at most 64 nodes: once through the call's shortcut, once kept on the general path
+    for roomy in ((False, True) if cfg.N_pad == 64 else (False,)):
+        gpu = H.run_gpu_literal(cfg, pool, cfg.K, roomy_state=roomy, **kw)
+        H.compare_tree(cfg, gpu, trees, check_rows=False)
+        H.compare_mask(cfg, gpu, [O.build_tree_mask(t.parent) for t in trees])
     return gpu, trees
 
 
@@ -162,13 +165,14 @@ def test_nan_row_sets_status_and_stops_sequence():
     seeds = [H.find_admissible_seed(cfg, 0, cfg.seed, cap=cfg.N - 1)[0], cfg.seed]
     pool = H.build_pool(cfg, seeds)
     pool[1, 2, 1234] = np.nan
-    gpu = H.run_gpu_literal(cfg, pool, cfg.K)
-    assert int(gpu["status"][1]) & 4
-    assert int(gpu["n_nodes"][1]) == 1 + cfg.K          # stopped after the layer that read the bad row
-    assert int(gpu["frontier_count"][1]) == 0
     t = H.oracle_tree(cfg, pool[0], H.root_tokens(cfg)[0], cap=cfg.N - 1)
     assert t.margin > H.MARGIN_TOL
-    H.compare_tree(cfg, {k: v[:1] for k, v in gpu.items()}, [t], check_rows=False)
+    for roomy in (False, True):      # the shortcut for small trees, then the general path
+        gpu = H.run_gpu_literal(cfg, pool, cfg.K, roomy_state=roomy)
+        assert int(gpu["status"][1]) & 4
+        assert int(gpu["n_nodes"][1]) == 1 + cfg.K          # stopped after the layer that read the bad row
+        assert int(gpu["frontier_count"][1]) == 0
+        H.compare_tree(cfg, {k: v[:1] for k, v in gpu.items()}, [t], check_rows=False)
 
 
 def test_budget_of_one_and_two():
@@ -274,9 +278,10 @@ def test_random_small_configurations():
         if min(t.margin for t in trees) <= H.MARGIN_TOL:
             continue
         print("case", it, dtype, "V", V, "N", N, "K", K, "B", B, "init", init_layers, "mu", mu, rec, "Dmax", Dmax, flush=True)
-        gpu = H.run_gpu_literal(cfg, pool, K, init_layers=init_layers, layer_by_layer=bool(it % 2))
-        H.compare_tree(cfg, gpu, trees, check_rows=False)
-        H.compare_mask(cfg, gpu, [O.build_tree_mask(t.parent) for t in trees])
+        for roomy in ((False, True) if cfg.N_pad == 64 else (False,)):
+            gpu = H.run_gpu_literal(cfg, pool, K, init_layers=init_layers, layer_by_layer=bool(it % 2), roomy_state=roomy)
+            H.compare_tree(cfg, gpu, trees, check_rows=False)
+            H.compare_mask(cfg, gpu, [O.build_tree_mask(t.parent) for t in trees])
         ran += 1
     assert ran >= 24
 
