@@ -298,9 +298,9 @@ def run_workload(T, torch, np, H, cfg, args, steps, warmup, extras=True):
         dt_s = time.perf_counter() - t0
         check_slots(T, slots, used, "per-layer launches")
         per_layer = {"ms_per_step": dt_s * 1e3 / steps, "steps_per_s": steps / dt_s,
-                     "launches_per_step": 2 + 2 * depth_cap + (2 if nb > 256 else 1),
-                     "what": "talon_tree_init + %d x talon_expand_select_layer (a snapshot launch and the scan + "
-                             "selection launch each; layers after a tree is complete find no work) + "
+                     "launches_per_step": 2 + depth_cap + (2 if nb > 256 else 1),
+                     "what": "talon_tree_init + %d x talon_expand_select_layer (one launch each: the scan with the "
+                             "selections in its tail; layers after a tree is complete find no work) + "
                              "talon_build_tree_mask + talon_tree_attention, one HIP graph per step" % depth_cap}
 
     # ---- kernel timing region: the same K steps launched eagerly, with HIP events (on the

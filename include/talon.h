@@ -149,7 +149,12 @@ int talon_select_budget(const talon_tree_state* st, int32_t k, const int32_t* ca
  * talon_expand_layer with the budget selection of talon_select_budget run in its tail, per
  * sequence, by the workgroup that writes the last row of that sequence's frontier.  Same
  * results as the two calls in a row; arguments and errors as theirs.  `workspace` must have
- * been initialised by talon_expand_workspace_init.
+ * been initialised by talon_expand_workspace_init (once: every launch leaves it as it found it).
+ * The selections rewrite the tree state that every workgroup of the launch reads when it
+ * starts, so a selection holds back until all of them have read it; the other workgroups
+ * never wait, so this ends whatever else runs on the device (no need for the whole grid to be
+ * resident).  Should it not end within two seconds (a workspace that was never initialised),
+ * the sequence is marked TALON_STATUS_ABORTED and left as it was.
  */
 int talon_expand_select_layer(const void* logits, int dtype, int64_t row_stride, int64_t seq_stride,
                               int row_mode, int32_t layer, const talon_tree_state* st, int32_t vocab,

@@ -75,7 +75,7 @@ int expand_layout(int B, int N_pad, int vocab, int k, int dtype, ExpandLayout* L
   L->off_seq_ticket = align_up(rows * sizeof(int32_t), 256);
   L->off_desc = L->off_seq_ticket + align_up(static_cast<size_t>(B) * sizeof(int32_t), 256);
   L->off_exit = L->off_desc + align_up(static_cast<size_t>(N_pad) * B * sizeof(uint64_t), 256);
-  L->off_max = L->off_exit + align_up(static_cast<size_t>(kExitGroups + 1) * sizeof(uint32_t), 256);
+  L->off_max = L->off_exit + align_up(static_cast<size_t>(kExitWords) * sizeof(uint32_t), 256);
   L->off_sum = L->off_max + align_up(rows * chunks * sizeof(float), 256);
   L->off_keys = L->off_sum + align_up(rows * chunks * sizeof(double), 256);
   L->total = L->off_keys + align_up(rows * chunks * k * sizeof(uint64_t), 256);
@@ -406,14 +406,12 @@ int run_fused_layers(bool single_launch, const int32_t* root_token, uint64_t* ma
     if (mask) return check_hip(launch_mask(*st, mask, s), "mask launch");
     return TALON_OK;
   }
-  // The single launch starts fresh trees itself and leaves its counters clean; every other
-  // mode takes its first frontier from a snapshot of the public tree state made by a small
-  // launch of its own (the selections of a launch rewrite the public state while workgroups of
-  // the same launch may still be starting, and every workgroup must see the same item map).
-  const bool starts_trees = root_token != nullptr;   // talon_build_tree only: single launch, first layer 0
-  if (starts_trees) ea.root_token = root_token;
-  else if ((rc = check_hip(launch_fused_init(*st, ea, s), "fused init launch"))) return rc;
-  if (!single_launch) {   // one layer, one launch
+  ea.spin_ticks = spin_limit_ticks();
+  if (!single_launch) {
+    ea.spin_ticks = 200000000ull;   // two seconds of the 100 MHz clock: this wait always ends (see below), the bound is a safety net
+    // One layer, one launch.  Its workgroups read the frontier from the public tree state and
+    // its selections rewrite that state, so a selection waits until every workgroup of the
+    // grid has read it (two counters in the workspace, back at zero when the launch ends).
     ea.launch_idx = 0;
     if (g_profile.enabled && (rc = check_hip(profile_record(s), "profile event"))) return rc;
     rc = check_hip(launch_expand(ea, dtype, expand_grid(st, L.chunks, first_layer, k, K_init, init_layers), true, s), "expand launch");
@@ -421,6 +419,12 @@ int run_fused_layers(bool single_launch, const int32_t* root_token, uint64_t* ma
     if (g_profile.enabled && (rc = check_hip(profile_record(s), "profile event"))) return rc;
     return TALON_OK;
   }
+  // The single launch starts fresh trees itself and leaves its counters clean; when it continues
+  // trees, its first frontier comes from a snapshot of the public tree state made by a small
+  // launch of its own (layer i of the loop reads descriptor i).
+  const bool starts_trees = root_token != nullptr;   // talon_build_tree only: first layer 0
+  if (starts_trees) ea.root_token = root_token;
+  else if ((rc = check_hip(launch_fused_init(*st, ea, s), "fused init launch"))) return rc;
   // One launch walks all layers.  Its grid is the widest layer's, capped by what the device
   // holds at once (the kernel's workgroups wait for each other between layers).
   int grid = 1;
@@ -433,7 +437,6 @@ int run_fused_layers(bool single_launch, const int32_t* root_token, uint64_t* ma
   grid = grid < resident ? grid : resident;
   if (grid > 0xFFFF) grid = 0xFFFF;   // the exit ticket counts workgroups in 16 bits
   ea.layers = layers;
-  ea.spin_ticks = spin_limit_ticks();
   ea.tree_mask = mask;
   if (g_profile.enabled && (rc = check_hip(profile_record(s), "profile event"))) return rc;
   rc = check_hip(launch_expand_tree(ea, dtype, grid, s), "expand tree launch");

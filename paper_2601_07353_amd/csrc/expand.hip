@@ -351,10 +351,7 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
       if (TREE && a.root_token && launch_idx == 0) {   // fresh trees: the frontier is the root
         s_begin[tid] = 0;
         c = 1;
-      } else if constexpr (FUSED) {   // {begin, count} in one 8-byte load
-        // (also in a launch of one layer: its selections rewrite the public tree state while
-        // workgroups may still be starting, so the frontier is read from a snapshot taken by a
-        // small launch before this one; every workgroup must see the same item map)
+      } else if constexpr (TREE) {   // {begin, count} in one 8-byte load
         const unsigned long long* dp = a.desc + (launch_idx * a.B + tid);
         unsigned long long d2 = ld<TREE, unsigned long long>(dp);
         if constexpr (TREE) {
@@ -372,6 +369,10 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
         s_begin[tid] = static_cast<int>(static_cast<uint32_t>(d2));
         c = static_cast<int>(static_cast<uint32_t>(d2 >> 32) & 0x7FFFFFFFu);
       } else {  // the loads are issued together; the select below is register-only
+        // (In a launch of one layer with the selection in its tail, that selection rewrites this
+        // state while workgroups of the same launch may still be starting, and every workgroup
+        // must see the same item map: a workgroup says below that it has read the state, and a
+        // selection touches nothing before every workgroup of the grid has said so.)
         const uint32_t stat = a.status[tid];
         const int fc = a.frontier_count[tid];
         s_begin[tid] = a.frontier_begin[tid];
@@ -392,7 +393,12 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
     }
   }
   const int total_rows = s_prefix[a.B];
-  if (total_rows == 0) return 0;
+  if (total_rows == 0) return 0;   // (nothing will be selected in this launch: nobody waits for anybody)
+  if constexpr (FUSED && !TREE) {
+    // this workgroup has read the frontier (the loads fed the prefix sums that thread 0 has
+    // waited for at the barrier above)
+    if (tid == 0) __hip_atomic_fetch_add(a.exit_ticket + kStartedWord, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
   const int k = a.k;
 
   // ---- chunks per row from the width of this layer
@@ -767,7 +773,26 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
           if (tid == 0) s_last = row_bad ? 2 : 1;   // a one-row frontier: the workgroup that wrote the row selects right away
         }
         __syncthreads();
-        if (s_last) {
+        if constexpr (!TREE) {
+          if (s_last) {
+            // One layer per launch: the selection rewrites the state the item map is made from.
+            // Wait until every workgroup of the grid has read it (workgroups that have not
+            // started yet start as others leave; only the at most B selecting workgroups wait,
+            // so the others always get their turn).  The wait is bounded like the single
+            // launch's: a workgroup that gives up marks the sequence aborted and selects nothing.
+            if (tid == 0) {
+              const unsigned long long t0 = wall_clock64();
+              while (load_agent(a.exit_ticket + kStartedWord) != gridDim.x) {
+                if (wall_clock64() - t0 > a.spin_ticks) { s_last = 3; break; }
+                __builtin_amdgcn_s_sleep(2);
+              }
+            }
+            __syncthreads();
+          }
+        }
+        if (s_last == 3) {
+          if (tid == 0) atomicOr(&a.status[b], static_cast<uint32_t>(TALON_STATUS_ABORTED));
+        } else if (s_last) {
           TL_ANY(launch_idx, 2);
           // A launch that started the tree itself knows the sequence's status (nothing but a
           // row that cannot be normalised can have touched it), its size and its layer
@@ -794,6 +819,21 @@ __device__ __forceinline__ int expand_body(const ExpandArgs& a, const int launch
               st_<true, unsigned long long>(a.desc + ((launch_idx + 1) * a.B + b), next | kDescReady);
             TL_ANY(launch_idx, 3);
           }   // (a launch of one layer leaves no descriptor: the next call starts from the public state)
+        }
+        if constexpr (!TREE) {
+          if (s_last) {
+            // the last selection of the launch puts the two counters back to zero (every
+            // workgroup has started by now, so nobody counts after this)
+            if (tid == 0) {
+              int active = 0;
+              for (int q = 0; q < a.B; ++q) active += (s_prefix[q + 1] > s_prefix[q]) ? 1 : 0;
+              const uint32_t done_before = __hip_atomic_fetch_add(a.exit_ticket + kSelectedWord, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              if (static_cast<int>(done_before) + 1 == active) {
+                store_agent(a.exit_ticket + kStartedWord, 0u);
+                store_agent(a.exit_ticket + kSelectedWord, 0u);
+              }
+            }
+          }
         }
       }
     }
@@ -903,7 +943,7 @@ __global__ __launch_bounds__(kThreads, 3) void expand_tree_kernel(ExpandArgs a) 
       atomicOr(&a.status[i], TALON_STATUS_ABORTED);
     }
   }
-  for (int i = t; i <= kExitGroups; i += kThreads) store_agent(a.exit_ticket + i, 0u);
+  for (int i = t; i < kExitWords; i += kThreads) store_agent(a.exit_ticket + i, 0u);
 }
 
 __global__ __launch_bounds__(kThreads) void fill_zero_kernel(uint32_t* p, size_t n) {

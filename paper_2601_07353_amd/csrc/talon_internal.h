@@ -34,6 +34,11 @@ struct SelectArgs {
 // Measured over 8 to 255 groups on grids of 300 to 700 workgroups: 128 is the fastest; fewer
 // groups lengthen the first level, more lengthen the second.
 constexpr int kExitGroups = 128;
+// Words of the exit-ticket array: the groups' count, one count per group, and two counters of the
+// launches of one layer (workgroups that have read the frontier; selections that have finished).
+constexpr int kStartedWord = kExitGroups + 1;
+constexpr int kSelectedWord = kExitGroups + 2;
+constexpr int kExitWords = kExitGroups + 3;
 constexpr unsigned long long kDescReady = 1ull << 63;
 
 struct ExpandArgs {
@@ -60,9 +65,11 @@ struct ExpandArgs {
   // row of that sequence's frontier has been written): selection parameters, the index of
   // this launch in the loop, per-sequence row tickets and per-layer frontier descriptors
   // [N_pad][B], one 8-byte word each: begin in the low half, count and kDescReady in the
-  // high half.  Layer i of a call reads desc[i] (desc[0] is copied from the public tree
-  // state, or known when the launch starts the trees itself) and its selections write
-  // desc[i+1], so a workgroup that starts late still sees the frontier of its own layer.
+  // high half.  In the single launch, layer i reads desc[i] (desc[0] is copied from the public
+  // tree state, or known when the launch starts the trees itself) and its selections write
+  // desc[i+1], so a workgroup that is late still sees the frontier of its own layer.  A launch
+  // of one layer reads the public tree state instead and holds its selections back until every
+  // workgroup has done so (kStartedWord).
   SelectArgs sel;
   int launch_idx;
   int32_t* seq_ticket;   // [B]
@@ -77,7 +84,7 @@ struct ExpandArgs {
   // root row of every sequence, and the workgroup that writes that row initialises the
   // sequence's state first.
   int layers;
-  uint32_t* exit_ticket; // [kExitGroups + 1] workgroups that have left, counted per group, then the groups
+  uint32_t* exit_ticket; // [kExitWords] workgroups that have left, counted per group, then the groups; see kStartedWord
   unsigned long long spin_ticks;
   uint64_t* tree_mask;   // optional: ancestor masks written at the end of the single launch
   const int32_t* root_token;   // optional [B]

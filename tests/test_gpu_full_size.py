@@ -116,9 +116,9 @@ def test_c5_stress_full_size_all_trees(c5_run):
 
 def test_c5_stress_per_layer_launches(c5_run):
     """The same sixteen trees through one fused launch per layer (talon_expand_select_layer).  At
-    this size a launch has more workgroups than the device starts at once and its selections
-    finish while others are still starting: every workgroup must still see the frontier the
-    launch began with (it reads a snapshot, not the public state the selections rewrite)."""
+    this size a launch has more workgroups than the device starts at once: every workgroup must
+    still see the frontier the launch began with, so a selection may rewrite the tree state only
+    when every workgroup of the grid has read it."""
     cfg, _, trees, masks, _, pool = c5_run
     gpu = H.run_gpu_step(cfg, pool=pool, with_attention=False, layerwise="fused")
     H.compare_tree(cfg, gpu, trees, check_rows=False)
