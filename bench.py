@@ -41,6 +41,9 @@ def parse_args():
                     help="only run plain device copies of 1 GiB (reads 1 GiB, writes 1 GiB each): the "
                          "reference that scales the FETCH_SIZE / WRITE_SIZE counters of a --pmc run")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget for the oracle timing sample")
+    ap.add_argument("--probes", action="store_true",
+                    help="cycles per instruction of the attention step's instruction mixes (one and two wavefronts "
+                         "per SIMD) and the rate of direct-to-LDS tile loads per compute unit")
     ap.add_argument("--attainable", action="store_true",
                     help="only run the library's two probes: a streaming read of 1 GiB and 512 MiB buffers (cold) "
                          "and a register-resident bf16 MFMA loop; prints the rates they reach")
@@ -121,8 +124,8 @@ def main():
 
     from workloads import CONFIGS
     cfg = CONFIGS[args.config.lower()]
-    plain = not (args.copy_calibration or args.attainable or args.zipf_grid or args.scan_grid or args.sweep
-                 or args.literal)
+    plain = not (args.copy_calibration or args.attainable or args.probes or args.zipf_grid or args.scan_grid
+                 or args.sweep or args.literal)
     # The oracle's timing runs first, in forked worker processes, before this process touches
     # the GPU (a process that has initialised the GPU must not be forked into workers).
     cpu = None
@@ -147,6 +150,9 @@ def main():
         print(json.dumps({"copy_calibration": {"bytes_read": 1 << 30, "bytes_written": 1 << 30, "copies": 10}}))
         return
 
+    if args.probes:
+        print(json.dumps({"probes": probes(T, torch)}))
+        return
     if args.attainable:
         print(json.dumps({"attainable": attainable(T, torch)}))
         return
@@ -646,6 +652,38 @@ def zipf_grid(T, torch, np, H, K=10, N=60, warm=20, runs=100):
                 res[label] = float(np.mean(us))
                 res[label.replace("_us", "_new_nodes")] = int(st.n_nodes[0].item()) - 1 - K
             out.append(res)
+    return out
+
+
+def probes(T, torch):
+    """Cycle counts (shader clock) of the two attention-step probes of the library."""
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    out = {"issue": [], "tile_loads": []}
+    mixes = [(0, "32 exp2", 32), (1, "32 fma", 32), (2, "16 mfma 32x32x16 bf16, 4 accumulators", 16),
+             (3, "16 mfma 32x32x16 bf16, 1 accumulator", 16), (4, "16 mfma + 32 (fma, exp2)", 16)]
+    iters = 2000
+    for waves in (4, 8):
+        for mode, what, per_round in mixes:
+            cyc = torch.zeros(8, dtype=torch.int64, device="cuda")
+            T.talon_probe_issue(mode, waves, iters, cyc, sink)
+            torch.cuda.synchronize()
+            c = cyc.cpu().numpy()[:waves].astype(float) / iters
+            out["issue"].append({"mix": what, "waves_per_simd": waves // 4, "cycles_per_round_first_wave": float(c[0]),
+                                 "cycles_per_round_slowest_wave": float(c.max()),
+                                 "cycles_per_instruction_slowest_wave": float(c.max()) / per_round})
+    window = torch.zeros(16 << 20, dtype=torch.uint8, device="cuda")
+    for waves in (4, 8):
+        for loads in (4, 8):
+            for with_mfma in (False, True):
+                cyc = torch.zeros(2048, dtype=torch.int64, device="cuda")
+                T.talon_probe_tile_loads(window, loads, with_mfma, waves, iters, cyc, sink)
+                torch.cuda.synchronize()
+                c = cyc.cpu().numpy().reshape(256, 8)[:, :waves].astype(float) / iters
+                kb = waves * loads            # KB per compute unit and round
+                out["tile_loads"].append({"waves": waves, "loads_per_wave": loads, "with_16_mfma": with_mfma,
+                                          "KB_per_cu_round": kb, "cycles_per_round_mean": float(c.mean()),
+                                          "cycles_per_round_slowest_wave": float(c.max()),
+                                          "bytes_per_cycle_per_cu": kb * 1024.0 / float(c.mean())})
     return out
 
 

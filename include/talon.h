@@ -333,6 +333,25 @@ int talon_probe_read(const void* buf, size_t bytes, void* sink, void* stream);
 int talon_probe_mfma(int32_t workgroups, int32_t iters, void* sink, double* flops, void* stream);
 
 /*
+ * Two probes of what a tree-attention step is made of, in cycles of the shader clock (no
+ * counterpart in the paper; they back the analysis of that kernel).
+ * talon_probe_issue: one workgroup of `waves` (4 or 8: one or two per SIMD) wavefronts; each
+ * runs `iters` rounds of instruction mix `mode` (0: 32 independent exp2; 1: 32 independent
+ * fma; 2: 16 v_mfma_f32_32x32x16_bf16 over four accumulators; 3: the same over one; 4: 16
+ * matrix instructions with 32 (fma, exp2) pairs between them) and stores its cycle count in
+ * cycles[wavefront] (device, 8 words).
+ * talon_probe_tile_loads: 256 workgroups of `waves` wavefronts; per round every wavefront issues
+ * `loads` (4 or 8) direct-to-LDS loads of 1 KB from its workgroup's 64 KB of `window` (device,
+ * at least 16 MiB, 16-byte aligned; the windows stay in the L2), with sixteen matrix
+ * instructions around them if `with_mfma`, and waits for them; cycles[workgroup * 8 +
+ * wavefront] (device, 2048 words) gets the cycles of all `iters` rounds.
+ * `sink` as above.  Errors: INVALID_ARG.
+ */
+int talon_probe_issue(int32_t mode, int32_t waves, int32_t iters, uint64_t* cycles, void* sink, void* stream);
+int talon_probe_tile_loads(const void* window, size_t window_bytes, int32_t loads, int32_t with_mfma,
+                           int32_t waves, int32_t iters, uint64_t* cycles, void* sink, void* stream);
+
+/*
  * Tree attention mask (Fig. 5(b); App. B): bit j of row i is set iff node j is node i or
  * one of its ancestors, the root included.
  *   mask [B][N_pad][N_pad/64] uint64, bit j of row i = word j/64, bit j%64.

@@ -35,7 +35,7 @@ TALON_ROWS_BY_FRONTIER = 1
 EXPORTS = [
     "talon_last_error_string", "talon_tree_init", "talon_expand_workspace_bytes",
     "talon_expand_workspace_init", "talon_expand_layer", "talon_select_budget", "talon_expand_select_layer",
-    "talon_expand_tree", "talon_build_tree", "talon_build_tree_checked", "talon_set_spin_limit_us", "talon_profile_scan_launches", "talon_profile_read", "talon_probe_read", "talon_probe_mfma", "talon_verify_workspace_bytes", "talon_target_argmax",
+    "talon_expand_tree", "talon_build_tree", "talon_build_tree_checked", "talon_set_spin_limit_us", "talon_profile_scan_launches", "talon_profile_read", "talon_probe_read", "talon_probe_mfma", "talon_probe_issue", "talon_probe_tile_loads", "talon_verify_workspace_bytes", "talon_target_argmax",
     "talon_literal_workspace_bytes", "talon_expand_literal",
     "talon_greedy_accept", "talon_compact_kv", "talon_prune_tree",
     "talon_build_tree_mask", "talon_tree_attention_workspace_bytes", "talon_tree_attention",
@@ -103,6 +103,8 @@ def load_library() -> ctypes.CDLL:
     lib.talon_prune_tree.argtypes = [POINTER(_CTreeState), c_int32, P, P]
     lib.talon_probe_read.argtypes = [P, c_size_t, P, P]
     lib.talon_probe_mfma.argtypes = [c_int32, c_int32, P, POINTER(c_double), P]
+    lib.talon_probe_issue.argtypes = [c_int32, c_int32, c_int32, P, P, P]
+    lib.talon_probe_tile_loads.argtypes = [P, c_size_t, c_int32, c_int32, c_int32, c_int32, P, P, P]
     lib.talon_build_tree_mask.argtypes = [POINTER(_CTreeState), P, P]
     lib.talon_tree_attention_workspace_bytes.restype = c_size_t
     lib.talon_tree_attention_workspace_bytes.argtypes = [c_int32] * 6
@@ -291,6 +293,19 @@ def talon_probe_mfma(workgroups: int, iters: int, sink: torch.Tensor, stream=Non
     fl = c_double(0.0)
     _check(load_library().talon_probe_mfma(workgroups, iters, _ptr(sink), ctypes.byref(fl), _stream(stream)))
     return fl.value
+
+
+def talon_probe_issue(mode: int, waves: int, iters: int, cycles: torch.Tensor, sink: torch.Tensor, stream=None):
+    """cycles: 8 int64 on the device, one per wavefront."""
+    _check(load_library().talon_probe_issue(mode, waves, iters, _ptr(cycles), _ptr(sink), _stream(stream)))
+
+
+def talon_probe_tile_loads(window: torch.Tensor, loads: int, with_mfma: bool, waves: int, iters: int,
+                           cycles: torch.Tensor, sink: torch.Tensor, stream=None):
+    """window: at least 16 MiB on the device; cycles: 2048 int64 on the device, [workgroup][wavefront]."""
+    _check(load_library().talon_probe_tile_loads(_ptr(window), window.numel() * window.element_size(), loads,
+                                                 1 if with_mfma else 0, waves, iters, _ptr(cycles), _ptr(sink),
+                                                 _stream(stream)))
 
 
 def talon_build_tree_mask(st: TreeState, mask: torch.Tensor, stream=None):

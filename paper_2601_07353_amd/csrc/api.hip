@@ -749,6 +749,28 @@ int talon_probe_mfma(int32_t workgroups, int32_t iters, void* sink, double* flop
   return check_hip(launch_mfma_probe(workgroups, iters, sink, static_cast<hipStream_t>(stream)), "mfma probe launch");
 }
 
+int talon_probe_issue(int32_t mode, int32_t waves, int32_t iters, uint64_t* cycles, void* sink, void* stream) {
+  if (!cycles || !sink || mode < 0 || mode > 4 || (waves != 4 && waves != 8) || iters < 1 ||
+      (reinterpret_cast<uintptr_t>(cycles) & 7u)) {
+    set_error("talon_probe_issue: mode in [0, 4], waves 4 or 8, iters >= 1, 8 device words for the cycles and a 4-byte device sink are required");
+    return TALON_ERR_INVALID_ARG;
+  }
+  return check_hip(launch_issue_probe(mode, waves, iters, cycles, sink, static_cast<hipStream_t>(stream)), "issue probe launch");
+}
+
+int talon_probe_tile_loads(const void* window, size_t window_bytes, int32_t loads, int32_t with_mfma, int32_t waves,
+                           int32_t iters, uint64_t* cycles, void* sink, void* stream) {
+  if (!window || !cycles || !sink || (loads != 4 && loads != 8) || (waves != 4 && waves != 8) || iters < 1 ||
+      window_bytes < (static_cast<size_t>(256) << 16) || (reinterpret_cast<uintptr_t>(window) & 15u) ||
+      (reinterpret_cast<uintptr_t>(cycles) & 7u)) {
+    set_error("talon_probe_tile_loads: a 16-byte aligned window of at least 16 MiB, loads 4 or 8, waves 4 or 8, iters >= 1, "
+              "2048 device words for the cycles and a 4-byte device sink are required");
+    return TALON_ERR_INVALID_ARG;
+  }
+  return check_hip(launch_tile_load_probe(loads, with_mfma != 0, waves, iters, window, cycles, sink, static_cast<hipStream_t>(stream)),
+                   "tile load probe launch");
+}
+
 int talon_build_tree_mask(const talon_tree_state* st, uint64_t* mask, void* stream) {
   int rc = check_state(st);
   if (rc) return rc;

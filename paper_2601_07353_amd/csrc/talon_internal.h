@@ -152,6 +152,8 @@ hipError_t launch_compact_kv(const uint16_t* k_tree, const uint16_t* v_tree, con
                              hipStream_t s);
 hipError_t launch_read_probe(const void* buf, size_t bytes, void* sink, hipStream_t s);
 hipError_t launch_mfma_probe(int workgroups, int iters, void* sink, hipStream_t s);
+hipError_t launch_issue_probe(int mode, int waves, int iters, void* cycles, void* sink, hipStream_t s);
+hipError_t launch_tile_load_probe(int loads, bool with_mfma, int waves, int iters, const void* window, void* cycles, void* sink, hipStream_t s);
 hipError_t launch_fused_init(const talon_tree_state& st, const ExpandArgs& a, hipStream_t s);
 hipError_t launch_expand_tree(const ExpandArgs& a, int dtype, int grid, hipStream_t s);
 int expand_tree_max_grid(int dtype);
