@@ -173,8 +173,16 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void tree_attention_kerne
   // key instead: its score is masked to -inf below, so its probability is exactly 0 and the
   // (finite) value row it brought along adds nothing.
   constexpr int ROWS_PER_LOAD = 64 / CPR;                 // key rows per wavefront load
-  constexpr int LOADS = kKeyTile / ROWS_PER_LOAD / NW;    // loads per wavefront, tile and tensor
-  static_assert(LOADS >= 1, "every wavefront loads at least one group of key rows");
+  // With eight wavefronts only the last four issue tile loads (twice as many each).  A compute
+  // unit's address path takes a step's 32 KB in about 512 cycles whoever issues them, and a
+  // wavefront waits at its loads for its turn: with half of the wavefronts loading, the other
+  // half never waits there (measured: 16384 keys 2.6 % faster; two or one loading wavefronts
+  // are slower again, and which half loads makes no difference).
+  constexpr int LW = NW == 8 ? NW / 2 : NW;   // wavefronts that issue tile loads
+  constexpr int LOADS = kKeyTile / ROWS_PER_LOAD / LW;    // loads per loading wavefront, tile and tensor
+  static_assert(LOADS >= 1, "every loading wavefront loads at least one group of key rows");
+  const int lwave = wave - (NW - LW);                     // the loaders are the last LW wavefronts
+  const bool loader = lwave >= 0 && lwave < LW;           // wave-uniform
   // LDS: two K stages then two V stages.
   unsigned long long* s_mask = reinterpret_cast<unsigned long long*>(smem + 4 * SM::T_ELEMS);
   auto stage_k = [&](int st_) { return smem + st_ * SM::T_ELEMS; };
@@ -187,7 +195,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void tree_attention_kerne
     const uint16_t* base = is_prefix ? pre_base : tree_base;
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
-      const int row0_ = (wave * LOADS + i) * ROWS_PER_LOAD;
+      const int row0_ = (lwave * LOADS + i) * ROWS_PER_LOAD;
       const int row = row0_ + lane / CPR;
       const int cslot = lane % CPR;
       int key = key0 + row;
@@ -201,31 +209,56 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void tree_attention_kerne
   // the address is a per-lane base plus tile and load offsets (no 64-bit multiplies).
   const int lrow = lane / CPR;                       // key row of this lane inside one load
   const size_t tile_step = static_cast<size_t>(kKeyTile) * a.kv_stride_t;       // elements between tiles
-  uint32_t koff[LOADS], voff[LOADS];                 // byte offset of this lane's chunk inside a tile, per load
+  // Byte offset of this lane's chunk inside a tile, per load.  Where a loading wavefront has
+  // four loads per tensor (half of the wavefronts load), there are no registers to spare for
+  // eight offsets: the first row of a load goes into the wave-uniform base address and the lane
+  // offset is put together at the load.  The first row u of a load is a multiple of
+  // ROWS_PER_LOAD and lrow is below it, so kswz(u + lrow) = kswz(u) ^ kswz(lrow) and
+  // vswz(u + lrow) = vswz(lrow).
+  constexpr bool kOffsetsAtLoad = LW != NW;
+  uint32_t koff[kOffsetsAtLoad ? 1 : LOADS], voff[kOffsetsAtLoad ? 1 : LOADS];
+  uint32_t lane_row_bytes = 0, kchunk_bytes = 0;
+  if constexpr (kOffsetsAtLoad) {
+    lane_row_bytes = static_cast<uint32_t>(lrow) * static_cast<uint32_t>(a.kv_stride_t) * 2u;
+    kchunk_bytes = static_cast<uint32_t>(((lane % CPR) ^ SM::kswz(lrow)) * 16);
+    koff[0] = 0;
+    voff[0] = lane_row_bytes + static_cast<uint32_t>(((lane % CPR) ^ SM::vswz(lrow)) * 16);
+  } else {
 #pragma unroll
-  for (int i = 0; i < LOADS; ++i) {
-    const int row = (wave * LOADS + i) * ROWS_PER_LOAD + lrow;
-    const uint32_t row_bytes = static_cast<uint32_t>(row) * static_cast<uint32_t>(a.kv_stride_t) * 2u;
-    koff[i] = row_bytes + static_cast<uint32_t>(((lane % CPR) ^ SM::kswz(row)) * 16);
-    voff[i] = row_bytes + static_cast<uint32_t>(((lane % CPR) ^ SM::vswz(row)) * 16);
+    for (int i = 0; i < LOADS; ++i) {
+      const int row = (lwave * LOADS + i) * ROWS_PER_LOAD + lrow;
+      const uint32_t row_bytes = static_cast<uint32_t>(row) * static_cast<uint32_t>(a.kv_stride_t) * 2u;
+      koff[i] = row_bytes + static_cast<uint32_t>(((lane % CPR) ^ SM::kswz(row)) * 16);
+      voff[i] = row_bytes + static_cast<uint32_t>(((lane % CPR) ^ SM::vswz(row)) * 16);
+    }
   }
   auto load_full_prefix = [&](int t, int kst, int vst, bool want_k, bool want_v) {
     const uint16_t* kt_ = kp_base + static_cast<size_t>(t) * tile_step;   // wave-uniform
     const uint16_t* vt_ = vp_base + static_cast<size_t>(t) * tile_step;
-    uint16_t* sK = stage_k(kst) + wave * LOADS * ROWS_PER_LOAD * DH;
-    uint16_t* sV = stage_v(vst) + wave * LOADS * ROWS_PER_LOAD * DH;
+    uint16_t* sK = stage_k(kst) + lwave * LOADS * ROWS_PER_LOAD * DH;
+    uint16_t* sV = stage_v(vst) + lwave * LOADS * ROWS_PER_LOAD * DH;
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
-      if (want_k) global_to_lds_16(kt_, koff[i], sK + i * ROWS_PER_LOAD * DH);
-      if (want_v) global_to_lds_16(vt_, voff[i], sV + i * ROWS_PER_LOAD * DH);
+      if constexpr (kOffsetsAtLoad) {
+        const int u = (lwave * LOADS + i) * ROWS_PER_LOAD;                            // wave-uniform
+        const size_t row_elems = static_cast<size_t>(u) * a.kv_stride_t;
+        if (want_k) global_to_lds_16(kt_ + row_elems, lane_row_bytes + (kchunk_bytes ^ static_cast<uint32_t>(SM::kswz(u) * 16)),
+                                     sK + i * ROWS_PER_LOAD * DH);
+        if (want_v) global_to_lds_16(vt_ + row_elems, voff[0], sV + i * ROWS_PER_LOAD * DH);
+      } else {
+        if (want_k) global_to_lds_16(kt_, koff[i], sK + i * ROWS_PER_LOAD * DH);
+        if (want_v) global_to_lds_16(vt_, voff[i], sV + i * ROWS_PER_LOAD * DH);
+      }
     }
   };
   auto is_full_prefix = [&](int t) { return t < nPT && (t + 1) * kKeyTile <= L; };
   auto load_k = [&](int t, int st_) {
+    if (!loader) return;
     if (is_full_prefix(t)) load_full_prefix(t, st_, 0, true, false);
     else load_tensor(t, kp_base, kt_base, stage_k(st_), true);
   };
   auto load_v = [&](int t, int st_) {
+    if (!loader) return;
     if (is_full_prefix(t)) load_full_prefix(t, 0, st_, false, true);
     else load_tensor(t, vp_base, vt_base, stage_v(st_), false);
   };
