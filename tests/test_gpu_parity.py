@@ -248,6 +248,86 @@ def test_launch_forms_share_one_workspace():
         same(snapshot(), want[which])
 
 
+def test_captured_steps_replay_like_eager_ones():
+    """A serving loop captures its step once and replays it.  Two graphs over ONE workspace and tree
+    state (one launch per layer + mask; the whole tree in one launch) are replayed in turns, with
+    the logits buffer they read rewritten, eager launches of the other forms and synchronisations
+    between the replays: every replay must give the tree and mask the eager launch gives, so the
+    counters the launches share (row tickets, the two per-layer counts, exit tickets) have to be
+    back at zero after every replay, not only after the first."""
+    import torch
+    import paper_2601_07353_amd as T
+    cfg = small(name="replay", V=40000, logits_dtype="bf16", K=8, N=100, Dmax=12, B=3,
+                recipe=(("gauss", 6.0, 8.0), ("gauss", 0.5, 1.0), ("gauss", 2.0, 8.0)))
+    seeds = [admissible_seeds(dataclasses.replace(cfg, seed=cfg.seed + 31 * i)) for i in range(3)]
+    pools = [H.to_device_logits(H.build_pool(cfg, s)) for s in seeds]
+    live = torch.empty_like(pools[0])          # the buffer the captured launches read
+    roots = torch.from_numpy(H.root_tokens(cfg)).cuda()
+    st = T.TreeState(cfg.B, cfg.N)
+    cand = T.Candidates(cfg.B, st.N_pad, cfg.K)
+    ws = T.make_expand_workspace(cfg.B, st.N_pad, cfg.V, cfg.K, T.TALON_DTYPE_BF16)
+    mask = torch.zeros((cfg.B, st.N_pad, st.N_pad // 64), dtype=torch.int64, device="cuda")
+
+    def snapshot():
+        torch.cuda.synchronize()
+        n = [int(x) for x in st.n_nodes.cpu()]
+        return {"n": n, "status": st.status.cpu().numpy().copy(),
+                "token": [st.token[b, :k].cpu().numpy().copy() for b, k in enumerate(n)],
+                "parent": [st.parent[b, :k].cpu().numpy().copy() for b, k in enumerate(n)],
+                "mask": [mask[b, :k].cpu().numpy().copy() for b, k in enumerate(n)]}
+
+    def same(a, b):
+        assert a["n"] == b["n"]
+        np.testing.assert_array_equal(a["status"], b["status"])
+        for key in ("token", "parent", "mask"):
+            for x, y in zip(a[key], b[key]):
+                np.testing.assert_array_equal(x, y)
+
+    def per_layer(p):
+        T.talon_tree_init(st, roots)
+        for d in range(cfg.Dmax):
+            T.talon_expand_select_layer(p, st, cfg.K, cfg.mu, cfg.K, 1, cfg.Dmax, cand, ws, layer=d)
+        T.talon_build_tree_mask(st, mask)
+
+    def whole(p):
+        T.talon_build_tree(roots, p, st, cfg.K, cfg.mu, cfg.K, 1, cfg.Dmax, cand, ws, mask=mask)
+
+    want = []
+    for p in pools:
+        per_layer(p)
+        want.append(snapshot())
+    assert want[0]["token"][0].tolist() != want[1]["token"][0].tolist()
+
+    graphs = {}
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):             # one eager pass on the capture stream first
+        live.copy_(pools[0])
+        per_layer(live)
+        whole(live)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for name, form in (("per_layer", per_layer), ("whole", whole)):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            form(live)
+        graphs[name] = g
+
+    order = [("per_layer", 1), ("per_layer", 2), ("whole", 0), ("per_layer", 0), ("whole", 1), ("per_layer", 1),
+             ("per_layer", 2), ("whole", 2), ("per_layer", 0)]
+    for i, (name, which) in enumerate(order):
+        live.copy_(pools[which])
+        mask.fill_(-1)
+        graphs[name].replay()
+        same(snapshot(), want[which])
+        other = (which + 1) % 3               # eager work of the other form on the same workspace in between
+        (whole if name == "per_layer" else per_layer)(pools[other])
+        same(snapshot(), want[other])
+        if i % 3 == 2:
+            torch.cuda.synchronize()
+            (live.float().sum() + st.logp.sum()).item()   # library work of the program's own between replays
+
+
 @pytest.mark.parametrize("fused", [True, False])
 def test_dense_frontier_batches_with_padded_rows(fused):
     """The layout a serving loop has: after every layer the draft model's logits exist for the
