@@ -566,33 +566,51 @@ __global__ __launch_bounds__(kThreads) void tree_attention_combine_kernel(AttnAr
   const int slab = t / (2 * RPW);        // 8 head-dim values: c = 2 * slab + h
   const int c = 2 * slab + h;
   const int rho = blockIdx.x * RPW + r;
-  if (blockIdx.x * RPW >= rows) return;  // the whole workgroup is past the end
-  const bool valid = rho < rows;
-  int L = a.prefix_len[b];
-  L = L < 0 ? 0 : (L > a.max_prefix_len ? a.max_prefix_len : L);
-  const int T = (L + kKeyTile - 1) / kKeyTile + (a.n_nodes[b] + kKeyTile - 1) / kKeyTile;
-  int ns = (T + a.tiles_per_split - 1) / a.tiles_per_split;  // splits that held at least one tile
-  ns = ns < a.splits ? ns : a.splits;
+  // Every split of a row tile that has rows stores a partial result (one without key tiles stores
+  // a maximum of -inf), and the partial arrays have room for every row the grid covers, so no
+  // address here depends on the sequence's lengths: all loads of up to eight splits are issued
+  // together with the load of the node count, one memory round trip, and the running maximum is
+  // carried across blocks of eight.  Rows past the end read what nobody wrote and are dropped.
   const size_t block0 = static_cast<size_t>(bg) * a.splits * a.rows_pad;
-  const size_t base = block0 + (valid ? rho : 0);
-  // branch-free, so that the loads of all splits are in flight together
+  const size_t base = block0 + rho;
+  const size_t in_block = (static_cast<size_t>(slab) * a.rows_pad + rho) * 8 + 4 * h;
   float M = kNegInfF;
-  for (int s = 0; s < ns; ++s) M = fmaxf(M, a.part_m[base + static_cast<size_t>(s) * a.rows_pad]);
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   float den = 0.f;
-  const size_t in_block = (static_cast<size_t>(slab) * a.rows_pad + (valid ? rho : 0)) * 8 + 4 * h;
-#pragma unroll 4
-  for (int s = 0; s < ns; ++s) {
-    const size_t pr = base + static_cast<size_t>(s) * a.rows_pad;
-    const float ms = a.part_m[pr];
-    const float ls = a.part_l[pr];
-    const bf16x4 v = *reinterpret_cast<const bf16x4*>(
-        a.part_o + (block0 + static_cast<size_t>(s) * a.rows_pad) * DH + in_block);
-    const float w = ms == kNegInfF ? 0.f : __builtin_amdgcn_exp2f(ms - M) * ls;   // an empty split: weight 0
-    den += w;
-    acc.x += w * static_cast<float>(v[0]); acc.y += w * static_cast<float>(v[1]);
-    acc.z += w * static_cast<float>(v[2]); acc.w += w * static_cast<float>(v[3]);
+  for (int s0 = 0; s0 < a.splits; s0 += 8) {
+    float ms[8], ls[8];
+    bf16x4 vs[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int s = s0 + u;
+      ms[u] = kNegInfF;
+      ls[u] = 0.f;
+      vs[u] = bf16x4{0, 0, 0, 0};
+      if (s < a.splits) {   // uniform
+        const size_t pr = base + static_cast<size_t>(s) * a.rows_pad;
+        ms[u] = a.part_m[pr];
+        ls[u] = a.part_l[pr];
+        vs[u] = *reinterpret_cast<const bf16x4*>(a.part_o + (block0 + static_cast<size_t>(s) * a.rows_pad) * DH + in_block);
+      }
+    }
+    float Mb = M;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) Mb = fmaxf(Mb, ms[u]);
+    if (Mb == kNegInfF) continue;              // nothing but empty splits so far
+    const float keep = __builtin_amdgcn_exp2f(M - Mb);   // 0 on the first block that holds anything
+    M = Mb;
+    den *= keep;
+    acc.x *= keep; acc.y *= keep; acc.z *= keep; acc.w *= keep;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const float w = ms[u] == kNegInfF ? 0.f : __builtin_amdgcn_exp2f(ms[u] - M) * ls[u];   // an empty split: weight 0
+      den += w;
+      acc.x += w * static_cast<float>(vs[u][0]); acc.y += w * static_cast<float>(vs[u][1]);
+      acc.z += w * static_cast<float>(vs[u][2]); acc.w += w * static_cast<float>(vs[u][3]);
+    }
   }
+  if (blockIdx.x * RPW >= rows) return;  // the whole workgroup is past the end
+  const bool valid = rho < rows;
   const float inv = 1.f / den;
   bf16x4 v;
   v[0] = static_cast<__bf16>(acc.x * inv);
