@@ -502,16 +502,33 @@ __global__ __launch_bounds__(kThreads) void literal_select_kernel(LiteralArgs a)
   // flat); otherwise every pass reads it from memory, row by row.
   const bool dense = total <= kPoolLds;
   if (dense) {
-    for (int j0 = 0; j0 < F; j0 += 4) {
+    // One pool position per thread and round, four rounds in flight: the row of a position is
+    // the last one that starts at or before it (rows without survivors start where the next
+    // one does, and the last row that starts at or before a position below `total` has some).
+    for (int i0 = 0; i0 < total; i0 += 4 * kThreads) {
       unsigned long long k[4];
-#pragma unroll
-      for (int u = 0; u < 4; ++u)
-        k[u] = (j0 + u < F && tid < s_cnt[j0 + u]) ? rows[static_cast<size_t>(j0 + u) * kLiteralRowCap + tid] : 0ull;
+      int jj[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        if (j0 + u < F && tid < s_cnt[j0 + u]) {
-          s_pool[s_off[j0 + u] + tid] = k[u];
-          s_pool_j[s_off[j0 + u] + tid] = static_cast<unsigned char>(j0 + u);
+        const int i = i0 + u * kThreads + tid;
+        k[u] = 0ull;
+        jj[u] = 0;
+        if (i < total) {
+          int lo_j = 0, hi_j = F - 1;
+          while (lo_j < hi_j) {
+            const int mid = (lo_j + hi_j + 1) >> 1;
+            if (s_off[mid] <= i) lo_j = mid; else hi_j = mid - 1;
+          }
+          jj[u] = lo_j;
+          k[u] = rows[static_cast<size_t>(lo_j) * kLiteralRowCap + (i - s_off[lo_j])];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int i = i0 + u * kThreads + tid;
+        if (i < total) {
+          s_pool[i] = k[u];
+          s_pool_j[i] = static_cast<unsigned char>(jj[u]);
         }
       }
     }
@@ -605,7 +622,15 @@ __global__ __launch_bounds__(kThreads) void literal_select_kernel(LiteralArgs a)
         if (tid < nf) {
           const unsigned long long mh = s_fin_hi[tid], ml = s_fin_lo[tid];
           int rank = 0;
-          for (int i = 0; i < nf; ++i) {
+          int i = 0;
+          for (; i + 8 <= nf; i += 8) {
+            unsigned long long oh[8], ol[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { oh[u] = s_fin_hi[i + u]; ol[u] = s_fin_lo[i + u]; }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) rank += (oh[u] > mh || (oh[u] == mh && ol[u] > ml)) ? 1 : 0;
+          }
+          for (; i < nf; ++i) {
             const unsigned long long oh = s_fin_hi[i], ol = s_fin_lo[i];
             rank += (oh > mh || (oh == mh && ol > ml)) ? 1 : 0;
           }
@@ -637,7 +662,16 @@ __global__ __launch_bounds__(kThreads) void literal_select_kernel(LiteralArgs a)
     const int myj = s_kj[tid];
     const unsigned long long myk = s_kkey[tid];
     int rank = 0;
-    for (int i = 0; i < n_keep; ++i) {
+    int i = 0;
+    for (; i + 8 <= n_keep; i += 8) {   // eight broadcast reads in flight: the loop is bound by LDS latency
+      int oj[8];
+      unsigned long long ok[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) { oj[u] = s_kj[i + u]; ok[u] = s_kkey[i + u]; }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) rank += (oj[u] < myj || (oj[u] == myj && ok[u] > myk)) ? 1 : 0;
+    }
+    for (; i < n_keep; ++i) {
       const int oj = s_kj[i];
       rank += (oj < myj || (oj == myj && s_kkey[i] > myk)) ? 1 : 0;
     }
