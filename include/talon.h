@@ -241,9 +241,14 @@ int talon_build_tree_checked(const int32_t* root_token, const void* logits, int 
  * arrays are written.
  * Trees of at most 64 nodes (N_pad = 64) take a shortcut where the workspace allows it: a row can
  * get at most N - 1 <= 63 children, so the capped loop with k = N - 1 cuts nothing and builds
- * the same tree in one launch (the launch talon_expand_tree makes).  With `layers` > 1 that
- * launch's workgroups wait for each other between layers and can give up as described at
- * talon_build_tree (TALON_STATUS_ABORTED on every sequence); calls with `layers` = 1 never wait.
+ * the same tree in one launch (the launch talon_expand_tree makes).  When N - 1 > 32 that loop
+ * first runs with k = 32, which is much cheaper to rank, and its selections record whether any
+ * of them kept the 32nd candidate of a row; if none did, no row was cut short and the tree
+ * stands.  Otherwise a second launch (enqueued with the first, left at once by every workgroup
+ * when it is not needed) rebuilds the layers of this call from the state the call started
+ * from, with k = N - 1.  With `layers` > 1 these launches' workgroups wait for each other
+ * between layers and can give up as described at talon_build_tree (TALON_STATUS_ABORTED on
+ * every sequence); calls with `layers` = 1 never wait.
  *   `workspace`: talon_literal_workspace_bytes bytes of device memory, no initialisation
  *   needed; it must not be shared with a call running at the same time.
  *   Errors: as talon_expand_layer and talon_select_budget (k does not apply).

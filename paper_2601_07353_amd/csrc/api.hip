@@ -75,7 +75,7 @@ int expand_layout(int B, int N_pad, int vocab, int k, int dtype, ExpandLayout* L
   L->off_seq_ticket = align_up(rows * sizeof(int32_t), 256);
   L->off_desc = L->off_seq_ticket + align_up(static_cast<size_t>(B) * sizeof(int32_t), 256);
   L->off_exit = L->off_desc + align_up(static_cast<size_t>(N_pad) * B * sizeof(uint64_t), 256);
-  L->off_max = L->off_exit + align_up(static_cast<size_t>(kExitWords) * sizeof(uint32_t), 256);
+  L->off_max = L->off_exit + align_up(static_cast<size_t>(kExitWords + 1) * sizeof(uint32_t), 256);   // + the cap_hit word
   L->off_sum = L->off_max + align_up(rows * chunks * sizeof(float), 256);
   L->off_keys = L->off_sum + align_up(rows * chunks * sizeof(double), 256);
   L->total = L->off_keys + align_up(rows * chunks * k * sizeof(uint64_t), 256);
@@ -151,6 +151,7 @@ ExpandArgs make_expand_args(const void* logits, int64_t row_stride, int64_t seq_
   a.layers = 0;
   a.spin_ticks = 0;
   a.tree_mask = nullptr;
+  a.run_if = nullptr;
   memset(&a.sel, 0, sizeof(a.sel));
   a.part_max = reinterpret_cast<float*>(w + L.off_max);
   a.part_sum = reinterpret_cast<double*>(w + L.off_sum);
@@ -216,9 +217,12 @@ struct LiteralLayout {
   // cap of N - 1 is no cap at all and the capped single-launch loop builds the uncapped tree.
   // Its workspace and candidate arrays (for k = 63) lie over the same bytes as the layout above.
   bool capped_loop_fits;
-  size_t c_workspace, c_token, c_logit, c_prob, c_edge, c_max, c_lse;
+  size_t c_workspace, c_token, c_logit, c_prob, c_edge, c_max, c_lse, c_saved;
 };
 constexpr int kCappedLoopK = 63;
+// The loop is first tried with this per-row cap, which is far cheaper to rank than N - 1: the tree
+// is the uncapped one unless a selection kept the last candidate of a row (SelectArgs::cap_hit).
+constexpr int kCappedLoopTryK = 32;
 
 int literal_layout(int B, int N_pad, int vocab, int dtype, LiteralLayout* V) {
   int rc = expand_layout(B, N_pad, vocab, 1, dtype, &V->scan);
@@ -254,6 +258,7 @@ int literal_layout(int B, int N_pad, int vocab, int dtype, LiteralLayout* V) {
     V->c_edge = c;  c += align_up(cc * sizeof(double), 256);
     V->c_max = c;   c += align_up(rows * sizeof(float), 256);
     V->c_lse = c;   c += align_up(rows * sizeof(double), 256);
+    V->c_saved = c; c += align_up(static_cast<size_t>(5) * B * sizeof(int32_t), 256);
     V->total = c > V->total ? c : V->total;
   }
   return TALON_OK;
@@ -339,6 +344,7 @@ int talon_select_budget(const talon_tree_state* st, int32_t k, const int32_t* ca
   SelectArgs a;
   a.st = *st; a.k = k; a.cand_token = cand_token; a.cand_prob = cand_prob; a.cand_edge_logp = cand_edge_logp;
   a.log_mu = log(static_cast<double>(mu)); a.K_init = K_init; a.init_layers = init_layers; a.max_depth = max_depth;
+  a.cap_hit = nullptr;
   return check_hip(launch_select(a, static_cast<hipStream_t>(stream)), "select launch");
 }
 
@@ -383,11 +389,20 @@ unsigned long long spin_limit_ticks() {
   return static_cast<unsigned long long>(us < 0 ? 0 : us) * 100ull;
 }
 
+// A single launch that is one of a pair (talon_expand_literal): the first runs with a small
+// per-row cap, saves the per-sequence state it starts from and raises a flag if the cap may have
+// mattered; the second runs with the full cap from the saved state, and only if the flag is up.
+struct Speculation {
+  uint32_t* cap_hit;        // first launch: raised by its selections
+  const uint32_t* run_if;   // second launch: the same word
+  int32_t* saved;           // [5][B]
+};
+
 int run_fused_layers(bool single_launch, const int32_t* root_token, uint64_t* mask, const void* logits, int dtype, int64_t row_stride, int64_t seq_stride, int row_mode,
                      int first_layer, int layers, const talon_tree_state* st, int32_t vocab, int32_t k, float mu,
                      int32_t K_init, int32_t init_layers, int32_t max_depth, int32_t* cand_token, float* cand_logit,
                      float* cand_prob, double* cand_edge_logp, float* row_max, double* row_lse, void* workspace,
-                     size_t workspace_bytes, void* stream) {
+                     size_t workspace_bytes, void* stream, const Speculation* spec = nullptr) {
   ExpandLayout L;
   int rc = check_expand_args(logits, dtype, row_stride, seq_stride, row_mode, st, vocab, k, cand_token, cand_logit,
                              cand_prob, cand_edge_logp, row_max, row_lse, workspace, workspace_bytes, &L);
@@ -399,6 +414,7 @@ int run_fused_layers(bool single_launch, const int32_t* root_token, uint64_t* ma
   SelectArgs sa;
   sa.st = *st; sa.k = k; sa.cand_token = cand_token; sa.cand_prob = cand_prob; sa.cand_edge_logp = cand_edge_logp;
   sa.log_mu = log(static_cast<double>(mu)); sa.K_init = K_init; sa.init_layers = init_layers; sa.max_depth = max_depth;
+  sa.cap_hit = spec ? spec->cap_hit : nullptr;
   ea.sel = sa;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (layers <= 0) {   // N = 1: the tree is its root
@@ -423,8 +439,17 @@ int run_fused_layers(bool single_launch, const int32_t* root_token, uint64_t* ma
   // trees, its first frontier comes from a snapshot of the public tree state made by a small
   // launch of its own (layer i of the loop reads descriptor i).
   const bool starts_trees = root_token != nullptr;   // talon_build_tree only: first layer 0
-  if (starts_trees) ea.root_token = root_token;
-  else if ((rc = check_hip(launch_fused_init(*st, ea, s), "fused init launch"))) return rc;
+  if (starts_trees) {
+    ea.root_token = root_token;
+  } else {
+    FusedInitArgs fi;
+    fi.mode = !spec ? kInitPlain : (spec->run_if ? kInitRestoreIf : kInitSave);
+    fi.saved = spec ? spec->saved : nullptr;
+    fi.flag = spec ? spec->run_if : nullptr;
+    fi.clear = spec && !spec->run_if ? ea.exit_ticket : nullptr;
+    if ((rc = check_hip(launch_fused_init(*st, ea, fi, s), "fused init launch"))) return rc;
+  }
+  ea.run_if = spec ? spec->run_if : nullptr;
   // One launch walks all layers.  Its grid is the widest layer's, capped by what the device
   // holds at once (the kernel's workgroups wait for each other between layers).
   int grid = 1;
@@ -565,20 +590,39 @@ int talon_expand_literal(const void* logits, int dtype, int64_t row_stride, int6
     // no row is ever cut short, so the capped loop in its single launch builds the same tree
     // (Alg. 2 with the pool as printed; a row's children enter in rank order, so a child
     // beyond rank N - 1 could only be chosen after N - 1 siblings, which the budget forbids).
-    // The same argument bounds K_init.  The launch wants its counters zero.
+    // The same argument bounds K_init.
     const int k = st->N - 1 < vocab ? st->N - 1 : vocab;
     const int most_layers = layers < st->N - 1 ? layers : st->N - 1;
     ExpandLayout C;
     rc = expand_layout(st->B, st->N_pad, vocab, k, dtype, &C);
     if (rc) return rc;
-    hipStream_t cs = static_cast<hipStream_t>(stream);
-    rc = check_hip(launch_fill_zero(w, C.off_max, cs), "counter fill launch");
-    if (rc) return rc;
-    return run_fused_layers(true, nullptr, nullptr, logits, dtype, row_stride, seq_stride, row_mode, 0, most_layers, st, vocab, k,
-                            mu, K_init < k ? K_init : k, init_layers, max_depth, reinterpret_cast<int32_t*>(w + V.c_token),
-                            reinterpret_cast<float*>(w + V.c_logit), reinterpret_cast<float*>(w + V.c_prob),
-                            reinterpret_cast<double*>(w + V.c_edge), reinterpret_cast<float*>(w + V.c_max),
-                            reinterpret_cast<double*>(w + V.c_lse), workspace, V.c_workspace, stream);
+    auto run = [&](int kk, const Speculation* spec) {
+      return run_fused_layers(true, nullptr, nullptr, logits, dtype, row_stride, seq_stride, row_mode, 0, most_layers, st, vocab, kk,
+                              mu, K_init < kk ? K_init : kk, init_layers, max_depth, reinterpret_cast<int32_t*>(w + V.c_token),
+                              reinterpret_cast<float*>(w + V.c_logit), reinterpret_cast<float*>(w + V.c_prob),
+                              reinterpret_cast<double*>(w + V.c_edge), reinterpret_cast<float*>(w + V.c_max),
+                              reinterpret_cast<double*>(w + V.c_lse), workspace, V.c_workspace, stream, spec);
+    };
+    // (the start of a single launch that continues trees zeroes row tickets, sequence tickets and
+    // descriptors; the other counters are zeroed here, or by the start of the first launch below)
+    if (k <= kCappedLoopTryK) {
+      rc = check_hip(launch_fill_zero(w + C.off_exit, C.off_max - C.off_exit, static_cast<hipStream_t>(stream)), "counter fill launch");
+      if (rc) return rc;
+      return run(k, nullptr);
+    }
+    // Ranking N - 1 candidates per row costs about twice what 32 cost, and trees whose rows get
+    // that many children are rare.  So the loop runs with a cap of 32 first, from a saved copy
+    // of the per-sequence state, and its selections say whether any of them kept the 32nd
+    // candidate of a row.  If none did, the cap never cut a row short and the tree is the one of
+    // the uncapped pool: a selection that wants more than 32 tokens of a row wants its 32 best
+    // too, the last of them included.  Otherwise a second launch, which every workgroup leaves
+    // at once when the flag is down, builds the trees again from the saved state with the full
+    // cap.  (The flag word lies behind the exit tickets; the first launch's start zeroes all of them.)
+    uint32_t* flag = reinterpret_cast<uint32_t*>(w + C.off_exit) + kCapHitWord;
+    Speculation first = {flag, nullptr, reinterpret_cast<int32_t*>(w + V.c_saved)};
+    Speculation second = {nullptr, flag, reinterpret_cast<int32_t*>(w + V.c_saved)};
+    if ((rc = run(kCappedLoopTryK, &first))) return rc;
+    return run(k, &second);
   }
   L = V.scan;   // offsets of the roomier layout; the scan strides its partial keys by k_scan
   const ExpandArgs ea = make_expand_args(logits, row_stride, seq_stride, row_mode, st, vocab, k_scan,

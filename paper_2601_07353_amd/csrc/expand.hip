@@ -857,6 +857,8 @@ __global__ __launch_bounds__(kThreads, MODE == kModeSplit ? 4 : 3) void expand_k
 template <int EPL>
 __global__ __launch_bounds__(kThreads, 3) void expand_tree_kernel(ExpandArgs a) {
   __shared__ int s_go;
+  // a launch that is only wanted when an earlier one of the same call has raised its flag
+  if (a.run_if && load_agent(a.run_if) == 0u) return;
   bool gave_up = false;
   // One pass more than there are layers: the pass after the last layer finds every sequence
   // finished (depth cap or budget), which is also the proof that every selection is
@@ -975,19 +977,35 @@ int expand_chunk_elems(int dtype) { return dtype == TALON_DTYPE_F32 ? kChunkByte
 // Start of a fused call that continues trees already begun: frontier descriptors of its first
 // layer from the public tree state, none for the later layers; zero tickets (nothing leaves
 // them taken, but a caller may hand over a workspace that other launch forms have used).
-__global__ void fused_init_kernel(talon_tree_state st, unsigned long long* desc, int32_t* ticket, int32_t* seq_ticket) {
+__global__ void fused_init_kernel(talon_tree_state st, unsigned long long* desc, int32_t* ticket, int32_t* seq_ticket,
+                                  FusedInitArgs f) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (f.mode == kInitRestoreIf && *f.flag == 0u) return;
+  if (f.mode == kInitSave && f.clear && i <= kExitWords) f.clear[i] = 0u;   // (the grid has at least 256 threads)
   if (i >= st.B * st.N_pad) return;
   ticket[i] = 0;
   if (i >= st.B) { desc[i] = 0ull; return; }
   seq_ticket[i] = 0;
+  if (f.mode == kInitSave) {
+    f.saved[i] = st.n_nodes[i];
+    f.saved[st.B + i] = st.frontier_begin[i];
+    f.saved[2 * st.B + i] = st.frontier_count[i];
+    f.saved[3 * st.B + i] = st.depth_cur[i];
+    f.saved[4 * st.B + i] = static_cast<int32_t>(st.status[i]);
+  } else if (f.mode == kInitRestoreIf) {
+    st.n_nodes[i] = f.saved[i];
+    st.frontier_begin[i] = f.saved[st.B + i];
+    st.frontier_count[i] = f.saved[2 * st.B + i];
+    st.depth_cur[i] = f.saved[3 * st.B + i];
+    st.status[i] = static_cast<uint32_t>(f.saved[4 * st.B + i]);
+  }
   const uint32_t count = (st.status[i] & kDoneMask) ? 0u : static_cast<uint32_t>(st.frontier_count[i]);
   desc[i] = kDescReady | (static_cast<unsigned long long>(count) << 32) | static_cast<uint32_t>(st.frontier_begin[i]);
 }
 
-hipError_t launch_fused_init(const talon_tree_state& st, const ExpandArgs& a, hipStream_t s) {
+hipError_t launch_fused_init(const talon_tree_state& st, const ExpandArgs& a, const FusedInitArgs& f, hipStream_t s) {
   const int n = st.B * st.N_pad;
-  hipLaunchKernelGGL(fused_init_kernel, dim3((n + 255) / 256), dim3(256), 0, s, st, a.desc, a.ticket, a.seq_ticket);
+  hipLaunchKernelGGL(fused_init_kernel, dim3((n + 255) / 256), dim3(256), 0, s, st, a.desc, a.ticket, a.seq_ticket, f);
   return hipGetLastError();
 }
 

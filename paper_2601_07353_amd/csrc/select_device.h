@@ -104,6 +104,7 @@ __device__ __forceinline__ unsigned long long select_sequence(const SelectArgs& 
       // candidates are valid up to the first invalid one (missing candidates sit at the end)
       const int n_valid = vb == ~0ull ? 64 : __builtin_ctzll(~vb);
       const int n_keep = n_valid < limit ? n_valid : limit;
+      if (a.cap_hit && tid == 0 && n_keep >= k) st_<true, uint32_t>(a.cap_hit, 1u);   // the row's last candidate is kept
       if (tid < n_keep) {
         const size_t o = base + n + tid;
         st.token[o] = tok;
@@ -291,6 +292,7 @@ __device__ __forceinline__ unsigned long long select_sequence(const SelectArgs& 
     if (key == T) { keep = eq_rank < need_eq; ++eq_rank; }
     if (key == 0ull) keep = false;
     if (keep) { keep_bits |= 1u << i; ++keep_local; }
+    if (keep && a.cap_hit && (c_begin + i) % k == k - 1) st_<true, uint32_t>(a.cap_hit, 1u);   // a row's last candidate
   }
   int n_keep;
   int pos = block_exclusive_scan_i32(keep_local, s_red_i32, &n_keep);

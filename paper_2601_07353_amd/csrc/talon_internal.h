@@ -27,6 +27,11 @@ struct SelectArgs {
   const double* cand_edge_logp;
   double log_mu;
   int K_init, init_layers, max_depth;
+  // Optional: set to 1 when a selection keeps the last (k-th) candidate of a row, i.e. when the
+  // per-row cap may have cut the pool of Alg. 2 short.  While it stays 0 the tree is the one the
+  // uncapped pool gives: a selection that wants more than k tokens of a row also wants the row's
+  // k best, all of which the capped pool holds.
+  uint32_t* cap_hit;
 };
 
 // Workgroups leave the single-launch kernel through a two-level ticket (one counter for all
@@ -39,6 +44,8 @@ constexpr int kExitGroups = 128;
 constexpr int kStartedWord = kExitGroups + 1;
 constexpr int kSelectedWord = kExitGroups + 2;
 constexpr int kExitWords = kExitGroups + 3;
+// One more word behind them, which no launch clears: the cap_hit flag of a speculative run.
+constexpr int kCapHitWord = kExitWords;
 constexpr unsigned long long kDescReady = 1ull << 63;
 
 struct ExpandArgs {
@@ -88,6 +95,19 @@ struct ExpandArgs {
   unsigned long long spin_ticks;
   uint64_t* tree_mask;   // optional: ancestor masks written at the end of the single launch
   const int32_t* root_token;   // optional [B]
+  const uint32_t* run_if;      // optional: the single launch does nothing unless this word is non-zero
+};
+
+// Start of a single launch that continues trees: what it does with the five per-sequence words
+// of the tree state (nodes, frontier begin and count, depth, status) besides reading them.
+constexpr int kInitPlain = 0;     // nothing
+constexpr int kInitSave = 1;      // copy them to `saved` [5][B] first
+constexpr int kInitRestoreIf = 2; // if *flag is non-zero: put them back from `saved`, then start; else do nothing
+struct FusedInitArgs {
+  int mode;
+  int32_t* saved;
+  const uint32_t* flag;
+  uint32_t* clear;   // optional: kExitWords + 1 words (exit tickets, layer counters, cap_hit) set to zero with kInitSave
 };
 
 // Uncapped ("paper-literal") layer of Alg. 2: the pool of a parent is its whole row.
@@ -154,7 +174,7 @@ hipError_t launch_read_probe(const void* buf, size_t bytes, void* sink, hipStrea
 hipError_t launch_mfma_probe(int workgroups, int iters, void* sink, hipStream_t s);
 hipError_t launch_issue_probe(int mode, int waves, int iters, void* cycles, void* sink, hipStream_t s);
 hipError_t launch_tile_load_probe(int loads, bool with_mfma, int waves, int iters, const void* window, void* cycles, void* sink, hipStream_t s);
-hipError_t launch_fused_init(const talon_tree_state& st, const ExpandArgs& a, hipStream_t s);
+hipError_t launch_fused_init(const talon_tree_state& st, const ExpandArgs& a, const FusedInitArgs& f, hipStream_t s);
 hipError_t launch_expand_tree(const ExpandArgs& a, int dtype, int grid, hipStream_t s);
 int expand_tree_max_grid(int dtype);
 hipError_t launch_expand(const ExpandArgs& a, int dtype, int grid, bool fused, hipStream_t s);

@@ -65,6 +65,26 @@ def test_one_layer_per_call_and_two_top_k_layers():
     _case(CASES["tiny-f32"], init_layers=0, layer_by_layer=True)
 
 
+@pytest.mark.parametrize("layer_by_layer", [False, True])
+def test_small_trees_whose_rows_get_more_than_32_children(layer_by_layer):
+    """Trees of at most 64 nodes are first built with a per-row cap of 32 and, when a selection
+    kept the 32nd candidate of a row, again from the saved state with the cap N - 1.  Three
+    sequences in one call: peaked rows (largest fan-out 5), flat rows where one parent gets 31
+    children (the last count the first build may keep) and flat rows where one gets 36 (the
+    second build, which then redoes all three).  With one call per layer the wide layer is the
+    second call, so the state the second build goes back to is not the root's."""
+    cfg = dataclasses.replace(CONFIGS["c1"], name="literal-wide-n60", B=3, V=4099, N=60, Dmax=8, K=2, mu=0.1,
+                              recipe=(("gauss", 6.0, 8.0), ("gauss", 0.3, 0.5), ("gauss", 2.0, 2.5)))
+    trees = _case(cfg, layer_by_layer=layer_by_layer)
+    fans = [int(np.bincount(np.asarray(t.parent[1:]), minlength=t.n).max()) for t in trees]
+    print("largest fan-out per sequence", fans, "nodes", [t.n for t in trees])
+    assert fans[0] < 31 and fans[1] == 31 and fans[2] > 32
+    # the same recipes one sequence at a time (other rows: fan-outs 5, 45, 38): a call whose first build stands, two whose second runs
+    for b in range(3):
+        one = dataclasses.replace(cfg, name="literal-wide-n60-%d" % b, B=1, recipe=cfg.recipe[b], seed=cfg.seed + 100 * b)
+        _case(one, layer_by_layer=layer_by_layer)
+
+
 def test_capped_path_agrees_where_its_cap_suffices():
     """N = 60, k = 59: the fast path's tree is the uncapped tree, so both entry points must
     produce the same arrays, bit for bit (probabilities included: same arithmetic)."""
