@@ -212,7 +212,7 @@ constexpr int kLiteralScanK = 16;
 struct LiteralLayout {
   ExpandLayout scan;
   int k_max;   // candidates per row the layout has room for: kLiteralScanK, or 1 for very wide rows
-  size_t off_token, off_logit, off_prob, off_edge, off_max, off_lse, off_count, off_keys, total;
+  size_t off_token, off_logit, off_prob, off_edge, off_max, off_lse, off_count, off_keys, off_part_count, off_part_keys, part_keys_per_seq, total;
   // Trees of at most 64 nodes: a row can never get more than N - 1 <= 63 children, so a per-row
   // cap of N - 1 is no cap at all and the capped single-launch loop builds the uncapped tree.
   // Its workspace and candidate arrays (for k = 63) lie over the same bytes as the layout above.
@@ -244,6 +244,10 @@ int literal_layout(int B, int N_pad, int vocab, int dtype, LiteralLayout* V) {
   V->off_lse = o;   o += align_up(rows * sizeof(double), 256);
   V->off_count = o; o += align_up(rows * sizeof(int32_t), 256);
   V->off_keys = o;  o += align_up(rows * kLiteralRowCap * sizeof(uint64_t), 256);
+  V->off_part_count = o; o += align_up(rows * kLiteralChunks * sizeof(int32_t), 256);
+  // parts of rows: a layer's rows times the nodes it may take never exceed (N / 2)^2
+  V->part_keys_per_seq = static_cast<size_t>(kLiteralChunks) * (N_pad / 2) * (N_pad / 2);
+  V->off_part_keys = o;  o += align_up(static_cast<size_t>(B) * V->part_keys_per_seq * sizeof(uint64_t), 256);
   V->total = o;
   V->capped_loop_fits = false;
   ExpandLayout C;
@@ -640,6 +644,10 @@ int talon_expand_literal(const void* logits, int dtype, int64_t row_stride, int6
   la.row_lse = reinterpret_cast<const double*>(w + V.off_lse);
   la.row_count = reinterpret_cast<int32_t*>(w + V.off_count);
   la.row_key = reinterpret_cast<unsigned long long*>(w + V.off_keys);
+  la.part_key = reinterpret_cast<unsigned long long*>(w + V.off_part_keys);
+  la.part_keys_per_seq = V.part_keys_per_seq;
+  la.part_count = reinterpret_cast<int32_t*>(w + V.off_part_count);
+  la.row_ticket = ea.ticket;        // the scan's row tickets: zero whenever the scan is not running
   hipStream_t s = static_cast<hipStream_t>(stream);
   // the scan's row tickets start at zero and every launch leaves them so
   rc = check_hip(launch_fill_zero(w + L.off_ticket, L.off_max - L.off_ticket, s), "ticket fill launch");

@@ -111,6 +111,10 @@ struct FusedInitArgs {
 };
 
 // Uncapped ("paper-literal") layer of Alg. 2: the pool of a parent is its whole row.
+#ifndef TALON_LITERAL_CHUNKS
+#define TALON_LITERAL_CHUNKS 8
+#endif
+constexpr int kLiteralChunks = TALON_LITERAL_CHUNKS;     // parts a row is streamed in at most (their survivors, 8 * 255 keys, are merged in LDS)
 constexpr int kLiteralRowCap = 256;   // survivors of one row that can still be chosen: at most N - 1 <= 255
 struct LiteralPlan {   // what a layer does for one sequence
   double thr;          // gate threshold on the path score, log(mu) + anchor (-inf on top-K layers)
@@ -131,6 +135,14 @@ struct LiteralArgs {
   const double* row_lse;           // [B*N_pad]
   int32_t* row_count;              // [B*N_pad] survivors kept of a row
   unsigned long long* row_key;     // [B*N_pad][kLiteralRowCap] their keys (sortable logit << 32 | ~token)
+  // A row of a sequence with few rows is streamed in up to kLiteralChunks parts by as many
+  // workgroups: part c of frontier row j of a layer that takes at most `limit` nodes leaves its
+  // survivors at part_key[b * part_keys_per_seq + (j * parts + c) * limit] (rows * limit never
+  // exceeds (N / 2)^2) and their number in part_count.
+  unsigned long long* part_key;
+  size_t part_keys_per_seq;
+  int32_t* part_count;             // [B*N_pad][kLiteralChunks]
+  int32_t* row_ticket;             // [B*N_pad] parts of a row that have finished; zero between launches
 };
 
 struct AttnArgs {
