@@ -12,7 +12,7 @@
 //            candidate is its largest logit), gate threshold log(mu) + m_d  (Eq. 4), limit)
 //   collect  per frontier row: the tokens that pass the gate, at most `limit` of them, the
 //            best by (logit descending, token ascending) -- a radix select over the row when
-//            more pass
+//            more pass; rows of a narrow layer are streamed in parts by several workgroups
 //   select   per sequence: the `limit` best of what the rows kept, by (path score descending,
 //            parent ascending, in-row rank ascending), appended in (parent, rank) order
 // Keys are unique ((logit, token) inside a row, (score, parent, token) inside a layer), so
