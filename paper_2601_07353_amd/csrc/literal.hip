@@ -871,17 +871,18 @@ __global__ __launch_bounds__(kCollectThreads) void literal_collect_kernel(Litera
 }
 
 // One workgroup per sequence: the budget check over what the rows kept.
-__global__ __launch_bounds__(kThreads) void literal_select_kernel(LiteralArgs a) {
+template <int NT>
+__global__ __launch_bounds__(NT) void literal_select_kernel(LiteralArgs a) {
   __shared__ SelectLds2 s_s;
   __shared__ CommonLds s_cm;
   const int b = blockIdx.x;
-  const LiteralPlan p = make_plan<kThreads>(a, b, s_cm.red_u64, &s_cm.plan);
+  const LiteralPlan p = make_plan<NT>(a, b, s_cm.red_u64, &s_cm.plan);
   if (!p.active) {
     // a row of this layer could not be normalised: the sequence stops here
     if (threadIdx.x == 0 && (p.status & TALON_STATUS_BAD_ROW) && !(p.status & kDoneMask) && p.F > 0) a.st.frontier_count[b] = 0;
     return;
   }
-  literal_select<kThreads>(a, b, p, s_s, s_cm);
+  literal_select<NT>(a, b, p, s_s, s_cm);
 }
 
 }  // namespace
@@ -896,7 +897,8 @@ hipError_t launch_literal_layer(const LiteralArgs& a, int dtype, hipStream_t s) 
   const dim3 grid(per_seq < most ? per_seq : most, a.st.B);
   if (dtype == TALON_DTYPE_F32) hipLaunchKernelGGL(literal_collect_kernel<4>, grid, dim3(kCollectThreads), 0, s, a);
   else hipLaunchKernelGGL(literal_collect_kernel<8>, grid, dim3(kCollectThreads), 0, s, a);
-  hipLaunchKernelGGL(literal_select_kernel, dim3(a.st.B), dim3(kThreads), 0, s, a);
+  // (four wavefronts: on 8 or 16 the barriers between the passes cost more than the shorter loops save)
+  hipLaunchKernelGGL(literal_select_kernel<kThreads>, dim3(a.st.B), dim3(kThreads), 0, s, a);
   return hipGetLastError();
 }
 
