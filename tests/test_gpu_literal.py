@@ -85,6 +85,23 @@ def test_small_trees_whose_rows_get_more_than_32_children(layer_by_layer):
         _case(one, layer_by_layer=layer_by_layer)
 
 
+@pytest.mark.parametrize("dtype,V", [("f32", 40001), ("bf16", 70001)])
+def test_rows_streamed_in_parts(dtype, V):
+    """A layer of a few rows leaves compute units idle, and its rows are streamed in parts by
+    several workgroups (four here: two rows per sequence, at least 2048 vectors per part).
+    Second layer of the three sequences: rows of which every token passes the gate (every part
+    cuts to the limit of 197, the merge selects among 4 x 197 survivors); rows of which 320-380
+    pass (f32: no part overflows, the merge selects) or about 60 (bf16: the merge copies); rows
+    that the scan's 16 best settle (nothing is streamed)."""
+    cfg = dataclasses.replace(CONFIGS["c1"], name="literal-parts", B=3, V=V, logits_dtype=dtype, N=200, Dmax=6, K=2, mu=0.05,
+                              recipe=(("gauss", 0.05, 0.1), ("gauss", 1.6, 1.9), ("gauss", 6.0, 8.0)))
+    trees = _case(cfg)
+    fans = [int(np.bincount(np.asarray(t.parent[1:]), minlength=t.n).max()) for t in trees]
+    print("largest fan-out per sequence", fans, "nodes", [t.n for t in trees])
+    assert fans[0] > 190 and fans[1] >= 64 and fans[2] < 16
+    _case(cfg, layer_by_layer=True)
+
+
 def test_capped_path_agrees_where_its_cap_suffices():
     """N = 60, k = 59: the fast path's tree is the uncapped tree, so both entry points must
     produce the same arrays, bit for bit (probabilities included: same arithmetic)."""
